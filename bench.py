@@ -1,0 +1,178 @@
+"""Benchmark of the label-looping greedy decoder on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic batch: encoder
+projection of all B*T frames, then the device-resident label-looping decode
+(predictor steps, predictor projections, fused joint + argmax, hypothesis
+updates) -- the paper's "non-encoder" time (Sec. 4).  Inputs and weights are
+resident in HBM before the timed region starts.
+
+Prints ONE JSON line: whole-job throughput in decoded encoder frames/s, the
+roofline figures of the dominant kernel (the persistent decode kernel), and the
+CPU oracle timed beside it on the host cores of the same box.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(cfg, stats) -> float:
+    """Bytes the method has to move for the passes the decode kernel executed:
+    per predictor pass the LSTM matrices and the predictor projection, per joint
+    pass the output matrix, plus one gathered enc_proj row (float32) per scored
+    (hypothesis, frame) row and the predictor rows' state."""
+    wb = 2 if cfg.dtype == "bf16" else 4
+    H, Hp, E, O = cfg.h_joint, cfg.h_pred, cfg.emb_dim, cfg.n_out
+    pred = H * Hp * wb
+    if cfg.pred_kind == "lstm":
+        in_dim = E
+        for _ in range(cfg.pred_layers):
+            pred += 4 * Hp * (in_dim + Hp) * wb
+            in_dim = Hp
+    joint = O * H * wb
+    return (stats["pred_passes"] * pred + stats["joint_passes"] * joint
+            + stats["joint_rows"] * H * 4 + stats["pred_rows"] * Hp * 4)
+
+
+def time_workload(cfg, steps, warmup, window=0, n_clusters=0):
+    import torch
+    from paper_2406_06220_amd import binding, synth
+    dev = "cuda:0"
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    u_cap = cfg.T * cfg.max_symbols
+    model = binding.DeviceModel(cfg, w, dev)
+    dec = binding.Decoder(model, cfg.B, cfg.T, u_cap, window=window, n_clusters=n_clusters)
+    enc_d = model.upload_enc(enc)
+    len_d = torch.from_numpy(ln).to(dev)
+    stream = torch.cuda.current_stream(dev)
+    for _ in range(max(warmup, 1)):
+        dec(enc_d, len_d, stream=stream)
+    out = dec.results()
+    assert out["stats"]["abort"] == 0, "device-side wait timed out"
+    # ---- whole hot path, K steps
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        dec(enc_d, len_d, stream=stream)
+    torch.cuda.synchronize(dev)
+    dt = (time.perf_counter() - t0) / steps
+    # ---- the decode kernel on its own: HIP events on the launch stream around a call
+    #      that reuses the projection already in the workspace
+    dec.options.reuse_enc_proj = 1
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(steps)]
+    for a, b in ev:
+        a.record(stream)
+        dec(enc_d, len_d, stream=stream)
+        b.record(stream)
+    torch.cuda.synchronize(dev)
+    dec.options.reuse_enc_proj = 0
+    k_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    frames = int(np.clip(ln, 0, cfg.T).sum())
+    return dict(cfg=cfg, weights=w, enc=enc, len=ln, out=out, sec_per_step=dt, decode_kernel_ms=k_ms,
+                frames=frames, u_cap=u_cap)
+
+
+def cpu_baseline(res, budget_utts=None):
+    """The oracle as it stands, all host threads, on (a sample of) the same batch."""
+    from oracle import oracle
+    cfg = res["cfg"]
+    n = cfg.B if budget_utts is None else min(cfg.B, budget_utts)
+    om = oracle.OracleModel(cfg, res["weights"])
+    t0 = time.perf_counter()
+    r = oracle.decode_batch(om, res["enc"][:n], res["len"][:n], cfg.max_symbols, res["u_cap"])
+    dt = time.perf_counter() - t0
+    frames = int(res["len"][:n].sum())
+    # while we are here: the GPU result must be the oracle's
+    same = all((res["out"]["len"][b] == r["len"][b]
+                and (res["out"]["labels"][b, :r["len"][b]] == r["labels"][b, :r["len"][b]]).all())
+               for b in range(n))
+    return dict(value=frames / dt, unit="frames/s", cores=int(r["threads"]), kind="oracle",
+                sample=f"first {n} of {cfg.B} utterances of the same batch, one run, "
+                       f"{dt:.1f} s wall", labels_match_gpu=bool(same))
+
+
+def traffic_from_profiles(name):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(path):
+        with open(path) as f:
+            return json.load(f).get(name)
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2_rnnt_lstm")
+    ap.add_argument("--window", type=int, default=0)
+    ap.add_argument("--clusters", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-extra", action="store_true", help="skip the B=128 line")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU (the batch would shard across GPUs without "
+              "any exchange, see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2406_06220_amd import binding, synth
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    binding.load_library()
+
+    cfg = synth.CONFIGS[args.workload]
+    res = time_workload(cfg, args.steps, args.warmup, args.window, args.clusters)
+    st = res["out"]["stats"]
+    alg = algorithmic_bytes(cfg, st)
+    k_s = res["decode_kernel_ms"] * 1e-3
+    achieved = alg / k_s / 1e9
+    line = {
+        "metric": "decoded encoder frames/sec (greedy decode only)",
+        "value": res["frames"] / res["sec_per_step"],
+        "unit": "frames/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["sec_per_step"] * 1e3,
+        "us_per_batch": res["sec_per_step"] * 1e6,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} T={cfg.T} d_enc={cfg.d_enc} "
+                               f"{cfg.pred_kind}x{cfg.pred_layers} h_pred={cfg.h_pred} H={cfg.h_joint} "
+                               f"V={cfg.vocab} D={cfg.n_dur} S={cfg.max_symbols}, "
+                               f"{cfg.dtype} weights, fp32 accumulation",
+                   "frames_per_batch": res["frames"],
+                   "labels_per_batch": int(res["out"]["len"].sum()),
+                   "window": args.window, "clusters": args.clusters},
+        "decode_stats": st,
+        "roofline": {"bound": "hbm", "kernel": "decode_kernel",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "algorithmic_bytes_per_launch": alg,
+                     "kernel_ms": res["decode_kernel_ms"],
+                     "traffic": traffic_from_profiles(cfg.name)},
+    }
+    if not args.no_extra and args.workload == "cfg2_rnnt_lstm":
+        cfg_b = synth.CONFIGS["cfg2_rnnt_lstm_b128"]
+        rb = time_workload(cfg_b, max(args.steps // 2, 3), max(args.warmup, 1), args.window, args.clusters)
+        line["b128"] = {"workload": cfg_b.name, "value": rb["frames"] / rb["sec_per_step"],
+                        "unit": "frames/s", "us_per_batch": rb["sec_per_step"] * 1e6,
+                        "frames_per_batch": rb["frames"], "decode_stats": rb["out"]["stats"]}
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(res)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

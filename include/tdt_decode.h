@@ -1,0 +1,191 @@
+/*
+ * tdt_decode.h -- C ABI of the label-looping greedy decoder for Transducer and
+ * Token-and-Duration Transducer (TDT) models on one AMD MI355X (gfx950).
+ *
+ * The library implements the paper's Algorithm 3 ("Label-looping Algorithm",
+ * Sec. 3.2), its TDT variant (Sec. 3.3) and the precomputed encoder / predictor
+ * projections (Sec. 3.4) as hand-written HIP kernels.  The label loop and the
+ * frame loop are controlled on the device; a call enqueues work on the caller's
+ * stream and returns without synchronising.
+ *
+ * Conventions
+ *   - every pointer marked DEVICE is device memory owned by the caller; the
+ *     library allocates nothing, keeps no state between calls, reads inputs and
+ *     weights, and writes only outputs and the workspace;
+ *   - every matrix is [out_features][in_features], row-major;
+ *   - dtype 0: enc, embeddings and weight matrices are float32;
+ *     dtype 1: they are bfloat16 (raw 16-bit patterns); biases are float32 in
+ *     both cases, and every accumulation and intermediate value is float32;
+ *   - labels are 0..V-1, the blank symbol is V, and V is also the start-of-
+ *     sequence label fed to the predictor before the first emission;
+ *   - functions return 0 on success or a negative tdt_status code; on a negative
+ *     return nothing has been enqueued.
+ */
+#ifndef TDT_DECODE_H
+#define TDT_DECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TDT_MAX_LSTM_LAYERS 2
+#define TDT_MAX_CONTEXT 2
+#define TDT_MAX_DURATIONS 16
+/* widest vector a kernel stages per row: d_enc, h_joint, h_pred and
+   emb_dim + h_pred must not exceed it; all four dims must be multiples of 8 */
+#define TDT_MAX_DIM 2048
+
+enum tdt_status {
+    TDT_OK = 0,
+    TDT_ERR_NULL = -1,        /* a required pointer is NULL */
+    TDT_ERR_SHAPE = -2,       /* B, T, u_cap or max_symbols < 1, or a model dim out of range */
+    TDT_ERR_UNSUPPORTED = -3, /* dtype, predictor kind, layer count or option not supported */
+    TDT_ERR_DURATIONS = -4,   /* n_dur / durations mismatch, negative entry, or no positive entry */
+    TDT_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or smaller than tdt_workspace_bytes */
+    TDT_ERR_LAUNCH = -6       /* the HIP runtime refused a launch or a query */
+};
+
+enum tdt_pred_kind {
+    TDT_PRED_STATELESS = 0, /* dec = concatenated embeddings of the last `pred_layers` labels */
+    TDT_PRED_LSTM = 1       /* dec = top hidden state of a `pred_layers`-layer LSTM */
+};
+
+/* per-hypothesis bits written to out_status */
+#define TDT_HYP_TRUNCATED 1   /* stopped because it reached u_cap labels */
+#define TDT_HYP_LEN_CLAMPED 2 /* enc_len[b] was outside [0, T] and was clamped */
+
+/*
+ * Model description (Sec. 2 "Background": encoder output, prediction network,
+ * joiner; Sec. 3.4: the two projections into the joint space).
+ *
+ *   enc_proj[b,t] = w_enc * enc[b,t] + b_enc
+ *   dec           = predictor(state, last label)
+ *   pred_proj     = w_pred * dec + b_pred
+ *   logits        = w_out * relu(enc_proj + pred_proj) + b_out
+ *   logits[0..V]      label scores (index V = blank)
+ *   logits[V+1..V+D]  TDT duration-class scores (n_dur = D; 0 for a Transducer)
+ *
+ * LSTM gate order in w_ih / w_hh / b_lstm rows is i, f, g, o (four blocks of
+ * h_pred rows); one bias vector per layer.  Layer 0 reads the embedding
+ * (emb_dim), layer 1 reads layer 0's hidden state (h_pred).
+ * Stateless predictor: `pred_layers` is the context size c (1 or 2); emb holds c
+ * tables [c][V+1][emb_dim]; table c-1 embeds the newest label; h_pred must equal
+ * c * emb_dim.  All pointers DEVICE; unused entries may be NULL.
+ */
+typedef struct {
+    int32_t dtype;       /* 0 float32, 1 bfloat16 (see conventions) */
+    int32_t d_enc;       /* encoder output width */
+    int32_t h_joint;     /* joint hidden width H */
+    int32_t vocab;       /* V, number of real labels */
+    int32_t n_dur;       /* D, number of duration classes; 0 = plain Transducer */
+    int32_t pred_kind;   /* enum tdt_pred_kind */
+    int32_t pred_layers; /* LSTM layers (1..2) or stateless context size (1..2) */
+    int32_t h_pred;      /* predictor output width */
+    int32_t emb_dim;     /* embedding width (per table) */
+    const void *w_enc;   /* [h_joint][d_enc] */
+    const float *b_enc;  /* [h_joint] */
+    const void *emb;     /* LSTM: [V+1][emb_dim]; stateless: [c][V+1][emb_dim] */
+    const void *w_ih[TDT_MAX_LSTM_LAYERS];    /* [4*h_pred][emb_dim | h_pred] */
+    const void *w_hh[TDT_MAX_LSTM_LAYERS];    /* [4*h_pred][h_pred] */
+    const float *b_lstm[TDT_MAX_LSTM_LAYERS]; /* [4*h_pred] */
+    const void *w_pred;  /* [h_joint][h_pred] */
+    const float *b_pred; /* [h_joint] */
+    const void *w_out;   /* [V+1+D][h_joint] */
+    const float *b_out;  /* [V+1+D] */
+} tdt_weights_t;
+
+/*
+ * Tuning knobs; pass NULL for defaults.  None of them changes the result.
+ *   window      frames of one hypothesis scored per joint pass while it searches
+ *               for its next non-blank label (the inner loop of Algorithm 3
+ *               advances one frame per pass; since the predictor output is fixed
+ *               during that loop, several upcoming frames can be scored at once
+ *               and the first non-blank taken).  0 = automatic.
+ *   n_clusters  the batch is split into this many groups of hypotheses that are
+ *               decoded by disjoint sets of workgroups without waiting for each
+ *               other.  0 = automatic.
+ *   reuse_enc_proj  non-zero: the workspace still holds the encoder projection that
+ *               an earlier call with the same enc, B, T and weights left there, and
+ *               the projection step is skipped (decoding one encoder output again
+ *               with other settings; timing the decode kernel on its own).
+ */
+typedef struct {
+    int32_t window;
+    int32_t n_clusters;
+    int32_t reuse_enc_proj;
+    int32_t reserved[5]; /* must be zero */
+} tdt_options_t;
+
+/* counters written to out_stats (int64 each); sums over all hypothesis groups */
+enum tdt_stat {
+    TDT_STAT_PRED_PASSES = 0, /* batched predictor steps executed (Alg. 3 line 6) */
+    TDT_STAT_PRED_ROWS = 1,   /* hypothesis rows those steps updated */
+    TDT_STAT_JOINT_PASSES = 2, /* batched joint passes executed (Alg. 3 lines 7 and 13) */
+    TDT_STAT_JOINT_ROWS = 3,  /* (hypothesis, frame) rows those passes scored */
+    TDT_STAT_OUTER_MAX = 4,   /* largest number of label-loop iterations of any group */
+    TDT_STAT_ABORT = 5,       /* non-zero if an internal wait timed out (results invalid) */
+    TDT_STAT_COUNT = 8
+};
+
+/*
+ * Bytes of DEVICE workspace tdt_greedy_decode needs for this model and these
+ * sizes (projected encoder frames [B][T][h_joint] in float32 dominate).
+ * Host-only computation.  Returns TDT_OK or TDT_ERR_NULL / _SHAPE / _UNSUPPORTED.
+ */
+int tdt_workspace_bytes(const tdt_weights_t *weights, int B, int T, int u_cap, size_t *bytes);
+
+/*
+ * Batched greedy decoding (Algorithm 3; Sec. 3.3 for TDT; Sec. 3.1 for the
+ * batched hypothesis arrays the outputs mirror).
+ *
+ *   enc         DEVICE [B][T][d_enc], dtype per weights->dtype.  Frames at or
+ *               beyond enc_len[b] are never read.
+ *   enc_len     DEVICE [B] int32 valid frames per utterance; values outside
+ *               [0, T] are clamped and flagged in out_status.
+ *   durations   HOST [n_dur] frame increments of the duration classes
+ *               (e.g. {0,1,2,3,4}); NULL iff n_dur == 0.  A blank with increment 0
+ *               advances one frame.
+ *   max_symbols most labels a hypothesis may emit without its frame index moving;
+ *               on the max_symbols-th the frame index is advanced by one.
+ *   u_cap       label capacity per hypothesis; a hypothesis that reaches it stops
+ *               and is flagged TDT_HYP_TRUNCATED.  len*max_symbols always suffices.
+ *   out_labels  DEVICE [B][u_cap] int32 emitted labels      (first out_len[b] valid)
+ *   out_frames  DEVICE [B][u_cap] int32 frame each label was emitted at
+ *   out_len     DEVICE [B] int32
+ *   out_score   DEVICE [B] float, sum over emitted labels of
+ *               log_softmax(label logits)[label]
+ *   out_status  DEVICE [B] int32 TDT_HYP_* bits
+ *   out_stats   DEVICE [TDT_STAT_COUNT] int64, or NULL
+ *   workspace   DEVICE, 256-byte aligned, >= tdt_workspace_bytes(); contents are
+ *               scratch and may be reused by the caller after the stream drains
+ *   stream      hipStream_t (NULL = default stream)
+ *
+ * Calls that share a workspace must not overlap.  Returns TDT_OK once
+ * everything is enqueued; outputs are valid after the stream is synchronised.
+ */
+int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
+                      const tdt_weights_t *weights, const int32_t *durations, int max_symbols,
+                      int u_cap, int32_t *out_labels, int32_t *out_frames, int32_t *out_len,
+                      float *out_score, int32_t *out_status, int64_t *out_stats,
+                      void *workspace, size_t workspace_bytes, const tdt_options_t *options,
+                      void *stream);
+
+/*
+ * The encoder projection alone (Sec. 3.4, the precomputation at line 2 of
+ * Algorithm 3): out[r][:] = w_enc * enc[r][:] + b_enc for r < rows.
+ *   enc DEVICE [rows][d_enc] (dtype per weights), out DEVICE [rows][h_joint] float32.
+ * Exposed so that the dense contraction can be checked and timed on its own.
+ */
+int tdt_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *weights,
+                           float *out, void *stream);
+
+/* Static, human-readable name of a status code. */
+const char *tdt_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TDT_DECODE_H */

@@ -1,0 +1,184 @@
+// Encoder projection (paper Sec. 3.4; the precomputation at line 2 of Algorithm 3):
+//   out[r][n] = sum_k enc[r][k] * w_enc[n][k] + b_enc[n]
+// A dense contraction over all B*T frames, so it runs on the matrix cores:
+// bf16 operands, fp32 accumulation, fp32 output (v_mfma_f32_32x32x16_bf16).
+// Both operands are K-contiguous ("NT" GEMM), which is the layout the MFMA lane
+// mapping wants: lane l supplies row (l % 32), k-slice (l / 32) * 8 .. + 7.
+#include "tdt_internal.h"
+
+namespace tdt {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 64;   // workgroup tile
+constexpr int GEMM_THREADS = 256;            // 4 wavefronts, each a 64x64 sub-tile
+
+// 16-byte chunk index c of a row is stored at chunk (c ^ (row & 7)) so that the
+// 32 rows a wavefront reads for one k-slice spread over all LDS banks.
+__device__ inline int lds_off(int row, int chunk) { return row * BK + ((chunk ^ (row & 7)) << 3); }
+
+__global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
+    float *__restrict__ C, long long M, int N, int K)
+{
+    __shared__ __align__(16) uint16_t As[BM * BK];
+    __shared__ __align__(16) uint16_t Bs[BN * BK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    // 1-D grid, column tiles fastest: the workgroups that share a row tile of
+    // `A` are dispatched back to back
+    const int nt_n = (N + BN - 1) / BN;
+    const long long m0 = (long long)(blockIdx.x / nt_n) * BM;
+    const int n0 = (blockIdx.x % nt_n) * BN;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    uint4 ra[4], rb[4];
+    auto load_tiles = [&](int k0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = tid + j * GEMM_THREADS;   // 0..1023
+            const int row = c >> 3, kc = c & 7;
+            const int k = k0 + kc * 8;
+            const long long m = m0 + row;
+            const int n = n0 + row;
+            ra[j] = (m < M && k < K) ? *reinterpret_cast<const uint4 *>(A + m * K + k)
+                                     : make_uint4(0, 0, 0, 0);
+            rb[j] = (n < N && k < K) ? *reinterpret_cast<const uint4 *>(W + (long long)n * K + k)
+                                     : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_tiles = [&]() {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = tid + j * GEMM_THREADS;
+            const int row = c >> 3, kc = c & 7;
+            *reinterpret_cast<uint4 *>(As + lds_off(row, kc)) = ra[j];
+            *reinterpret_cast<uint4 *>(Bs + lds_off(row, kc)) = rb[j];
+        }
+    };
+
+    const int nk = (K + BK - 1) / BK;
+    load_tiles(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        store_tiles();
+        __syncthreads();
+        if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            const int chunk = s * 2 + (lane >> 5);
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int ar = wm * 64 + i * 32 + (lane & 31);
+                const int br = wn * 64 + i * 32 + (lane & 31);
+                a[i] = *reinterpret_cast<const bf16x8 *>(As + lds_off(ar, chunk));
+                b[i] = *reinterpret_cast<const bf16x8 *>(Bs + lds_off(br, chunk));
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+            if (n >= N) continue;
+            const float bn = bias[n];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const long long m = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                if (m < M) C[m * N + n] = acc[i][j][e] + bn;
+            }
+        }
+}
+
+// float32 models (small): classic 64x64 tile, 4x4 outputs per thread.
+__global__ __launch_bounds__(256) void enc_proj_f32_kernel(
+    const float *__restrict__ A, const float *__restrict__ W, const float *__restrict__ bias,
+    float *__restrict__ C, long long M, int N, int K)
+{
+    __shared__ float As[16][65];
+    __shared__ float Ws[16][65];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int nt_n = (N + 63) / 64;
+    const long long m0 = (long long)(blockIdx.x / nt_n) * 64;
+    const int n0 = (blockIdx.x % nt_n) * 64;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int idx = tid + j * 256;
+            const int row = idx >> 4, kk = idx & 15;
+            const int k = k0 + kk;
+            const long long m = m0 + row;
+            const int n = n0 + row;
+            As[kk][row] = (m < M && k < K) ? A[m * K + k] : 0.0f;
+            Ws[kk][row] = (n < N && k < K) ? W[(long long)n * K + k] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = Ws[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const long long m = m0 + ty * 4 + i;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n < N) C[m * N + n] = acc[i][j] + bias[n];
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,
+                                     float *out, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const int N = w->h_joint, K = w->d_enc;
+    if (w->dtype == 1) {
+        dim3 grid((unsigned)(((N + BN - 1) / BN) * ((rows + BM - 1) / BM)));
+        hipLaunchKernelGGL(enc_proj_bf16_kernel, grid, dim3(GEMM_THREADS), 0, stream,
+                           static_cast<const uint16_t *>(enc),
+                           static_cast<const uint16_t *>(w->w_enc), w->b_enc, out,
+                           (long long)rows, N, K);
+    } else {
+        dim3 grid((unsigned)(((N + 63) / 64) * ((rows + 63) / 64)));
+        hipLaunchKernelGGL(enc_proj_f32_kernel, grid, dim3(256), 0, stream,
+                           static_cast<const float *>(enc), static_cast<const float *>(w->w_enc),
+                           w->b_enc, out, (long long)rows, N, K);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace tdt

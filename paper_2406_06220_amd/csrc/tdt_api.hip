@@ -1,0 +1,233 @@
+// Host side of the C ABI: argument checks, workspace layout, launches.
+#include <string.h>
+
+#include "tdt_internal.h"
+
+namespace tdt {
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T)
+{
+    WorkspaceLayout L{};
+    size_t off = 0;
+    const size_t lstm_layers = w->pred_kind == TDT_PRED_LSTM ? (size_t)w->pred_layers : 0;
+    L.enc_proj = off;
+    off = align_up(off + (size_t)B * T * w->h_joint * sizeof(float), 256);
+    L.pred_proj = off;
+    off = align_up(off + (size_t)B * w->h_joint * sizeof(float), 256);
+    L.partials = off;
+    off = align_up(off + 2 * (size_t)kPartialEntries * sizeof(LsePartial), 256);
+    // everything from here on is cleared by the init kernel of every call
+    L.zero_begin = off;
+    // per-row argmax cells: a cluster never scores more than min(kMaxRowsPerPass,
+    // hyps * kMaxWindow) rows per pass, so (B + kMaxGrid) * kMaxWindow cells cover any split
+    L.row_entries = (size_t)kRowBufs * ((size_t)B + kMaxGrid) * kMaxWindow;
+    L.row_lab = off;
+    off = align_up(off + L.row_entries * sizeof(unsigned long long), 256);
+    L.row_dur = off;
+    off = align_up(off + L.row_entries * sizeof(unsigned long long), 256);
+    L.hbuf = off;
+    off = align_up(off + 2 * lstm_layers * B * w->h_pred * sizeof(float), 256);
+    L.cbuf = off;
+    off = align_up(off + lstm_layers * B * w->h_pred * sizeof(float), 256);
+    L.barrier = off;
+    off = align_up(off + 2 * (size_t)kMaxGrid * kBarrierStride * sizeof(unsigned), 256);
+    L.abort_flag = off;
+    off = align_up(off + 256, 256);
+    L.zero_end = off;
+    L.total = off;
+    return L;
+}
+
+static int check_model(const tdt_weights_t *w)
+{
+    if (!w) return TDT_ERR_NULL;
+    if (w->dtype != 0 && w->dtype != 1) return TDT_ERR_UNSUPPORTED;
+    if (w->pred_kind != TDT_PRED_STATELESS && w->pred_kind != TDT_PRED_LSTM) return TDT_ERR_UNSUPPORTED;
+    if (w->pred_layers < 1) return TDT_ERR_UNSUPPORTED;
+    if (w->pred_kind == TDT_PRED_LSTM && w->pred_layers > TDT_MAX_LSTM_LAYERS) return TDT_ERR_UNSUPPORTED;
+    if (w->pred_kind == TDT_PRED_STATELESS && w->pred_layers > TDT_MAX_CONTEXT) return TDT_ERR_UNSUPPORTED;
+    const int dims[4] = {w->d_enc, w->h_joint, w->h_pred, w->emb_dim};
+    for (int d : dims)
+        if (d < 8 || d > TDT_MAX_DIM || d % 8 != 0) return TDT_ERR_SHAPE;
+    if (w->vocab < 1 || w->vocab > (1 << 24)) return TDT_ERR_SHAPE;
+    if (w->n_dur < 0 || w->n_dur > TDT_MAX_DURATIONS) return TDT_ERR_SHAPE;
+    if (w->pred_kind == TDT_PRED_LSTM && w->emb_dim + w->h_pred > TDT_MAX_DIM) return TDT_ERR_SHAPE;
+    if (w->pred_kind == TDT_PRED_LSTM && w->pred_layers > 1 && 2 * w->h_pred > TDT_MAX_DIM)
+        return TDT_ERR_SHAPE;
+    if (w->pred_kind == TDT_PRED_STATELESS && w->h_pred != w->pred_layers * w->emb_dim)
+        return TDT_ERR_SHAPE;
+    return TDT_OK;
+}
+
+static int check_model_pointers(const tdt_weights_t *w, bool need_decoder)
+{
+    if (!w->w_enc || !w->b_enc) return TDT_ERR_NULL;
+    if (!need_decoder) return TDT_OK;
+    if (!w->emb || !w->w_pred || !w->b_pred || !w->w_out || !w->b_out) return TDT_ERR_NULL;
+    if (w->pred_kind == TDT_PRED_LSTM)
+        for (int l = 0; l < w->pred_layers; ++l)
+            if (!w->w_ih[l] || !w->w_hh[l] || !w->b_lstm[l]) return TDT_ERR_NULL;
+    return TDT_OK;
+}
+
+}  // namespace tdt
+
+using namespace tdt;
+
+extern "C" {
+
+int tdt_workspace_bytes(const tdt_weights_t *weights, int B, int T, int u_cap, size_t *bytes)
+{
+    if (!weights || !bytes) return TDT_ERR_NULL;
+    if (B < 1 || T < 1 || u_cap < 1) return TDT_ERR_SHAPE;
+    const int st = check_model(weights);
+    if (st != TDT_OK) return st;
+    *bytes = workspace_layout(weights, B, T).total;
+    return TDT_OK;
+}
+
+int tdt_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *weights, float *out,
+                           void *stream)
+{
+    if (!weights) return TDT_ERR_NULL;
+    const int st = check_model(weights);
+    if (st != TDT_OK) return st;
+    if (!enc || !out) return TDT_ERR_NULL;
+    if (check_model_pointers(weights, false) != TDT_OK) return TDT_ERR_NULL;
+    if (rows < 0 || rows > ((int64_t)1 << 31)) return TDT_ERR_SHAPE;
+    if (launch_encoder_projection(enc, rows, weights, out, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return TDT_ERR_LAUNCH;
+    return TDT_OK;
+}
+
+int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
+                      const tdt_weights_t *weights, const int32_t *durations, int max_symbols,
+                      int u_cap, int32_t *out_labels, int32_t *out_frames, int32_t *out_len,
+                      float *out_score, int32_t *out_status, int64_t *out_stats, void *workspace,
+                      size_t workspace_bytes, const tdt_options_t *options, void *stream)
+{
+    if (!weights) return TDT_ERR_NULL;
+    int st = check_model(weights);
+    if (st != TDT_OK) return st;
+    if (!enc || !enc_len || !out_labels || !out_frames || !out_len || !out_score || !out_status)
+        return TDT_ERR_NULL;
+    st = check_model_pointers(weights, true);
+    if (st != TDT_OK) return st;
+    if (B < 1 || T < 1 || u_cap < 1 || max_symbols < 1) return TDT_ERR_SHAPE;
+    if ((int64_t)B * T > ((int64_t)1 << 31) || (int64_t)B * u_cap > ((int64_t)1 << 40)) return TDT_ERR_SHAPE;
+    // durations (Sec. 3.3): one non-negative frame increment per class, at least one positive
+    if ((weights->n_dur == 0) != (durations == nullptr)) return TDT_ERR_DURATIONS;
+    bool any_pos = weights->n_dur == 0;
+    for (int j = 0; j < weights->n_dur; ++j) {
+        if (durations[j] < 0 || durations[j] > T + 1) return TDT_ERR_DURATIONS;
+        any_pos |= durations[j] > 0;
+    }
+    if (!any_pos) return TDT_ERR_DURATIONS;
+    int window = 0, n_clusters = 0;
+    bool reuse_enc_proj = false;
+    if (options) {
+        for (int r : options->reserved)
+            if (r != 0) return TDT_ERR_UNSUPPORTED;
+        window = options->window;
+        n_clusters = options->n_clusters;
+        reuse_enc_proj = options->reuse_enc_proj != 0;
+        if (window < 0 || window > kMaxWindow || n_clusters < 0) return TDT_ERR_UNSUPPORTED;
+    }
+    const WorkspaceLayout L = workspace_layout(weights, B, T);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < L.total)
+        return TDT_ERR_WORKSPACE;
+
+    size_t lds = 0;
+    const int max_grid = decode_max_grid(weights->dtype, &lds, weights);
+    if (max_grid < 1) return TDT_ERR_LAUNCH;
+    const int min_clusters = (B + kMaxHypsPerCluster - 1) / kMaxHypsPerCluster;
+    if (n_clusters == 0) n_clusters = min_clusters;
+    if (n_clusters < min_clusters || n_clusters > max_grid) return TDT_ERR_UNSUPPORTED;
+    const int grid = max_grid / n_clusters * n_clusters;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    float *enc_proj = reinterpret_cast<float *>(ws + L.enc_proj);
+
+    if (launch_init(ws + L.zero_begin, L.zero_end - L.zero_begin,
+                    reinterpret_cast<long long *>(out_stats), s) != hipSuccess)
+        return TDT_ERR_LAUNCH;
+    if (!reuse_enc_proj &&
+        launch_encoder_projection(enc, (int64_t)B * T, weights, enc_proj, s) != hipSuccess)
+        return TDT_ERR_LAUNCH;
+
+    DecodeParams p{};
+    p.B = B;
+    p.T = T;
+    p.d_enc = weights->d_enc;
+    p.H = weights->h_joint;
+    p.V = weights->vocab;
+    p.D = weights->n_dur;
+    p.O = weights->vocab + 1 + weights->n_dur;
+    p.pred_kind = weights->pred_kind;
+    p.pred_layers = weights->pred_layers;
+    p.h_pred = weights->h_pred;
+    p.emb_dim = weights->emb_dim;
+    p.max_symbols = max_symbols;
+    p.u_cap = u_cap;
+    p.window = window;
+    p.n_clusters = n_clusters;
+    p.hyps_per_cluster = (B + n_clusters - 1) / n_clusters;
+    for (int j = 0; j < TDT_MAX_DURATIONS; ++j) p.durations[j] = j < weights->n_dur ? durations[j] : 0;
+    p.emb = weights->emb;
+    for (int l = 0; l < TDT_MAX_LSTM_LAYERS; ++l) {
+        p.w_ih[l] = weights->w_ih[l];
+        p.w_hh[l] = weights->w_hh[l];
+        p.b_lstm[l] = weights->b_lstm[l];
+    }
+    p.w_pred = weights->w_pred;
+    p.b_pred = weights->b_pred;
+    p.w_out = weights->w_out;
+    p.b_out = weights->b_out;
+    p.enc_proj = enc_proj;
+    p.enc_len = enc_len;
+    p.out_labels = out_labels;
+    p.out_frames = out_frames;
+    p.out_len = out_len;
+    p.out_status = out_status;
+    p.out_score = out_score;
+    p.out_stats = reinterpret_cast<long long *>(out_stats);
+    p.hbuf = reinterpret_cast<float *>(ws + L.hbuf);
+    p.cbuf = reinterpret_cast<float *>(ws + L.cbuf);
+    p.pred_proj = reinterpret_cast<float *>(ws + L.pred_proj);
+    p.partials = reinterpret_cast<LsePartial *>(ws + L.partials);
+    p.row_lab = reinterpret_cast<unsigned long long *>(ws + L.row_lab);
+    p.row_dur = reinterpret_cast<unsigned long long *>(ws + L.row_dur);
+    p.rows_per_cluster = p.hyps_per_cluster * kMaxWindow < kMaxRowsPerPass
+                             ? p.hyps_per_cluster * kMaxWindow : kMaxRowsPerPass;
+    p.barrier = reinterpret_cast<unsigned *>(ws + L.barrier);
+    p.abort_flag = reinterpret_cast<int *>(ws + L.abort_flag);
+    {
+        // bound on a single device-side wait: 4 s of the wall clock the kernel reads
+        int dev = 0, khz = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
+            khz = 100000;
+        p.timeout_ticks = 4000LL * khz;
+    }
+    if (launch_decode(p, weights->dtype, grid, s) != hipSuccess) return TDT_ERR_LAUNCH;
+    return TDT_OK;
+}
+
+const char *tdt_status_string(int status)
+{
+    switch (status) {
+    case TDT_OK: return "ok";
+    case TDT_ERR_NULL: return "a required pointer is NULL";
+    case TDT_ERR_SHAPE: return "a size or model dimension is out of range";
+    case TDT_ERR_UNSUPPORTED: return "unsupported dtype, predictor or option";
+    case TDT_ERR_DURATIONS: return "bad duration list";
+    case TDT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case TDT_ERR_LAUNCH: return "HIP launch or query failed";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,83 @@
+// Internal declarations shared by the translation units of libtdt_decode.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "tdt_decode.h"
+
+namespace tdt {
+
+constexpr int kThreads = 512;                 // threads per workgroup of the decode kernel
+constexpr int kWaves = kThreads / 64;         // 64-wide wavefronts per workgroup
+constexpr int kMaxGrid = 256;                 // one workgroup per compute unit
+constexpr int kMaxHypsPerCluster = 256;       // hypotheses one group of workgroups decodes
+constexpr int kMaxRowsPerPass = 2048;         // (hypothesis, frame) rows of one joint pass
+constexpr int kMaxColGroups = 64;             // output-column slices of one joint pass
+constexpr int kMaxWindow = 64;                // frames of one hypothesis per joint pass
+constexpr int kPartialEntries = kMaxRowsPerPass * kMaxGrid;  // per partial buffer
+constexpr int kBarrierStride = 64;            // uint32 slots between two barrier counters
+constexpr int kBarrierGroup = 32;             // workgroups that share a first-level counter
+constexpr int kRowBufs = 3;                   // rotating per-row argmax buffers
+
+// Softmax-denominator share of one slice of label columns for one joint row.
+struct __align__(8) LsePartial {
+    float max_lab;   // largest label logit in the slice
+    float sumexp;    // sum of exp(logit - max_lab) over the slice (0 if it has no label column)
+};
+static_assert(sizeof(LsePartial) == 8, "LsePartial must be 8 bytes");
+
+struct DecodeParams {
+    // sizes
+    int B, T, d_enc, H, V, D, O;
+    int pred_kind, pred_layers, h_pred, emb_dim;
+    int max_symbols, u_cap;
+    int window;            // 0 = automatic
+    int n_clusters, hyps_per_cluster;
+    int durations[TDT_MAX_DURATIONS];
+    // weights
+    const void *emb;
+    const void *w_ih[TDT_MAX_LSTM_LAYERS], *w_hh[TDT_MAX_LSTM_LAYERS];
+    const float *b_lstm[TDT_MAX_LSTM_LAYERS];
+    const void *w_pred;
+    const float *b_pred;
+    const void *w_out;
+    const float *b_out;
+    // inputs
+    const float *enc_proj;   // [B][T][H]
+    const int32_t *enc_len;  // [B]
+    // outputs
+    int32_t *out_labels, *out_frames, *out_len, *out_status;
+    float *out_score;
+    long long *out_stats;    // may be null
+    // workspace
+    float *hbuf;             // [2][layers][B][h_pred]  ping-pong hidden state
+    float *cbuf;             // [layers][B][h_pred]
+    float *pred_proj;        // [B][H]
+    LsePartial *partials;    // [2][kPartialEntries]
+    unsigned long long *row_lab;  // [n_clusters][kRowBufs][rows_per_cluster] packed (logit, ~label)
+    unsigned long long *row_dur;  // same shape, packed (logit, ~duration class)
+    int rows_per_cluster;
+    unsigned *barrier;       // [2 * kMaxGrid][kBarrierStride]: root counters, then group counters
+    int *abort_flag;
+    long long timeout_ticks; // bound on one wait, in wall-clock ticks
+};
+
+struct WorkspaceLayout {
+    size_t enc_proj, hbuf, cbuf, pred_proj, partials, row_lab, row_dur, barrier, abort_flag, total;
+    size_t row_entries;            // uint64 entries in each of row_lab / row_dur
+    size_t zero_begin, zero_end;   // byte range the init kernel clears
+};
+
+WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T);
+
+// launches (each returns a hipError_t)
+hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,
+                                     float *out, hipStream_t stream);
+hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats,
+                       hipStream_t stream);
+hipError_t launch_decode(const DecodeParams &p, int dtype, int grid, hipStream_t stream);
+// largest grid the decode kernel can run with all workgroups resident, 0 on error
+int decode_max_grid(int dtype, size_t *lds_bytes_out, const tdt_weights_t *w);
+
+}  // namespace tdt

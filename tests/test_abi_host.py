@@ -1,0 +1,125 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function the header declares, and rejects bad arguments before any device
+work (so these calls are safe on a machine without a GPU)."""
+from __future__ import annotations
+
+import ctypes as C
+import glob
+import os
+import re
+
+import pytest
+
+from paper_2406_06220_amd import binding, build, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_library()
+    return binding.load_library()
+
+
+def declared_functions():
+    names = []
+    for h in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        src = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names += re.findall(r"^\s*(?:const\s+)?(?:int|char|void|size_t)\s*\*?\s*(tdt_\w+)\s*\(", src,
+                            flags=re.M)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(binding.EXPORTS) <= set(names) and len(names) >= 4
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/ but not exported"
+
+
+def _weights(cfg, fake_ptr=4096):
+    w = binding.tdt_weights_t()
+    w.dtype = 1 if cfg.dtype == "bf16" else 0
+    w.d_enc, w.h_joint, w.vocab, w.n_dur = cfg.d_enc, cfg.h_joint, cfg.vocab, cfg.n_dur
+    w.pred_kind = 1 if cfg.pred_kind == "lstm" else 0
+    w.pred_layers, w.h_pred, w.emb_dim = cfg.pred_layers, cfg.h_pred, cfg.emb_dim
+    for f in ("w_enc", "b_enc", "emb", "w_pred", "b_pred", "w_out", "b_out"):
+        setattr(w, f, fake_ptr)
+    for l in range(2):
+        w.w_ih[l] = w.w_hh[l] = w.b_lstm[l] = fake_ptr
+    return w
+
+
+def _decode(lib, w, *, enc=4096, enc_len=4096, B=2, T=10, durations=None, S=3, u_cap=30,
+            outs=4096, ws=4096, ws_bytes=1 << 40, options=None):
+    dur = None
+    if durations is not None:
+        dur = (C.c_int32 * len(durations))(*durations)
+    return lib.tdt_greedy_decode(enc, enc_len, B, T, C.byref(w), dur, S, u_cap, outs, outs, outs,
+                                 outs, outs, None, ws, ws_bytes,
+                                 C.byref(options) if options is not None else None, None)
+
+
+def test_status_strings(lib):
+    for code in range(0, -7, -1):
+        s = binding.tdt_status_string(code)
+        assert s and s != "unknown status"
+    assert binding.tdt_status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    cfg = synth.CFG2
+    w = _weights(cfg)
+    n = binding.tdt_workspace_bytes(w, cfg.B, cfg.T, 100)
+    assert n >= cfg.B * cfg.T * cfg.h_joint * 4          # holds the projected encoder frames
+    assert n < cfg.B * cfg.T * cfg.h_joint * 4 + (128 << 20)
+    assert binding.tdt_workspace_bytes(w, 2 * cfg.B, cfg.T, 100) > n
+    size = C.c_size_t()
+    assert lib.tdt_workspace_bytes(None, 1, 1, 1, C.byref(size)) == -1
+    assert lib.tdt_workspace_bytes(C.byref(w), 0, 1, 1, C.byref(size)) == -2
+    assert lib.tdt_workspace_bytes(C.byref(w), 1, 1, 1, None) == -1
+
+
+def test_rejects_bad_arguments_before_device_work(lib):
+    cfg = synth.CFG3
+    w = _weights(cfg)
+    dur = list(cfg.durations)
+    # null pointers
+    assert _decode(lib, w, enc=None, durations=dur) == -1
+    assert _decode(lib, w, enc_len=None, durations=dur) == -1
+    assert _decode(lib, w, outs=None, durations=dur) == -1
+    w2 = _weights(cfg); w2.w_out = None
+    assert _decode(lib, w2, durations=dur) == -1
+    w2 = _weights(cfg); w2.w_hh[0] = None
+    assert _decode(lib, w2, durations=dur) == -1
+    # sizes
+    for kw in (dict(B=0), dict(T=0), dict(u_cap=0), dict(S=0)):
+        assert _decode(lib, w, durations=dur, **kw) == -2
+    for field, val in (("h_joint", 12), ("d_enc", 0), ("h_pred", 4096), ("vocab", 0), ("n_dur", 17)):
+        w2 = _weights(cfg); setattr(w2, field, val)
+        assert _decode(lib, w2, durations=dur) == -2
+    # unsupported model kinds
+    for field, val in (("dtype", 2), ("pred_kind", 3), ("pred_layers", 3), ("pred_layers", 0)):
+        w2 = _weights(cfg); setattr(w2, field, val)
+        assert _decode(lib, w2, durations=dur) == -3
+    ws = _weights(synth.CFG4); ws.h_pred = 320       # stateless: h_pred must be ctx * emb_dim
+    assert _decode(lib, ws) == -2
+    # durations
+    assert _decode(lib, w, durations=None) == -4                 # TDT model without a list
+    assert _decode(lib, w, durations=[0, 0, 0, 0, 0]) == -4      # no positive entry
+    assert _decode(lib, w, durations=[0, 1, -1, 3, 4]) == -4     # negative entry
+    assert _decode(lib, _weights(synth.CFG2), durations=[1]) == -4   # list given to a Transducer
+    # options
+    o = binding.tdt_options_t(); o.window = 65
+    assert _decode(lib, w, durations=dur, options=o) == -3
+    o = binding.tdt_options_t(); o.reserved[0] = 1
+    assert _decode(lib, w, durations=dur, options=o) == -3
+    # workspace
+    assert _decode(lib, w, durations=dur, ws=None) == -5
+    assert _decode(lib, w, durations=dur, ws=4096 + 8) == -5
+    assert _decode(lib, w, durations=dur, ws_bytes=1024) == -5
+    # encoder projection entry point
+    assert lib.tdt_encoder_projection(None, 10, C.byref(w), 4096, None) == -1
+    assert lib.tdt_encoder_projection(4096, -1, C.byref(w), 4096, None) == -2
+    assert lib.tdt_encoder_projection(4096, 10, None, 4096, None) == -1

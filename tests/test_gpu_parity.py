@@ -1,0 +1,229 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on
+the same seeded inputs.  Labels and frames bit-exact, scores within 1e-3; rows
+whose only difference is a flipped near-tie (top-2 margin < 1e-3) go through the
+oracle's tolerant replay and are counted (see tests/parity.py)."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+import fig2_model
+import parity
+from paper_2406_06220_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2406_06220_amd import binding
+    binding.load_library()          # raises if the HIP library was not built
+    return binding
+
+
+def run_gpu(binding, cfg, w, enc, ln, u_cap, window=0, n_clusters=0, max_symbols=None, repeat=1):
+    import torch
+    parity.announce(f"tdt_greedy_decode cfg={cfg.name} B={len(ln)} T={enc.shape[1]} u_cap={u_cap} "
+                    f"window={window} n_clusters={n_clusters} S={max_symbols or cfg.max_symbols}")
+    model = binding.DeviceModel(cfg, w)
+    dec = binding.Decoder(model, len(ln), enc.shape[1], u_cap, window=window, n_clusters=n_clusters)
+    enc_d = model.upload_enc(enc)
+    len_d = torch.from_numpy(np.ascontiguousarray(ln, np.int32)).to(model.device)
+    out = None
+    for _ in range(repeat):
+        dec(enc_d, len_d, max_symbols=max_symbols)
+        out = dec.results()
+        assert out["stats"]["abort"] == 0, "a device-side wait timed out"
+    return out
+
+
+def check(oracle, binding, cfg, w=None, enc=None, ln=None, u_cap=None, rows=None,
+          max_replayed_frac=0.1, **kw):
+    w = synth.generate_model(cfg) if w is None else w
+    if enc is None:
+        enc, ln = synth.generate_inputs(cfg)
+    u_cap = cfg.T * cfg.max_symbols if u_cap is None else u_cap
+    out = run_gpu(binding, cfg, w, enc, ln, u_cap, **kw)
+    om = oracle.OracleModel(cfg, w)
+    res = parity.compare(oracle, om, cfg, enc, ln, out, u_cap, rows=rows,
+                         max_symbols=kw.get("max_symbols"))
+    assert res["replayed"] <= max(1, int(max_replayed_frac * res["rows"])), res
+    parity.announce(f"  -> {res} stats={out['stats']}")
+    return out, res
+
+
+# ------------------------------------------------------------------ encoder projection
+@pytest.mark.parametrize("dtype,rows,d_enc,H", [
+    ("bf16", 1000, 512, 640), ("bf16", 37, 64, 72), ("bf16", 257, 1024, 1024), ("bf16", 128, 8, 8),
+    ("fp32", 200, 64, 64), ("fp32", 77, 24, 40)])
+def test_encoder_projection(oracle_lib, gpu, dtype, rows, d_enc, H):
+    import torch
+    cfg = synth.small_config("encproj", dtype=dtype, d_enc=d_enc, h_joint=H, seed=41, B=1, T=rows,
+                             len_lo=rows, len_hi=rows)
+    w = synth.generate_model(cfg)
+    w["b_enc"] = np.random.default_rng(5).standard_normal(H).astype(np.float32)
+    enc, _ = synth.generate_inputs(cfg)
+    parity.announce(f"tdt_encoder_projection dtype={dtype} rows={rows} d_enc={d_enc} H={H}")
+    model = gpu.DeviceModel(cfg, w)
+    enc_d = model.upload_enc(enc[0])
+    out = torch.full((rows + 3, H), 7.0, dtype=torch.float32, device=model.device)
+    gpu.tdt_encoder_projection(enc_d.data_ptr(), rows, model.c, out.data_ptr(),
+                               torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    om = oracle_lib.OracleModel(cfg, w)
+    idx = sorted(set([0, 1, rows // 2, rows - 2, rows - 1] + list(range(0, rows, max(1, rows // 23)))))
+    for r in idx:
+        ref = om.enc_proj_frame(enc[0, r])
+        np.testing.assert_allclose(got[r], ref, atol=2e-4, rtol=1e-5)
+    assert (got[rows:] == 7.0).all(), "rows past the end were written"
+
+
+# ------------------------------------------------------------------ the paper's Fig. 2
+@pytest.mark.parametrize("window,n_clusters", [(0, 0), (1, 1), (3, 2)])
+def test_fig2_example(oracle_lib, gpu, window, n_clusters):
+    ex = fig2_model.build()
+    cfg, w, enc, ln = fig2_model.real_model(ex)
+    out = run_gpu(gpu, cfg, w, enc, ln, 16, window=window, n_clusters=n_clusters)
+    for b, em in enumerate(ex["expected"]):
+        n = out["len"][b]
+        assert list(zip(out["labels"][b, :n], out["frames"][b, :n])) == em
+    if window == 1 and n_clusters == 1:
+        # one frame per pass is Algorithm 3 as printed: the hand-traced call counts
+        assert out["stats"]["pred_passes"] == ex["vals"]["label_looping_predictor_calls"]
+        assert out["stats"]["joint_passes"] == ex["vals"]["label_looping_joiner_calls"]
+
+
+# ------------------------------------------------------------------ small models, all variants
+SMALL = [
+    synth.small_config("g_rnnt_stateless1", d_enc=16, h_pred=16, emb_dim=16, h_joint=24, vocab=13,
+                       B=7, T=40, len_lo=0, len_hi=40, seed=51, default_blank_bias=1.0),
+    synth.small_config("g_rnnt_stateless2", d_enc=16, h_pred=16, emb_dim=8, pred_layers=2,
+                       h_joint=24, vocab=13, B=9, T=40, len_lo=5, len_hi=40, seed=52),
+    synth.small_config("g_rnnt_lstm1", pred_kind="lstm", d_enc=24, h_pred=16, emb_dim=8,
+                       h_joint=40, vocab=29, B=19, T=60, len_lo=1, len_hi=60, seed=53,
+                       default_blank_bias=0.8),
+    synth.small_config("g_tdt_lstm2", pred_kind="lstm", pred_layers=2, durations=(0, 1, 2, 3, 4),
+                       d_enc=24, h_pred=24, emb_dim=16, h_joint=40, vocab=29, B=21, T=90,
+                       len_lo=0, len_hi=90, seed=54, default_blank_bias=0.4, max_symbols=4),
+    synth.small_config("g_tdt_no01_bf16", dtype="bf16", pred_kind="lstm", durations=(2, 5),
+                       d_enc=32, h_pred=32, emb_dim=32, h_joint=48, vocab=70, B=6, T=80,
+                       len_lo=30, len_hi=80, seed=55, default_blank_bias=0.2),
+    synth.small_config("g_rnnt_lstm_bf16_wide", dtype="bf16", pred_kind="lstm", d_enc=136,
+                       h_pred=200, emb_dim=72, h_joint=264, vocab=300, B=33, T=50, len_lo=20,
+                       len_hi=50, seed=56, default_blank_bias=1.5, max_symbols=3),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+@pytest.mark.parametrize("window,n_clusters", [(0, 0), (1, 1), (5, 3), (64, 8)])
+def test_small_models(oracle_lib, gpu, cfg, window, n_clusters):
+    check(oracle_lib, gpu, cfg, window=window, n_clusters=n_clusters)
+
+
+def test_config1_tiny_rnnt(oracle_lib, gpu):
+    out, res = check(oracle_lib, gpu, synth.CFG1)
+    assert res["exact"] == synth.CFG1.B
+
+
+# ------------------------------------------------------------------ edge cases
+def test_edge_lengths_and_capacity(oracle_lib, gpu):
+    cfg = SMALL[2]
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    # empty utterances, and an all-empty batch
+    ln0 = ln.copy(); ln0[::3] = 0
+    check(oracle_lib, gpu, cfg, w, enc, ln0)
+    out = run_gpu(gpu, cfg, w, enc, np.zeros_like(ln), 10)
+    assert (out["len"] == 0).all() and (out["score"] == 0).all() and (out["status"] == 0).all()
+    # lengths outside [0, T] are clamped and flagged
+    bad = ln.copy(); bad[0] = -5; bad[1] = cfg.T + 9
+    out, _ = check(oracle_lib, gpu, cfg, w, enc, bad)
+    assert out["status"][0] & 2 and out["status"][1] & 2 and not (out["status"][2:] & 2).any()
+    # a small capacity truncates and says so
+    out, _ = check(oracle_lib, gpu, cfg, w, enc, ln, u_cap=3)
+    full = run_gpu(gpu, cfg, w, enc, ln, cfg.T * cfg.max_symbols)
+    assert ((out["status"] & 1) == (full["len"] >= 3)).all()
+    assert (out["len"] == np.minimum(full["len"], 3)).all()
+    # one symbol per frame, and B = 1
+    check(oracle_lib, gpu, cfg, w, enc, ln, max_symbols=1)
+    check(oracle_lib, gpu, cfg, w, enc[:1], ln[:1])
+
+
+def test_extreme_blank_bias(oracle_lib, gpu):
+    cfg = SMALL[2]
+    S = cfg.max_symbols
+    enc, ln = synth.generate_inputs(cfg)
+    out = run_gpu(gpu, cfg, synth.generate_model(cfg, 1e4), enc, ln, cfg.T * S)
+    assert (out["len"] == 0).all() and (out["score"] == 0).all()
+    out, _ = check(oracle_lib, gpu, cfg, synth.generate_model(cfg, -1e4), enc, ln)
+    assert (out["len"] == ln * S).all()
+
+
+def test_deterministic_and_permutation_invariant(oracle_lib, gpu):
+    cfg = SMALL[3]
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    u_cap = cfg.T * cfg.max_symbols
+    a = run_gpu(gpu, cfg, w, enc, ln, u_cap)
+    a2 = run_gpu(gpu, cfg, w, enc, ln, u_cap, repeat=2)
+    for key in ("labels", "frames", "len", "score", "status"):
+        assert (a[key] == a2[key]).all(), key
+    b = run_gpu(gpu, cfg, w, enc, ln, u_cap, n_clusters=4, window=7)
+    perm = np.random.default_rng(3).permutation(cfg.B)
+    c = run_gpu(gpu, cfg, w, enc[perm], ln[perm], u_cap)
+    # same launch shape: bit-identical, also under a permutation of the batch; another
+    # launch shape sums the softmax denominator in another order, so only the score may move
+    for key in ("len", "score", "status"):
+        assert (a[key][perm] == c[key]).all(), key
+    assert (a["len"] == b["len"]).all() and (a["status"] == b["status"]).all()
+    assert np.abs(a["score"] - b["score"]).max() < 1e-4
+    for i, p in enumerate(perm):
+        n = a["len"][p]
+        assert (a["labels"][p, :n] == b["labels"][p, :n]).all()
+        assert (a["labels"][p, :n] == c["labels"][i, :n]).all()
+        assert (a["frames"][p, :n] == c["frames"][i, :n]).all()
+
+
+# ------------------------------------------------------------------ the benchmark configurations
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["cfg2_rnnt_lstm", "cfg3_tdt_lstm", "cfg4_rnnt_stateless",
+                                  "cfg2_rnnt_lstm_b128", "cfg3_tdt_lstm_b128"])
+def test_benchmark_configs_full_batch(oracle_lib, gpu, name):
+    check(oracle_lib, gpu, synth.CONFIGS[name])
+
+
+def test_config2_cluster_and_window_variants(oracle_lib, gpu):
+    cfg = synth.CFG2
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    u_cap = cfg.T * cfg.max_symbols
+    om = oracle_lib.OracleModel(cfg, w)
+    orc = oracle_lib.decode_batch(om, enc, ln, cfg.max_symbols, u_cap)
+    for window, n_clusters in [(1, 1), (8, 8), (16, 32), (64, 2)]:
+        out = run_gpu(gpu, cfg, w, enc, ln, u_cap, window=window, n_clusters=n_clusters)
+        res = parity.compare(oracle_lib, om, cfg, enc, ln, out, u_cap, orc=orc)
+        assert res["replayed"] <= 3, res
+
+
+@pytest.mark.timeout(900)
+def test_config5_large_tdt_sampled_rows(oracle_lib, gpu):
+    """Full B=256, T=1500 on the GPU; the oracle decodes a sample of the rows (rows are
+    independent), the rest are checked by properties that hold for any row."""
+    cfg = synth.CFG5
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    u_cap = 4096
+    out = run_gpu(gpu, cfg, w, enc, ln, u_cap)
+    rows = [0, 37, 101, 170, 213, 255]
+    om = oracle_lib.OracleModel(cfg, w)
+    res = parity.compare(oracle_lib, om, cfg, enc, ln, out, u_cap, rows=rows)
+    assert res["replayed"] <= 1, res
+    for b in range(cfg.B):
+        n = out["len"][b]
+        lab, fr = out["labels"][b, :n], out["frames"][b, :n]
+        assert n > 0 and ((lab >= 0) & (lab < cfg.vocab)).all()
+        assert (np.diff(fr) >= 0).all() and (fr >= 0).all() and (fr < ln[b]).all()
+        assert out["score"][b] < 0 and out["status"][b] == 0
