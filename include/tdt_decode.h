@@ -116,7 +116,8 @@ typedef struct {
     int32_t window;
     int32_t n_clusters;
     int32_t reuse_enc_proj;
-    int32_t reserved[5]; /* must be zero */
+    int32_t max_items;   /* most workgroups of a group that share one phase's work; 0 = all */
+    int32_t reserved[4]; /* must be zero */
 } tdt_options_t;
 
 /* counters written to out_stats (int64 each); sums over all hypothesis groups */
@@ -127,7 +128,20 @@ enum tdt_stat {
     TDT_STAT_JOINT_ROWS = 3,  /* (hypothesis, frame) rows those passes scored */
     TDT_STAT_OUTER_MAX = 4,   /* largest number of label-loop iterations of any group */
     TDT_STAT_ABORT = 5,       /* non-zero if an internal wait timed out (results invalid) */
-    TDT_STAT_COUNT = 8
+    /* where the first hypothesis group's time went, in ticks of the device wall clock
+       (hipDeviceAttributeWallClockRate): predictor, projection, joint, decision, waits, all */
+    TDT_STAT_TICKS_PRED = 8,
+    TDT_STAT_TICKS_PROJ = 9,
+    TDT_STAT_TICKS_JOINT = 10,
+    TDT_STAT_TICKS_DECIDE = 11,
+    TDT_STAT_TICKS_BARRIER = 12,
+    TDT_STAT_TICKS_TOTAL = 13,
+    /* of which, inside the three GEMM-shaped phases: staging activations, multiplying,
+       epilogues */
+    TDT_STAT_TICKS_STAGE = 14,
+    TDT_STAT_TICKS_MMA = 15,
+    TDT_STAT_TICKS_EPILOGUE = 16,
+    TDT_STAT_COUNT = 24
 };
 
 /*

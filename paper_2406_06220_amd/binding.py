@@ -19,8 +19,11 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtdt_decode.so")
 
 TDT_MAX_LSTM_LAYERS = 2
-TDT_STAT_NAMES = ("pred_passes", "pred_rows", "joint_passes", "joint_rows", "outer_max", "abort")
-TDT_STAT_COUNT = 8
+TDT_STAT_NAMES = {"pred_passes": 0, "pred_rows": 1, "joint_passes": 2, "joint_rows": 3,
+                  "outer_max": 4, "abort": 5, "ticks_pred": 8, "ticks_proj": 9, "ticks_joint": 10,
+                  "ticks_decide": 11, "ticks_barrier": 12, "ticks_total": 13,
+                  "ticks_stage": 14, "ticks_mma": 15, "ticks_epilogue": 16}
+TDT_STAT_COUNT = 24
 TDT_HYP_TRUNCATED = 1
 TDT_HYP_LEN_CLAMPED = 2
 
@@ -42,7 +45,7 @@ class tdt_weights_t(C.Structure):
 
 class tdt_options_t(C.Structure):
     _fields_ = [("window", C.c_int32), ("n_clusters", C.c_int32), ("reuse_enc_proj", C.c_int32),
-                ("reserved", C.c_int32 * 5)]
+                ("max_items", C.c_int32), ("reserved", C.c_int32 * 4)]
 
 
 _lib = None
@@ -162,7 +165,7 @@ class Decoder:
     """Owns the output tensors and the workspace for one (model, B, T, u_cap)."""
 
     def __init__(self, model: DeviceModel, B: int, T: int, u_cap: int,
-                 window: int = 0, n_clusters: int = 0):
+                 window: int = 0, n_clusters: int = 0, max_items: int = 0):
         import torch
         self.model, self.B, self.T, self.u_cap = model, B, T, u_cap
         dev = model.device
@@ -178,6 +181,7 @@ class Decoder:
         self.options = tdt_options_t()
         self.options.window = window
         self.options.n_clusters = n_clusters
+        self.options.max_items = max_items
 
     def __call__(self, enc_dev, enc_len_dev, max_symbols: Optional[int] = None, stream=None):
         import torch
@@ -199,4 +203,4 @@ class Decoder:
         return dict(labels=self.labels.cpu().numpy(), frames=self.frames.cpu().numpy(),
                     len=self.lens.cpu().numpy(), score=self.score.cpu().numpy(),
                     status=self.status.cpu().numpy(),
-                    stats={n: int(st[i]) for i, n in enumerate(TDT_STAT_NAMES)})
+                    stats={n: int(st[i]) for n, i in TDT_STAT_NAMES.items()})

@@ -21,10 +21,19 @@
 //                         inner loop can be scored together and the first
 //                         non-blank taken -- same result, fewer dependent steps)
 //   D  decision           every workgroup reads the per-row argmax cells that the
-//                         joint pass filled with atomic maxima, walks the window (Alg. 3 lines 10-11,
-//                         16-19; TDT: the step is the predicted duration),
-//                         appends the label (line 20) and updates its copy of
-//                         the control state.
+//                         joint pass filled with atomic maxima, walks the window
+//                         (Alg. 3 lines 10-11, 16-19; TDT: the step is the
+//                         predicted duration), appends the label (line 20) and
+//                         updates its copy of the control state.
+//
+// Each heavy phase is a small-M GEMM: 16 activation rows (a "row tile") against
+// a slice of weight columns, cut into 16-column tiles.  A work item is (row
+// tile, group of column tiles); items are dealt round-robin to the cluster's
+// workgroups.  Activations are float32; bfloat16 weights run on the matrix
+// cores (v_mfma_f32_16x16x32_bf16) with every activation split exactly into
+// three bfloat16 terms (hi + lo + lo2 == x), so products are exact and only the
+// float32 summation order differs from a scalar reference.  float32 weights
+// (small models) use the vector ALUs.
 //
 // Exchange between workgroups.  Data one workgroup writes for another (hidden and
 // cell state, projected predictor output, per-row argmax cells, softmax partials,
@@ -36,18 +45,27 @@
 // cache-wide write-back or invalidate is ever needed, which keeps a barrier at
 // about a microsecond.  Weights and enc_proj are written before the kernel
 // starts and are read through the caches as usual.
-//
-// Arithmetic: float32 activations times float32 or bfloat16 weights with
-// float32 accumulation on the vector ALUs; a wavefront owns one output column,
-// its 64 lanes split the reduction dimension, 16 rows are processed per pass.
 #include <math.h>
 
 #include "tdt_internal.h"
 
+// 1: thread 0 also times staging / multiply / epilogue inside each work item (costs a
+// little; for profiling builds)
+#ifndef TDT_FINE_TIMERS
+#define TDT_FINE_TIMERS 0
+#endif
+
 namespace tdt {
 namespace {
 
-constexpr int RT = 16;   // rows of one staged activation tile
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int RT = 16;       // activation rows per tile
+constexpr int CT = 16;       // weight columns per tile
+constexpr int KSEG = 1024;   // longest stretch of the reduction dimension staged at once
+constexpr int MAXSEG = 4;    // K segments per phase (two inputs of up to 2 * KSEG each)
+constexpr int CP_LD = CT + 1;
 
 struct HypShared {
     int len[kMaxHypsPerCluster];
@@ -65,16 +83,43 @@ struct HypShared {
     int n_act, n_need;
     int wave_cnt[kWaves];
     int durations[TDT_MAX_DURATIONS];
-    float wstats[kWaves][RT][5];
-    int row_a[kMaxRowsPerPass];     // per joint row: argmax label (V = blank)
-    int row_d[kMaxRowsPerPass];     //                frame step of the argmax duration class
-    float row_m[kMaxRowsPerPass];   //                largest label logit
-    int dec_w[kMaxHypsPerCluster];  // per searching hypothesis: window offset the walk stopped at
+    float cpart[kWaves][RT][CP_LD];  // per-wavefront 16x16 partial results of one round
+    float wstats[kWaves][RT][5];     // per column tile of a round: row statistics
+    float bias[kWaves * CT];         // biases of the columns of the current round
+    int row_a[kMaxRowsPerPass];      // per joint row: argmax label (V = blank)
+    int row_d[kMaxRowsPerPass];      //                frame step of the argmax duration class
+    float row_m[kMaxRowsPerPass];    //                largest label logit
+    int dec_w[kMaxHypsPerCluster];   // per searching hypothesis: window offset the walk stopped at
     unsigned char dec_found[kMaxHypsPerCluster];   // ... on a non-blank label
     unsigned epoch;
     int aborted;
+    long long tk_stage, tk_mma, tk_epi;   // thread 0: ticks spent staging / multiplying / in epilogues
 };
 
+// one stretch of the reduction dimension: `K` inputs multiplied by columns
+// [wk0, wk0 + K) of the rows of weight matrix `w` (row stride wld)
+struct Seg {
+    const void *w;
+    int wld, wk0, K;
+    int part, k0;   // which input of the phase (0 / 1) and the offset inside it
+};
+
+__device__ inline int add_segments(Seg *segs, int n, const void *w, int K, int part)
+{
+    for (int k0 = 0; k0 < K && n < MAXSEG; k0 += KSEG) {
+        Seg s;
+        s.w = w;
+        s.wld = K;
+        s.wk0 = k0;
+        s.K = min(KSEG, K - k0);
+        s.part = part;
+        s.k0 = k0;
+        segs[n++] = s;
+    }
+    return n;
+}
+
+// ---- number formats
 template <typename WT> __device__ inline float2 load_w2(const WT *p);
 template <> __device__ inline float2 load_w2<float>(const float *p)
 {
@@ -84,42 +129,6 @@ template <> __device__ inline float2 load_w2<uint16_t>(const uint16_t *p)
 {
     const uint32_t u = *reinterpret_cast<const uint32_t *>(p);
     return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
-}
-template <typename WT> __device__ inline float load_w1(const WT *p);
-template <> __device__ inline float load_w1<float>(const float *p) { return *p; }
-template <> __device__ inline float load_w1<uint16_t>(const uint16_t *p)
-{
-    return __uint_as_float(((uint32_t)*p) << 16);
-}
-
-// acc[i] += sum over this lane's k of act[i][k] * w[k]   (K even; lanes take pairs)
-template <typename WT>
-__device__ inline void wave_dot(const float *act, int ld, int K, const WT *__restrict__ w,
-                                float (&acc)[RT], int lane)
-{
-    for (int k = lane * 2; k < K; k += 128) {
-        const float2 wv = load_w2<WT>(w + k);
-#pragma unroll
-        for (int i = 0; i < RT; ++i) {
-            const float2 a = *reinterpret_cast<const float2 *>(act + i * ld + k);
-            acc[i] = fmaf(a.x, wv.x, acc[i]);
-            acc[i] = fmaf(a.y, wv.y, acc[i]);
-        }
-    }
-}
-
-// after this every lane holds the wavefront-wide sums; returns the one of row `lane`
-__device__ inline float wave_reduce_select(float (&acc)[RT], int lane)
-{
-    float mine = 0.0f;
-#pragma unroll
-    for (int i = 0; i < RT; ++i) {
-        float v = acc[i];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-        if (lane == i) mine = v;
-    }
-    return mine;
 }
 
 __device__ inline float sigmoidf_dev(float x) { return 1.0f / (1.0f + expf(-x)); }
@@ -230,22 +239,313 @@ __device__ inline void build_list(HypShared &S, const unsigned char *flag, int G
     __syncthreads();
 }
 
-// split `n_cols` columns over the workgroups left after `n_tiles` row tiles took theirs
-__device__ inline void split_columns(int C, int n_tiles, int n_cols, int max_groups, int &n_groups,
-                                     int &per_group)
+// deal `n_units` column tiles to the workgroups left after `n_row_tiles` took theirs
+__device__ inline void split_tiles(int C, int n_row_tiles, int n_units, int max_groups, int &n_groups,
+                                   int &per_group)
 {
-    int g = C / (n_tiles > 0 ? n_tiles : 1);
+    int g = C / (n_row_tiles > 0 ? n_row_tiles : 1);
     if (g < 1) g = 1;
     if (g > max_groups) g = max_groups;
-    if (g > n_cols) g = n_cols;
-    per_group = (n_cols + g - 1) / g;
-    n_groups = (n_cols + per_group - 1) / per_group;
+    if (g > n_units) g = n_units;
+    per_group = (n_units + g - 1) / g;
+    n_groups = (n_units + per_group - 1) / per_group;
+}
+
+// ---------------------------------------------------------------------------
+// Activation tile in LDS and the two tile-GEMM back ends
+// ---------------------------------------------------------------------------
+// bfloat16 weights: three bfloat16 planes [3][RT][ldb] with hi + lo + lo2 == x.
+// float32 weights:  one float plane [RT][ldb].
+template <typename WT> struct ActTile;
+
+template <> struct ActTile<uint16_t> {
+    uint16_t *planes;
+    int ldb;   // elements per row (multiple of 8, padded)
+    __host__ __device__ static int row_elems(int kseg_max) { return ((kseg_max + 31) / 32) * 32 + 8; }
+    // x == hi + lo + lo2 exactly, each term a bfloat16: hi and lo are x and the first
+    // remainder truncated to their top 16 bits (a truncated term keeps the sign, so each
+    // remainder is exact and shorter by at least 8 significant bits); the second
+    // remainder has at most 8 significant bits left and is a bfloat16 as it stands
+    __device__ static void split3(float x, unsigned &hi, unsigned &lo, unsigned &lo2)
+    {
+        hi = __float_as_uint(x) & 0xffff0000u;
+        const float r1 = x - __uint_as_float(hi);
+        lo = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(lo);
+        lo2 = __float_as_uint(r2);
+    }
+    __device__ void store2(int i, int k, float2 v) const
+    {
+        unsigned a[3], b[3];
+        split3(v.x, a[0], a[1], a[2]);
+        split3(v.y, b[0], b[1], b[2]);
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)   // element k in the low half, k + 1 in the high half
+            *reinterpret_cast<unsigned *>(planes + ((size_t)pl * RT + i) * ldb + k) =
+                (a[pl] >> 16) | (b[pl] & 0xffff0000u);
+    }
+};
+
+template <> struct ActTile<float> {
+    float *planes;
+    int ldb;
+    __host__ __device__ static int row_elems(int kseg_max) { return ((kseg_max + 31) / 32) * 32; }
+    __device__ void store2(int i, int k, float2 v) const
+    {
+        *reinterpret_cast<float2 *>(planes + (size_t)i * ldb + k) = v;
+    }
+};
+
+// stage one K segment: f(i, k) gives the two inputs (k, k+1) of row i; the tail up to a
+// multiple of 32 is zero-filled.  All loads of a wavefront are issued before the first
+// value is used, so that their latencies overlap.
+template <typename WT, typename F>
+__device__ inline void stage_segment(const ActTile<WT> &A, int K, F f)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int Kpad = ((K + 31) / 32) * 32;
+    constexpr int RPW = RT / kWaves;    // rows per wavefront
+    constexpr int KIT = KSEG / 128;     // 64 lanes x 2 inputs per step
+    // f is called with in-range (i, k) only and must itself be free of branches around its
+    // loads (clamp the address, mask the value): a load inside a conditional block would be
+    // waited for before the next one is issued
+    float2 v[RPW][KIT];
+#pragma unroll
+    for (int ii = 0; ii < RPW; ++ii)
+#pragma unroll
+        for (int kk = 0; kk < KIT; ++kk) {
+            const int k = lane * 2 + kk * 128;
+            const float2 x = f(wave + ii * kWaves, k < K ? k : K - 2);
+            v[ii][kk] = make_float2(k < K ? x.x : 0.0f, k < K ? x.y : 0.0f);
+        }
+#pragma unroll
+    for (int ii = 0; ii < RPW; ++ii)
+#pragma unroll
+        for (int kk = 0; kk < KIT; ++kk) {
+            const int k = lane * 2 + kk * 128;
+            if (k < Kpad) A.store2(wave + ii * kWaves, k, v[ii][kk]);
+        }
+}
+
+// accumulators of one wavefront for one 16x16 tile
+template <typename WT> struct Accum;
+template <> struct Accum<uint16_t> {
+    f32x4 c;   // lane l: column l % 16, rows (l / 16) * 4 + e
+    __device__ void clear() { c = f32x4{0.0f, 0.0f, 0.0f, 0.0f}; }
+};
+template <> struct Accum<float> {
+    float c[CT];   // lane l < 16: row l, column j
+    __device__ void clear()
+    {
+#pragma unroll
+        for (int j = 0; j < CT; ++j) c[j] = 0.0f;
+    }
+};
+
+// matrix-core back end: this wavefront adds its share (k-steps kpart, kpart + ksplit, ...)
+// of one segment to the 16x16 tile whose 16 weight rows are given per lane (l % 16).
+// The first chunk of weight fragments can be fetched ahead (before the activations are
+// staged) with weight_prefetch.
+constexpr int CH = 4;   // weight fragments in flight per wavefront
+
+struct WeightCursor {
+    const uint16_t *wr;   // this lane's weight row at its k-quarter (row 0 if the column is padding)
+    bool live;            // false: the column is padding and its fragments are zero
+    int kq, n_my;
+};
+
+__device__ inline WeightCursor weight_cursor(const Seg &sg, long long wrow, int kpart, int ksplit, int lane)
+{
+    WeightCursor wc;
+    wc.kq = (lane >> 4) * 8;
+    wc.live = wrow >= 0;
+    wc.wr = static_cast<const uint16_t *>(sg.w) + (wc.live ? wrow : 0) * sg.wld + sg.wk0;
+    const int nsteps = (sg.K + 31) / 32;
+    wc.n_my = nsteps > kpart ? (nsteps - kpart + ksplit - 1) / ksplit : 0;
+    return wc;
+}
+
+// loads are unconditional (address clamped into the row, value masked) so that all CH of
+// them are in flight together
+__device__ inline void weight_prefetch(const WeightCursor &wc, const Seg &sg, int kpart, int ksplit, int c0,
+                                       uint4 (&b)[CH])
+{
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int k = (kpart + (c0 + j) * ksplit) * 32 + wc.kq;
+        const bool ok = wc.live && c0 + j < wc.n_my && k < sg.K;
+        const uint4 x = *reinterpret_cast<const uint4 *>(wc.wr + (k < sg.K ? k : sg.K - 8));
+        b[j] = make_uint4(ok ? x.x : 0u, ok ? x.y : 0u, ok ? x.z : 0u, ok ? x.w : 0u);
+    }
+}
+
+__device__ inline void tile_accumulate(const ActTile<uint16_t> &A, const Seg &sg, const WeightCursor &wc,
+                                       int kpart, int ksplit, uint4 (&b)[CH], bool have_first, f32x4 &acc,
+                                       int lane)
+{
+    const uint16_t *a0 = A.planes + (size_t)(lane & 15) * A.ldb + wc.kq;
+    const size_t plane = (size_t)RT * A.ldb;
+    for (int c0 = 0; c0 < wc.n_my; c0 += CH) {
+        if (c0 > 0 || !have_first) weight_prefetch(wc, sg, kpart, ksplit, c0, b);
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            if (c0 + j < wc.n_my) {
+                const int s = kpart + (c0 + j) * ksplit;
+                const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&b[j]);
+                const bf16x8 x0 = *reinterpret_cast<const bf16x8 *>(a0 + s * 32);
+                const bf16x8 x1 = *reinterpret_cast<const bf16x8 *>(a0 + plane + s * 32);
+                const bf16x8 x2 = *reinterpret_cast<const bf16x8 *>(a0 + 2 * plane + s * 32);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, bv, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, bv, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x2, bv, acc, 0, 0, 0);
+            }
+        }
+    }
+}
+
+// vector-ALU back end: the wavefront's 64 lanes split K, all 16 rows at once, one column
+__device__ inline float column_dot(const ActTile<float> &A, const Seg &sg, long long wrow, int lane)
+{
+    float acc[RT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i) acc[i] = 0.0f;
+    if (wrow >= 0) {
+        const float *w = static_cast<const float *>(sg.w) + wrow * sg.wld + sg.wk0;
+        for (int k = lane * 2; k < sg.K; k += 128) {
+            const float2 wv = *reinterpret_cast<const float2 *>(w + k);
+#pragma unroll
+            for (int i = 0; i < RT; ++i) {
+                const float2 a = *reinterpret_cast<const float2 *>(A.planes + (size_t)i * A.ldb + k);
+                acc[i] = fmaf(a.x, wv.x, acc[i]);
+                acc[i] = fmaf(a.y, wv.y, acc[i]);
+            }
+        }
+    }
+    float mine = 0.0f;
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+        float v = acc[i];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        if (lane == i) mine = v;
+    }
+    return mine;   // lane i < 16: row i
+}
+
+template <typename WT> struct Backend;
+template <> struct Backend<uint16_t> {
+    struct Pre {   // weight fragments fetched while the activations are being staged
+        WeightCursor wc;
+        uint4 b[CH];
+    };
+    template <typename RowF>
+    __device__ static void prefetch(Pre &pre, const Seg &sg, RowF rowidx, int ct, int kpart, int ksplit, int lane)
+    {
+        pre.wc = weight_cursor(sg, rowidx(ct, lane & 15), kpart, ksplit, lane);
+        weight_prefetch(pre.wc, sg, kpart, ksplit, 0, pre.b);
+    }
+    template <typename RowF>
+    __device__ static void accumulate(const ActTile<uint16_t> &A, const Seg &sg, RowF, int, int kpart, int ksplit,
+                                      Accum<uint16_t> &acc, int lane, Pre &pre)
+    {
+        tile_accumulate(A, sg, pre.wc, kpart, ksplit, pre.b, true, acc.c, lane);
+    }
+    __device__ static void spill(HypShared &S, const Accum<uint16_t> &acc, int wave, int lane)
+    {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) S.cpart[wave][(lane >> 4) * 4 + e][lane & 15] = acc.c[e];
+    }
+    __device__ static int ksplit_for(int n_ct) { return n_ct <= 1 ? 8 : n_ct <= 2 ? 4 : n_ct <= 4 ? 2 : 1; }
+};
+template <> struct Backend<float> {
+    struct Pre {};
+    template <typename RowF>
+    __device__ static void prefetch(Pre &, const Seg &, RowF, int, int, int, int) {}
+    template <typename RowF>
+    __device__ static void accumulate(const ActTile<float> &A, const Seg &sg, RowF rowidx, int ct, int, int,
+                                      Accum<float> &acc, int lane, Pre &)
+    {
+        for (int j = 0; j < CT; ++j) {
+            const float v = column_dot(A, sg, rowidx(ct, j), lane);
+#pragma unroll
+            for (int jj = 0; jj < CT; ++jj)
+                if (jj == j) acc.c[jj] += v;
+        }
+    }
+    __device__ static void spill(HypShared &S, const Accum<float> &acc, int wave, int lane)
+    {
+        if (lane < RT) {
+#pragma unroll
+            for (int j = 0; j < CT; ++j) S.cpart[wave][lane][j] = acc.c[j];
+        }
+    }
+    __device__ static int ksplit_for(int) { return 1; }
+};
+
+// One work item: all K segments of the staged rows against n_ct column tiles, a round of
+// (8 / ksplit) column tiles at a time.
+//   stage(seg)                     stages segment seg of the item's rows (stage_segment)
+//   rowidx(ct, j)    -> long long  weight row of column j of column tile ct, -1 if none
+//   epi(ct0, n, ksplit)            called by all threads once S.cpart holds round results:
+//                                  tile slot t (< n) is the sum over kp < ksplit of
+//                                  S.cpart[t * ksplit + kp]; S.bias[t * 16 + j] is
+//                                  bias[rowidx(ct0 + t, j)]
+// With one segment the rows are staged once; with several they are staged again for
+// every round.
+template <typename WT, typename StageF, typename RowF, typename EpiF>
+__device__ inline void run_item(HypShared &S, const ActTile<WT> &A, int nseg, const Seg *segs, int n_ct,
+                                const float *__restrict__ bias, StageF stage, RowF rowidx, EpiF epi)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ksplit = Backend<WT>::ksplit_for(n_ct);
+    const int tpr = kWaves / ksplit;          // column tiles per round
+    const int tslot = wave / ksplit, kpart = wave % ksplit;
+    for (int base = 0; base < n_ct; base += tpr) {
+        const int ct = base + tslot;
+        const bool mine = ct < n_ct;
+        Accum<WT> acc;
+        acc.clear();
+        if (threadIdx.x < tpr * CT) {   // read before the epilogue, behind two barriers
+            const long long r = base + (int)threadIdx.x / CT < n_ct ? rowidx(base + (int)threadIdx.x / CT, (int)threadIdx.x % CT) : -1;
+            S.bias[threadIdx.x] = r >= 0 ? bias[r] : 0.0f;
+        }
+        for (int sgi = 0; sgi < nseg; ++sgi) {
+            const Seg sg = segs[sgi];
+            long long tq = 0;
+            if (TDT_FINE_TIMERS && threadIdx.x == 0) tq = wall_clock64();
+            typename Backend<WT>::Pre pre;
+            // the weights do not depend on the activations: fetch the first of them now
+            if (mine) Backend<WT>::prefetch(pre, sg, rowidx, ct, kpart, ksplit, lane);
+            if (nseg > 1 || base == 0) {
+                __syncthreads();   // previous readers of the tile are done
+                stage(sgi);
+                __syncthreads();
+            }
+            if (TDT_FINE_TIMERS && threadIdx.x == 0) { const long long n = wall_clock64(); S.tk_stage += n - tq; tq = n; }
+            if (mine) Backend<WT>::accumulate(A, sg, rowidx, ct, kpart, ksplit, acc, lane, pre);
+            if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_mma += wall_clock64() - tq;
+        }
+        long long tq = 0;
+        if (TDT_FINE_TIMERS && threadIdx.x == 0) tq = wall_clock64();
+        if (mine) Backend<WT>::spill(S, acc, wave, lane);
+        __syncthreads();
+        epi(base, min(tpr, n_ct - base), ksplit);
+        __syncthreads();
+        if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_epi += wall_clock64() - tq;
+    }
+}
+
+__device__ inline float cpart_sum(const HypShared &S, int t, int ksplit, int i, int j)
+{
+    float v = S.cpart[t * ksplit][i][j];
+    for (int kp = 1; kp < ksplit; ++kp) v += S.cpart[t * ksplit + kp][i][j];
+    return v;
 }
 
 template <typename WT>
 __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 {
-    extern __shared__ __align__(16) float act[];
+    extern __shared__ __align__(16) unsigned char dyn_lds[];
     __shared__ HypShared S;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -259,6 +559,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     const int B = p.B, T = p.T, H = p.H, V = p.V, D = p.D, O = p.O;
     const int Hp = p.h_pred, E = p.emb_dim, L = p.pred_layers;
     const bool lstm = p.pred_kind == TDT_PRED_LSTM;
+
+    ActTile<WT> A;
+    A.planes = reinterpret_cast<decltype(A.planes)>(dyn_lds);
+    A.ldb = ActTile<WT>::row_elems(p.kseg_max);
 
     BarrierInfo bi;
     bi.root = p.barrier + (size_t)cl * kBarrierStride;
@@ -277,6 +581,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     unsigned long long *const rl_base = p.row_lab + (size_t)cl * kRowBufs * rows_cap;
     unsigned long long *const rd_base = p.row_dur + (size_t)cl * kRowBufs * rows_cap;
     const int max_cg = min(kMaxColGroups, kPartialEntries / ncl / kMaxRowsPerPass);
+    const int Csplit = p.max_items > 0 && p.max_items < C ? p.max_items : C;   // work items per phase
 
     // ---- Alg. 3 lines 3-4: empty hypotheses, time 0, everyone with frames is active
     for (int g = tid; g < G; g += kThreads) {
@@ -296,10 +601,18 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         S.need[g] = 0;
     }
     if (tid < TDT_MAX_DURATIONS) S.durations[tid] = p.durations[tid];
-    if (tid == 0) { S.epoch = 0; S.aborted = 0; }
+    if (tid == 0) { S.epoch = 0; S.aborted = 0; S.tk_stage = S.tk_mma = S.tk_epi = 0; }
     __syncthreads();
 
     long long st_pred_pass = 0, st_pred_rows = 0, st_joint_pass = 0, st_joint_rows = 0, st_outer = 0;
+    long long tk_p = 0, tk_q = 0, tk_j = 0, tk_d = 0, tk_bar = 0;   // wall-clock ticks per phase
+    long long tk0 = wall_clock64();
+    const long long tk_start = tk0;
+    auto lap = [&](long long &bucket) {
+        const long long now = wall_clock64();
+        bucket += now - tk0;
+        tk0 = now;
+    };
     int pp = 0;          // which half of hbuf holds the current hidden state
     unsigned jpass = 0;  // joint passes so far (selects the exchange buffers)
     bool ok = true;
@@ -316,112 +629,127 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         // ---- P: predictor step (Alg. 3 line 6)
         if (lstm) {
             for (int l = 0; l < L && ok; ++l) {
-                const int in_dim = l == 0 ? E : Hp, ld = in_dim + Hp;
-                const WT *w_ih = static_cast<const WT *>(p.w_ih[l]);
-                const WT *w_hh = static_cast<const WT *>(p.w_hh[l]);
+                const int in_dim = l == 0 ? E : Hp;
                 const float *bl = p.b_lstm[l];
                 const float *h_cur = p.hbuf + ((size_t)pp * L + l) * B * Hp;
                 float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L + l) * B * Hp;
                 const float *x_prev = l > 0 ? p.hbuf + ((size_t)(pp ^ 1) * L + (l - 1)) * B * Hp : nullptr;
                 float *cst = p.cbuf + (size_t)l * B * Hp;
-                int n_ug, upg;
-                split_columns(C, n_tiles_a, Hp, Hp, n_ug, upg);
+                Seg segs[MAXSEG];
+                int nseg = add_segments(segs, 0, p.w_ih[l], in_dim, 0);
+                nseg = add_segments(segs, nseg, p.w_hh[l], Hp, 1);
+                const int NT = (Hp + 3) / 4;   // a column tile = 4 hidden units x 4 gates
+                int n_ug, tpg;
+                split_tiles(Csplit, n_tiles_a, NT, NT, n_ug, tpg);
                 for (int it = rank; it < n_tiles_a * n_ug; it += C) {
                     const int ti = it / n_ug, ug = it % n_ug;
                     const int nrows = min(RT, n_act - ti * RT);
-                    for (int i = wave; i < RT; i += kWaves) {
-                        float *row = act + i * ld;
-                        if (i < nrows) {
-                            const int g = S.act_list[ti * RT + i];
-                            const size_t hb = (size_t)(b0 + g) * Hp;
-                            if (l == 0) {
-                                const WT *e = static_cast<const WT *>(p.emb) + (size_t)S.last[g] * E;
-                                for (int k = lane; k < E; k += 64) row[k] = load_w1<WT>(e + k);
-                            } else {
-                                for (int k = lane * 2; k < Hp; k += 128)
-                                    *reinterpret_cast<float2 *>(row + k) = ld_co2(x_prev + hb + k);
+                    const int tile0 = ug * tpg, n_ct = min(tpg, NT - tile0);
+                    run_item<WT>(
+                        S, A, nseg, segs, n_ct, bl,
+                        [&](int sgi) {
+                            const int k0 = segs[sgi].k0;
+                            if (segs[sgi].part == 1 || l > 0) {   // hidden state: coherent loads
+                                const float *src = segs[sgi].part == 1 ? h_cur : x_prev;
+                                stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                                    const bool valid = i < nrows;
+                                    const int g = S.act_list[ti * RT + (valid ? i : 0)];
+                                    const float2 x = ld_co2(src + (size_t)(b0 + g) * Hp + k0 + k);
+                                    return make_float2(valid ? x.x : 0.0f, valid ? x.y : 0.0f);
+                                });
+                            } else {                              // embedding of the last label
+                                stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                                    const bool valid = i < nrows;
+                                    const int g = S.act_list[ti * RT + (valid ? i : 0)];
+                                    const float2 x = load_w2<WT>(static_cast<const WT *>(p.emb) +
+                                                                 (size_t)S.last[g] * E + k0 + k);
+                                    return make_float2(valid ? x.x : 0.0f, valid ? x.y : 0.0f);
+                                });
                             }
-                            for (int k = lane * 2; k < Hp; k += 128)
-                                *reinterpret_cast<float2 *>(row + in_dim + k) = ld_co2(h_cur + hb + k);
-                        } else {
-                            for (int k = lane; k < ld; k += 64) row[k] = 0.0f;
-                        }
-                    }
-                    __syncthreads();
-                    const int u_end = min(Hp, (ug + 1) * upg);
-                    for (int u = ug * upg + wave; u < u_end; u += kWaves) {
-                        float gate[4];
+                        },
+                        [&](int ct, int j) -> long long {
+                            const int unit = (tile0 + ct) * 4 + (j >> 2);
+                            return unit < Hp ? (long long)(j & 3) * Hp + unit : -1;
+                        },
+                        [&](int base, int n, int ksplit) {
+                            // thread -> (tile slot, row, unit): all four gates, then the cell update
+                            const int t = tid >> 6, i = (tid & 63) >> 2, uq = tid & 3;
+                            const int unit = (tile0 + base + t) * 4 + uq;
+                            if (t < n && i < nrows && unit < Hp) {
+                                float gate[4];
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            float acc[RT];
-#pragma unroll
-                            for (int i = 0; i < RT; ++i) acc[i] = 0.0f;
-                            const size_t r = (size_t)q * Hp + u;
-                            wave_dot<WT>(act, ld, in_dim, w_ih + r * in_dim, acc, lane);
-                            wave_dot<WT>(act + in_dim, ld, Hp, w_hh + r * Hp, acc, lane);
-                            gate[q] = wave_reduce_select(acc, lane) + bl[r];
-                        }
-                        if (lane < nrows) {
-                            const int g = S.act_list[ti * RT + lane];
-                            const size_t o = (size_t)(b0 + g) * Hp + u;
-                            const float ig = sigmoidf_dev(gate[0]), fg = sigmoidf_dev(gate[1]);
-                            const float gg = tanhf(gate[2]), og = sigmoidf_dev(gate[3]);
-                            const float cn = fg * ld_co(cst + o) + ig * gg;
-                            st_co(cst + o, cn);
-                            st_co(h_next + o, og * tanhf(cn));
-                        }
-                    }
-                    __syncthreads();
+                                for (int q = 0; q < 4; ++q)
+                                    gate[q] = cpart_sum(S, t, ksplit, i, uq * 4 + q) + S.bias[t * CT + uq * 4 + q];
+                                const int g = S.act_list[ti * RT + i];
+                                const size_t o = (size_t)(b0 + g) * Hp + unit;
+                                const float ig = sigmoidf_dev(gate[0]), fg = sigmoidf_dev(gate[1]);
+                                const float gg = tanhf(gate[2]), og = sigmoidf_dev(gate[3]);
+                                const float cn = fg * ld_co(cst + o) + ig * gg;
+                                st_co(cst + o, cn);
+                                st_co(h_next + o, og * tanhf(cn));
+                            }
+                        });
                 }
+                lap(tk_p);
                 ok = cluster_barrier(S, bi, p.abort_flag, C, p.timeout_ticks);
+                lap(tk_bar);
             }
             if (!ok) break;
         }
 
         // ---- Q: predictor output into the joint space (Sec. 3.4)
         {
-            const WT *w_pred = static_cast<const WT *>(p.w_pred);
             const float *dec_src = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * B * Hp : nullptr;
-            int n_cg, cpg;
-            split_columns(C, n_tiles_a, H, H, n_cg, cpg);
+            Seg segs[MAXSEG];
+            const int nseg = add_segments(segs, 0, p.w_pred, Hp, 0);
+            const int NT = (H + CT - 1) / CT;
+            int n_cg, tpg;
+            split_tiles(Csplit, n_tiles_a, NT, NT, n_cg, tpg);
             for (int it = rank; it < n_tiles_a * n_cg; it += C) {
                 const int ti = it / n_cg, cg = it % n_cg;
                 const int nrows = min(RT, n_act - ti * RT);
-                for (int i = wave; i < RT; i += kWaves) {
-                    float *row = act + i * Hp;
-                    if (i < nrows) {
-                        const int g = S.act_list[ti * RT + i];
+                const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
+                run_item<WT>(
+                    S, A, nseg, segs, n_ct, p.b_pred,
+                    [&](int sgi) {
+                        const int k0 = segs[sgi].k0;
                         if (lstm) {
-                            const size_t hb = (size_t)(b0 + g) * Hp;
-                            for (int k = lane * 2; k < Hp; k += 128)
-                                *reinterpret_cast<float2 *>(row + k) = ld_co2(dec_src + hb + k);
+                            stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                                const bool valid = i < nrows;
+                                const int g = S.act_list[ti * RT + (valid ? i : 0)];
+                                const float2 x = ld_co2(dec_src + (size_t)(b0 + g) * Hp + k0 + k);
+                                return make_float2(valid ? x.x : 0.0f, valid ? x.y : 0.0f);
+                            });
                         } else {
-                            // table L-1 embeds the newest label, table 0 the older one
-                            const WT *emb = static_cast<const WT *>(p.emb);
-                            for (int c = 0; c < L; ++c) {
+                            // stateless: table L-1 embeds the newest label, table 0 the older one
+                            stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                                const bool valid = i < nrows;
+                                const int g = S.act_list[ti * RT + (valid ? i : 0)];
+                                const int kk = k0 + k, c = kk / E;
                                 const int tok = (c == L - 1) ? S.last[g] : S.last2[g];
-                                const WT *e = emb + ((size_t)c * (V + 1) + tok) * E;
-                                for (int k = lane; k < E; k += 64) row[c * E + k] = load_w1<WT>(e + k);
-                            }
+                                const float2 x = load_w2<WT>(static_cast<const WT *>(p.emb) +
+                                                             ((size_t)c * (V + 1) + tok) * E + (kk - c * E));
+                                return make_float2(valid ? x.x : 0.0f, valid ? x.y : 0.0f);
+                            });
                         }
-                    } else {
-                        for (int k = lane; k < Hp; k += 64) row[k] = 0.0f;
-                    }
-                }
-                __syncthreads();
-                const int c_end = min(H, (cg + 1) * cpg);
-                for (int n = cg * cpg + wave; n < c_end; n += kWaves) {
-                    float acc[RT];
-#pragma unroll
-                    for (int i = 0; i < RT; ++i) acc[i] = 0.0f;
-                    wave_dot<WT>(act, Hp, Hp, w_pred + (size_t)n * Hp, acc, lane);
-                    const float v = wave_reduce_select(acc, lane) + p.b_pred[n];
-                    if (lane < nrows)
-                        st_co(p.pred_proj + (size_t)(b0 + S.act_list[ti * RT + lane]) * H + n, v);
-                }
-                __syncthreads();
+                    },
+                    [&](int ct, int j) -> long long {
+                        const int n = (tile0 + ct) * CT + j;
+                        return n < H ? n : -1;
+                    },
+                    [&](int base, int n, int ksplit) {
+                        for (int idx = tid; idx < n * RT * CT; idx += kThreads) {
+                            const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
+                            const int col = (tile0 + base + t) * CT + j;
+                            if (i < nrows && col < H)
+                                st_co(p.pred_proj + (size_t)(b0 + S.act_list[ti * RT + i]) * H + col,
+                                      cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j]);
+                        }
+                    });
             }
+            lap(tk_q);
             ok = cluster_barrier(S, bi, p.abort_flag, C, p.timeout_ticks);
+            lap(tk_bar);
             if (!ok) break;
         }
 
@@ -433,14 +761,15 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         // ---- inner loop (Alg. 3 line 12): joint passes until nobody searches any more
         while (S.n_need > 0) {
             const int n_need = S.n_need;
-            int Kw = p.window > 0 ? p.window : 256 / n_need;
-            if (Kw < 4 && p.window <= 0) Kw = 4;
+            int Kw = p.window > 0 ? p.window : 512 / n_need;
+            if (Kw < 8 && p.window <= 0) Kw = 8;
             if (Kw > kMaxWindow) Kw = kMaxWindow;
             if (Kw * n_need > rows_cap) Kw = rows_cap / n_need;
             const int M = n_need * Kw;
             const int n_tiles = (M + RT - 1) / RT;
-            int n_cg, cpg;
-            split_columns(C, n_tiles, O, max_cg, n_cg, cpg);
+            const int NT = (O + CT - 1) / CT;
+            int n_cg, tpg;
+            split_tiles(Csplit, n_tiles, NT, max_cg, n_cg, tpg);
             LsePartial *pbuf = pbase + (size_t)(jpass & 1u) * kPartialEntries;
             unsigned long long *row_lab = rl_base + (size_t)(jpass % kRowBufs) * rows_cap;
             unsigned long long *row_dur = rd_base + (size_t)(jpass % kRowBufs) * rows_cap;
@@ -458,99 +787,122 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             st_joint_rows += M;
 
             // ---- J: joint network on M rows
-            const WT *w_out = static_cast<const WT *>(p.w_out);
+            Seg segs[MAXSEG];
+            const int nseg = add_segments(segs, 0, p.w_out, H, 0);
             for (int it = rank; it < n_tiles * n_cg; it += C) {
                 const int ti = it / n_cg, cg = it % n_cg;
-                for (int i = wave; i < RT; i += kWaves) {
-                    float *row = act + i * H;
-                    const int r = ti * RT + i;
-                    bool valid = r < M;
-                    int g = 0, f = 0;
-                    if (valid) {
-                        g = S.need_list[r / Kw];
-                        f = S.time[g] + r % Kw;
-                        valid = f < S.len[g];
-                    }
-                    if (valid) {
-                        const float *ep = p.enc_proj + ((size_t)(b0 + g) * T + f) * H;
-                        const float *pj = p.pred_proj + (size_t)(b0 + g) * H;
-                        for (int k = lane * 2; k < H; k += 128) {
-                            const float2 e2 = *reinterpret_cast<const float2 *>(ep + k);
-                            const float2 p2 = ld_co2(pj + k);
-                            *reinterpret_cast<float2 *>(row + k) =
-                                make_float2(fmaxf(e2.x + p2.x, 0.0f), fmaxf(e2.y + p2.y, 0.0f));
-                        }
-                    } else {
-                        for (int k = lane; k < H; k += 64) row[k] = 0.0f;
-                    }
-                }
-                __syncthreads();
-                // running statistics of row `lane` over this wavefront's columns
-                float mlab = -INFINITY, slab = 0.0f, mdur = -INFINITY;
-                int alab = 0, adur = 0;
-                const int c_end = min(O, (cg + 1) * cpg);
-                for (int n = cg * cpg + wave; n < c_end; n += kWaves) {
-                    float acc[RT];
+                const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
+                // running statistics of row `tid` (tid < 16) over this item's columns
+                float rm = -INFINITY, rs = 0.0f, rdm = -INFINITY;
+                int ra = 0, rda = 0;
+                run_item<WT>(
+                    S, A, nseg, segs, n_ct, p.b_out,
+                    [&](int sgi) {
+                        const int k0 = segs[sgi].k0;
+                        stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                            const int r = min(ti * RT + i, M - 1);
+                            const int g = S.need_list[r / Kw];
+                            const int f = S.time[g] + r % Kw;
+                            const bool valid = ti * RT + i < M && f < S.len[g];
+                            const float2 e2 = *reinterpret_cast<const float2 *>(
+                                p.enc_proj + ((size_t)(b0 + g) * T + (valid ? f : 0)) * H + k0 + k);
+                            const float2 p2 = ld_co2(p.pred_proj + (size_t)(b0 + g) * H + k0 + k);
+                            return make_float2(valid ? fmaxf(e2.x + p2.x, 0.0f) : 0.0f,
+                                               valid ? fmaxf(e2.y + p2.y, 0.0f) : 0.0f);
+                        });
+                    },
+                    [&](int ct, int j) -> long long {
+                        const int n = (tile0 + ct) * CT + j;
+                        return n < O ? n : -1;
+                    },
+                    [&](int base, int n, int ksplit) {
+                        // four threads share (tile slot t, row i), four columns each; lower
+                        // columns win ties, so the first maximum is kept
+                        const int t = tid >> 6, i = (tid >> 2) & 15, jq = tid & 3;
+                        float m = -INFINITY, s = 0.0f, dm = -INFINITY;
+                        int a = 0x7fffffff, da = 0x7fffffff;
+                        if (t < n) {
 #pragma unroll
-                    for (int i = 0; i < RT; ++i) acc[i] = 0.0f;
-                    wave_dot<WT>(act, H, H, w_out + (size_t)n * H, acc, lane);
-                    const float logit = wave_reduce_select(acc, lane) + p.b_out[n];
-                    if (n <= V) {
-                        if (logit > mlab) {
-                            slab = slab * expf(mlab - logit) + 1.0f;
-                            mlab = logit;
-                            alab = n;
-                        } else {
-                            slab += expf(logit - mlab);
-                        }
-                    } else if (logit > mdur) {
-                        mdur = logit;
-                        adur = n - (V + 1);
-                    }
-                }
-                if (lane < RT) {
-                    float *ws = S.wstats[wave][lane];
-                    ws[0] = mlab;
-                    ws[1] = __int_as_float(alab);
-                    ws[2] = slab;
-                    ws[3] = mdur;
-                    ws[4] = __int_as_float(adur);
-                }
-                __syncthreads();
-                if (wave == 0 && lane < RT && ti * RT + lane < M) {
-                    float m = -INFINITY, s = 0.0f, dm = -INFINITY;
-                    int a = 0, da = 0;
-#pragma unroll
-                    for (int w = 0; w < kWaves; ++w) {
-                        const float *ws = S.wstats[w][lane];
-                        const float wm = ws[0], wsum = ws[2], wd = ws[3];
-                        const int wa = __float_as_int(ws[1]), wda = __float_as_int(ws[4]);
-                        if (wsum > 0.0f) {   // the wavefront saw at least one label column
-                            if (wm > m || (wm == m && wa < a)) {
-                                s = (s > 0.0f ? s * expf(m - wm) : 0.0f) + wsum;
-                                m = wm;
-                                a = wa;
-                            } else {
-                                s += wsum * expf(wm - m);
+                            for (int jj = 0; jj < 4; ++jj) {
+                                const int j = jq * 4 + jj;
+                                const int col = (tile0 + base + t) * CT + j;
+                                const float logit = cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j];
+                                if (col <= V) {
+                                    if (logit > m) {
+                                        s = s * expf(m - logit) + 1.0f;
+                                        m = logit;
+                                        a = col;
+                                    } else {
+                                        s += expf(logit - m);
+                                    }
+                                } else if (col < O && logit > dm) {
+                                    dm = logit;
+                                    da = col - (V + 1);
+                                }
                             }
                         }
-                        if (wd > dm || (wd == dm && wd > -INFINITY && wda < da)) {
-                            dm = wd;
-                            da = wda;
+#pragma unroll
+                        for (int off = 1; off <= 2; off <<= 1) {
+                            const float om = __shfl_xor(m, off, 64), os = __shfl_xor(s, off, 64);
+                            const float odm = __shfl_xor(dm, off, 64);
+                            const int oa = __shfl_xor(a, off, 64), oda = __shfl_xor(da, off, 64);
+                            if (os > 0.0f) {
+                                if (om > m || (om == m && oa < a)) {
+                                    s = (s > 0.0f ? s * expf(m - om) : 0.0f) + os;
+                                    m = om;
+                                    a = oa;
+                                } else {
+                                    s += os * expf(om - m);
+                                }
+                            }
+                            if (odm > dm || (odm == dm && oda < da)) {
+                                dm = odm;
+                                da = oda;
+                            }
                         }
-                    }
-                    const int r = ti * RT + lane;
-                    if (s > 0.0f)
-                        __hip_atomic_fetch_max(row_lab + r, pack_best(m, a), __ATOMIC_RELAXED, TDT_AGENT);
-                    if (dm > -INFINITY)
-                        __hip_atomic_fetch_max(row_dur + r, pack_best(dm, da), __ATOMIC_RELAXED, TDT_AGENT);
-                    const unsigned long long lp = (unsigned long long)__float_as_uint(m) |
-                                                  ((unsigned long long)__float_as_uint(s) << 32);
+                        if (t < n && jq == 0) {
+                            float *ws = S.wstats[t][i];
+                            ws[0] = m;
+                            ws[1] = __int_as_float(a);
+                            ws[2] = s;
+                            ws[3] = dm;
+                            ws[4] = __int_as_float(da);
+                        }
+                        __syncthreads();
+                        if (tid < RT) {   // tiles ascend: '>' keeps the first maximum
+                            for (int tt = 0; tt < n; ++tt) {
+                                const float *ws = S.wstats[tt][tid];
+                                const float wm = ws[0], wsum = ws[2], wd = ws[3];
+                                if (wsum > 0.0f) {
+                                    if (wm > rm) {
+                                        rs = (rs > 0.0f ? rs * expf(rm - wm) : 0.0f) + wsum;
+                                        rm = wm;
+                                        ra = __float_as_int(ws[1]);
+                                    } else {
+                                        rs += wsum * expf(wm - rm);
+                                    }
+                                }
+                                if (wd > rdm) {
+                                    rdm = wd;
+                                    rda = __float_as_int(ws[4]);
+                                }
+                            }
+                        }
+                    });
+                if (tid < RT && ti * RT + tid < M) {
+                    const int r = ti * RT + tid;
+                    if (rs > 0.0f)
+                        __hip_atomic_fetch_max(row_lab + r, pack_best(rm, ra), __ATOMIC_RELAXED, TDT_AGENT);
+                    if (rdm > -INFINITY)
+                        __hip_atomic_fetch_max(row_dur + r, pack_best(rdm, rda), __ATOMIC_RELAXED, TDT_AGENT);
+                    const unsigned long long lp = (unsigned long long)__float_as_uint(rm) |
+                                                  ((unsigned long long)__float_as_uint(rs) << 32);
                     st_co64(reinterpret_cast<unsigned long long *>(pbuf + (size_t)r * n_cg + cg), lp);
                 }
-                __syncthreads();
             }
+            lap(tk_j);
             ok = cluster_barrier(S, bi, p.abort_flag, C, p.timeout_ticks);
+            lap(tk_bar);
             if (!ok) break;
 
             // ---- D: every workgroup takes the same decisions from the same cells
@@ -647,6 +999,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             }
             __syncthreads();
             build_list(S, S.need, G, S.need_list, &S.n_need);
+            lap(tk_d);
         }
         if (!ok) break;
         pp ^= 1;
@@ -660,12 +1013,26 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             p.out_status[b0 + g] = S.status[g];
         }
         if (tid == 0 && p.out_stats) {
-            atomicAdd((unsigned long long *)&p.out_stats[TDT_STAT_PRED_PASSES], (unsigned long long)st_pred_pass);
-            atomicAdd((unsigned long long *)&p.out_stats[TDT_STAT_PRED_ROWS], (unsigned long long)st_pred_rows);
-            atomicAdd((unsigned long long *)&p.out_stats[TDT_STAT_JOINT_PASSES], (unsigned long long)st_joint_pass);
-            atomicAdd((unsigned long long *)&p.out_stats[TDT_STAT_JOINT_ROWS], (unsigned long long)st_joint_rows);
+            auto add = [&](int slot, long long v) {
+                atomicAdd((unsigned long long *)&p.out_stats[slot], (unsigned long long)v);
+            };
+            add(TDT_STAT_PRED_PASSES, st_pred_pass);
+            add(TDT_STAT_PRED_ROWS, st_pred_rows);
+            add(TDT_STAT_JOINT_PASSES, st_joint_pass);
+            add(TDT_STAT_JOINT_ROWS, st_joint_rows);
             atomicMax((unsigned long long *)&p.out_stats[TDT_STAT_OUTER_MAX], (unsigned long long)st_outer);
-            if (!ok) atomicAdd((unsigned long long *)&p.out_stats[TDT_STAT_ABORT], 1ull);
+            if (!ok) add(TDT_STAT_ABORT, 1);
+            if (cl == 0) {   // where the first cluster's time went, in wall-clock ticks
+                add(TDT_STAT_TICKS_PRED, tk_p);
+                add(TDT_STAT_TICKS_PROJ, tk_q);
+                add(TDT_STAT_TICKS_JOINT, tk_j);
+                add(TDT_STAT_TICKS_DECIDE, tk_d);
+                add(TDT_STAT_TICKS_BARRIER, tk_bar);
+                add(TDT_STAT_TICKS_TOTAL, wall_clock64() - tk_start);
+                add(TDT_STAT_TICKS_STAGE, S.tk_stage);
+                add(TDT_STAT_TICKS_MMA, S.tk_mma);
+                add(TDT_STAT_TICKS_EPILOGUE, S.tk_epi);
+            }
         }
     }
 }
@@ -678,15 +1045,19 @@ __global__ void init_kernel(uint4 *zero, size_t n16, long long *out_stats)
     if (out_stats && blockIdx.x == 0 && threadIdx.x < TDT_STAT_COUNT) out_stats[threadIdx.x] = 0;
 }
 
-size_t lds_bytes_for(const tdt_weights_t *w)
+int kseg_max_for(const tdt_weights_t *w)
 {
     int kmax = w->h_joint;
     if (w->h_pred > kmax) kmax = w->h_pred;
-    if (w->pred_kind == TDT_PRED_LSTM) {
-        if (w->emb_dim + w->h_pred > kmax) kmax = w->emb_dim + w->h_pred;
-        if (w->pred_layers > 1 && 2 * w->h_pred > kmax) kmax = 2 * w->h_pred;
-    }
-    return (size_t)RT * kmax * sizeof(float);
+    if (w->pred_kind == TDT_PRED_LSTM && w->emb_dim > kmax) kmax = w->emb_dim;
+    return kmax < KSEG ? kmax : KSEG;
+}
+
+size_t lds_bytes_for(const tdt_weights_t *w)
+{
+    const int k = kseg_max_for(w);
+    if (w->dtype == 1) return (size_t)3 * RT * ActTile<uint16_t>::row_elems(k) * sizeof(uint16_t);
+    return (size_t)RT * ActTile<float>::row_elems(k) * sizeof(float);
 }
 
 }  // namespace
@@ -702,11 +1073,10 @@ hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats
     return hipGetLastError();
 }
 
-int decode_max_grid(int dtype, size_t *lds_bytes_out, const tdt_weights_t *w)
+int decode_max_grid(const tdt_weights_t *w)
 {
     const size_t lds = lds_bytes_for(w);
-    if (lds_bytes_out) *lds_bytes_out = lds;
-    const void *fn = dtype == 1 ? (const void *)decode_kernel<uint16_t> : (const void *)decode_kernel<float>;
+    const void *fn = w->dtype == 1 ? (const void *)decode_kernel<uint16_t> : (const void *)decode_kernel<float>;
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return 0;
@@ -714,7 +1084,7 @@ int decode_max_grid(int dtype, size_t *lds_bytes_out, const tdt_weights_t *w)
     int dev = 0, n_cu = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    hipError_t e = dtype == 1
+    hipError_t e = w->dtype == 1
         ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<uint16_t>, kThreads, lds)
         : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<float>, kThreads, lds);
     if (e != hipSuccess || per_cu < 1) {
@@ -726,18 +1096,13 @@ int decode_max_grid(int dtype, size_t *lds_bytes_out, const tdt_weights_t *w)
     return grid;
 }
 
-hipError_t launch_decode(const DecodeParams &p, int dtype, int grid, hipStream_t stream)
+hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid, hipStream_t stream)
 {
-    tdt_weights_t w{};
-    w.h_joint = p.H;
-    w.h_pred = p.h_pred;
-    w.emb_dim = p.emb_dim;
-    w.pred_kind = p.pred_kind;
-    w.pred_layers = p.pred_layers;
-    const size_t lds = lds_bytes_for(&w);
+    const size_t lds = lds_bytes_for(w);
     DecodeParams pc = p;
+    pc.kseg_max = kseg_max_for(w);
     void *args[] = {&pc};
-    const void *fn = dtype == 1 ? (const void *)decode_kernel<uint16_t> : (const void *)decode_kernel<float>;
+    const void *fn = w->dtype == 1 ? (const void *)decode_kernel<uint16_t> : (const void *)decode_kernel<float>;
     // cooperative launch: the runtime refuses a grid whose workgroups cannot all be
     // resident at once, which is what the cluster barriers rely on
     return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(kThreads), args, (unsigned)lds, stream);

@@ -125,7 +125,7 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
         any_pos |= durations[j] > 0;
     }
     if (!any_pos) return TDT_ERR_DURATIONS;
-    int window = 0, n_clusters = 0;
+    int window = 0, n_clusters = 0, max_items = 0;
     bool reuse_enc_proj = false;
     if (options) {
         for (int r : options->reserved)
@@ -133,14 +133,14 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
         window = options->window;
         n_clusters = options->n_clusters;
         reuse_enc_proj = options->reuse_enc_proj != 0;
-        if (window < 0 || window > kMaxWindow || n_clusters < 0) return TDT_ERR_UNSUPPORTED;
+        max_items = options->max_items;
+        if (window < 0 || window > kMaxWindow || n_clusters < 0 || max_items < 0) return TDT_ERR_UNSUPPORTED;
     }
     const WorkspaceLayout L = workspace_layout(weights, B, T);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < L.total)
         return TDT_ERR_WORKSPACE;
 
-    size_t lds = 0;
-    const int max_grid = decode_max_grid(weights->dtype, &lds, weights);
+    const int max_grid = decode_max_grid(weights);
     if (max_grid < 1) return TDT_ERR_LAUNCH;
     const int min_clusters = (B + kMaxHypsPerCluster - 1) / kMaxHypsPerCluster;
     if (n_clusters == 0) n_clusters = min_clusters;
@@ -173,6 +173,7 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     p.max_symbols = max_symbols;
     p.u_cap = u_cap;
     p.window = window;
+    p.max_items = max_items;
     p.n_clusters = n_clusters;
     p.hyps_per_cluster = (B + n_clusters - 1) / n_clusters;
     for (int j = 0; j < TDT_MAX_DURATIONS; ++j) p.durations[j] = j < weights->n_dur ? durations[j] : 0;
@@ -212,7 +213,7 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
             khz = 100000;
         p.timeout_ticks = 4000LL * khz;
     }
-    if (launch_decode(p, weights->dtype, grid, s) != hipSuccess) return TDT_ERR_LAUNCH;
+    if (launch_decode(p, weights, grid, s) != hipSuccess) return TDT_ERR_LAUNCH;
     return TDT_OK;
 }
 

@@ -12,7 +12,7 @@ constexpr int kThreads = 512;                 // threads per workgroup of the de
 constexpr int kWaves = kThreads / 64;         // 64-wide wavefronts per workgroup
 constexpr int kMaxGrid = 256;                 // one workgroup per compute unit
 constexpr int kMaxHypsPerCluster = 256;       // hypotheses one group of workgroups decodes
-constexpr int kMaxRowsPerPass = 2048;         // (hypothesis, frame) rows of one joint pass
+constexpr int kMaxRowsPerPass = 1024;         // (hypothesis, frame) rows of one joint pass
 constexpr int kMaxColGroups = 64;             // output-column slices of one joint pass
 constexpr int kMaxWindow = 64;                // frames of one hypothesis per joint pass
 constexpr int kPartialEntries = kMaxRowsPerPass * kMaxGrid;  // per partial buffer
@@ -33,6 +33,8 @@ struct DecodeParams {
     int pred_kind, pred_layers, h_pred, emb_dim;
     int max_symbols, u_cap;
     int window;            // 0 = automatic
+    int max_items;         // cap on work items per phase (0 = one per workgroup)
+    int kseg_max;          // longest K segment staged at once (set by launch_decode)
     int n_clusters, hyps_per_cluster;
     int durations[TDT_MAX_DURATIONS];
     // weights
@@ -76,8 +78,8 @@ hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_we
                                      float *out, hipStream_t stream);
 hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats,
                        hipStream_t stream);
-hipError_t launch_decode(const DecodeParams &p, int dtype, int grid, hipStream_t stream);
+hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid, hipStream_t stream);
 // largest grid the decode kernel can run with all workgroups resident, 0 on error
-int decode_max_grid(int dtype, size_t *lds_bytes_out, const tdt_weights_t *w);
+int decode_max_grid(const tdt_weights_t *w);
 
 }  // namespace tdt
