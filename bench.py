@@ -124,6 +124,9 @@ def main():
     ap.add_argument("--clusters", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the B=128 line")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy, so that a rocprofv3 "
+                         "--pmc run of this command holds a dispatch of known HBM traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU (the batch would shard across GPUs without "
@@ -133,6 +136,14 @@ def main():
     from paper_2406_06220_amd import binding, synth
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     binding.load_library()
+
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)           # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg = synth.CONFIGS[args.workload]
     res = time_workload(cfg, args.steps, args.warmup, args.window, args.clusters)

@@ -203,4 +203,4 @@ class Decoder:
         return dict(labels=self.labels.cpu().numpy(), frames=self.frames.cpu().numpy(),
                     len=self.lens.cpu().numpy(), score=self.score.cpu().numpy(),
                     status=self.status.cpu().numpy(),
-                    stats={n: int(st[i]) for n, i in TDT_STAT_NAMES.items()})
+                    stats={n: int(st[i]) for n, i in TDT_STAT_NAMES.items()}, raw_stats=st)

@@ -64,7 +64,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int RT = 16;       // activation rows per tile
 constexpr int CT = 16;       // weight columns per tile
 constexpr int KSEG = 1024;   // longest stretch of the reduction dimension staged at once
-constexpr int MAXSEG = 4;    // K segments per phase (two inputs of up to 2 * KSEG each)
 constexpr int CP_LD = CT + 1;
 
 struct HypShared {
@@ -96,28 +95,35 @@ struct HypShared {
     long long tk_stage, tk_mma, tk_epi;   // thread 0: ticks spent staging / multiplying / in epilogues
 };
 
-// one stretch of the reduction dimension: `K` inputs multiplied by columns
-// [wk0, wk0 + K) of the rows of weight matrix `w` (row stride wld)
+// One stretch of the reduction dimension: `K` inputs, starting at offset k0 of input
+// `part` of the phase, multiplied by columns [k0, k0 + K) of the rows of weight matrix
+// `w` (row stride wld).  A phase has one or two inputs (the LSTM has the layer input and
+// the hidden state); an input longer than KSEG is walked in KSEG pieces.
 struct Seg {
     const void *w;
-    int wld, wk0, K;
-    int part, k0;   // which input of the phase (0 / 1) and the offset inside it
+    int wld, k0, K, part;
 };
 
-__device__ inline int add_segments(Seg *segs, int n, const void *w, int K, int part)
-{
-    for (int k0 = 0; k0 < K && n < MAXSEG; k0 += KSEG) {
-        Seg s;
-        s.w = w;
-        s.wld = K;
-        s.wk0 = k0;
-        s.K = min(KSEG, K - k0);
-        s.part = part;
-        s.k0 = k0;
-        segs[n++] = s;
+struct PhaseInputs {
+    const void *w0, *w1;   // weight matrices of the two inputs (w1 null: one input)
+    int K0, K1;
+    __device__ int count() const
+    {
+        return (K0 + KSEG - 1) / KSEG + (w1 ? (K1 + KSEG - 1) / KSEG : 0);
     }
-    return n;
-}
+    __device__ Seg get(int i) const   // i < count(); branch-free enough to stay in registers
+    {
+        const int n0 = (K0 + KSEG - 1) / KSEG;
+        const bool first = i < n0;
+        Seg s;
+        s.part = first ? 0 : 1;
+        s.w = first ? w0 : w1;
+        s.wld = first ? K0 : K1;
+        s.k0 = (first ? i : i - n0) * KSEG;
+        s.K = min(KSEG, s.wld - s.k0);
+        return s;
+    }
+};
 
 // ---- number formats
 template <typename WT> __device__ inline float2 load_w2(const WT *p);
@@ -359,7 +365,7 @@ __device__ inline WeightCursor weight_cursor(const Seg &sg, long long wrow, int 
     WeightCursor wc;
     wc.kq = (lane >> 4) * 8;
     wc.live = wrow >= 0;
-    wc.wr = static_cast<const uint16_t *>(sg.w) + (wc.live ? wrow : 0) * sg.wld + sg.wk0;
+    wc.wr = static_cast<const uint16_t *>(sg.w) + (wc.live ? wrow : 0) * sg.wld + sg.k0;
     const int nsteps = (sg.K + 31) / 32;
     wc.n_my = nsteps > kpart ? (nsteps - kpart + ksplit - 1) / ksplit : 0;
     return wc;
@@ -410,7 +416,7 @@ __device__ inline float column_dot(const ActTile<float> &A, const Seg &sg, long 
 #pragma unroll
     for (int i = 0; i < RT; ++i) acc[i] = 0.0f;
     if (wrow >= 0) {
-        const float *w = static_cast<const float *>(sg.w) + wrow * sg.wld + sg.wk0;
+        const float *w = static_cast<const float *>(sg.w) + wrow * sg.wld + sg.k0;
         for (int k = lane * 2; k < sg.K; k += 128) {
             const float2 wv = *reinterpret_cast<const float2 *>(w + k);
 #pragma unroll
@@ -484,7 +490,7 @@ template <> struct Backend<float> {
 
 // One work item: all K segments of the staged rows against n_ct column tiles, a round of
 // (8 / ksplit) column tiles at a time.
-//   stage(seg)                     stages segment seg of the item's rows (stage_segment)
+//   stage(seg)                     stages Seg seg of the item's rows (stage_segment)
 //   rowidx(ct, j)    -> long long  weight row of column j of column tile ct, -1 if none
 //   epi(ct0, n, ksplit)            called by all threads once S.cpart holds round results:
 //                                  tile slot t (< n) is the sum over kp < ksplit of
@@ -493,10 +499,11 @@ template <> struct Backend<float> {
 // With one segment the rows are staged once; with several they are staged again for
 // every round.
 template <typename WT, typename StageF, typename RowF, typename EpiF>
-__device__ inline void run_item(HypShared &S, const ActTile<WT> &A, int nseg, const Seg *segs, int n_ct,
+__device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseInputs &in, int n_ct,
                                 const float *__restrict__ bias, StageF stage, RowF rowidx, EpiF epi)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nseg = in.count();
     const int ksplit = Backend<WT>::ksplit_for(n_ct);
     const int tpr = kWaves / ksplit;          // column tiles per round
     const int tslot = wave / ksplit, kpart = wave % ksplit;
@@ -510,7 +517,7 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, int nseg, co
             S.bias[threadIdx.x] = r >= 0 ? bias[r] : 0.0f;
         }
         for (int sgi = 0; sgi < nseg; ++sgi) {
-            const Seg sg = segs[sgi];
+            const Seg sg = in.get(sgi);
             long long tq = 0;
             if (TDT_FINE_TIMERS && threadIdx.x == 0) tq = wall_clock64();
             typename Backend<WT>::Pre pre;
@@ -518,7 +525,7 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, int nseg, co
             if (mine) Backend<WT>::prefetch(pre, sg, rowidx, ct, kpart, ksplit, lane);
             if (nseg > 1 || base == 0) {
                 __syncthreads();   // previous readers of the tile are done
-                stage(sgi);
+                stage(sg);
                 __syncthreads();
             }
             if (TDT_FINE_TIMERS && threadIdx.x == 0) { const long long n = wall_clock64(); S.tk_stage += n - tq; tq = n; }
@@ -635,9 +642,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L + l) * B * Hp;
                 const float *x_prev = l > 0 ? p.hbuf + ((size_t)(pp ^ 1) * L + (l - 1)) * B * Hp : nullptr;
                 float *cst = p.cbuf + (size_t)l * B * Hp;
-                Seg segs[MAXSEG];
-                int nseg = add_segments(segs, 0, p.w_ih[l], in_dim, 0);
-                nseg = add_segments(segs, nseg, p.w_hh[l], Hp, 1);
+                PhaseInputs in;
+                in.w0 = p.w_ih[l];
+                in.K0 = in_dim;
+                in.w1 = p.w_hh[l];
+                in.K1 = Hp;
                 const int NT = (Hp + 3) / 4;   // a column tile = 4 hidden units x 4 gates
                 int n_ug, tpg;
                 split_tiles(Csplit, n_tiles_a, NT, NT, n_ug, tpg);
@@ -646,19 +655,19 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     const int nrows = min(RT, n_act - ti * RT);
                     const int tile0 = ug * tpg, n_ct = min(tpg, NT - tile0);
                     run_item<WT>(
-                        S, A, nseg, segs, n_ct, bl,
-                        [&](int sgi) {
-                            const int k0 = segs[sgi].k0;
-                            if (segs[sgi].part == 1 || l > 0) {   // hidden state: coherent loads
-                                const float *src = segs[sgi].part == 1 ? h_cur : x_prev;
-                                stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                        S, A, in, n_ct, bl,
+                        [&](const Seg &sg) {
+                            const int k0 = sg.k0;
+                            if (sg.part == 1 || l > 0) {   // hidden state: coherent loads
+                                const float *src = sg.part == 1 ? h_cur : x_prev;
+                                stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
                                     const bool valid = i < nrows;
                                     const int g = S.act_list[ti * RT + (valid ? i : 0)];
                                     const float2 x = ld_co2(src + (size_t)(b0 + g) * Hp + k0 + k);
                                     return make_float2(valid ? x.x : 0.0f, valid ? x.y : 0.0f);
                                 });
-                            } else {                              // embedding of the last label
-                                stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                            } else {                       // embedding of the last label
+                                stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
                                     const bool valid = i < nrows;
                                     const int g = S.act_list[ti * RT + (valid ? i : 0)];
                                     const float2 x = load_w2<WT>(static_cast<const WT *>(p.emb) +
@@ -700,8 +709,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         // ---- Q: predictor output into the joint space (Sec. 3.4)
         {
             const float *dec_src = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * B * Hp : nullptr;
-            Seg segs[MAXSEG];
-            const int nseg = add_segments(segs, 0, p.w_pred, Hp, 0);
+            PhaseInputs in;
+            in.w0 = p.w_pred;
+            in.K0 = Hp;
+            in.w1 = nullptr;
+            in.K1 = 0;
             const int NT = (H + CT - 1) / CT;
             int n_cg, tpg;
             split_tiles(Csplit, n_tiles_a, NT, NT, n_cg, tpg);
@@ -710,11 +722,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 const int nrows = min(RT, n_act - ti * RT);
                 const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
                 run_item<WT>(
-                    S, A, nseg, segs, n_ct, p.b_pred,
-                    [&](int sgi) {
-                        const int k0 = segs[sgi].k0;
+                    S, A, in, n_ct, p.b_pred,
+                    [&](const Seg &sg) {
+                        const int k0 = sg.k0;
                         if (lstm) {
-                            stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                            stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
                                 const bool valid = i < nrows;
                                 const int g = S.act_list[ti * RT + (valid ? i : 0)];
                                 const float2 x = ld_co2(dec_src + (size_t)(b0 + g) * Hp + k0 + k);
@@ -722,7 +734,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             });
                         } else {
                             // stateless: table L-1 embeds the newest label, table 0 the older one
-                            stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                            stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
                                 const bool valid = i < nrows;
                                 const int g = S.act_list[ti * RT + (valid ? i : 0)];
                                 const int kk = k0 + k, c = kk / E;
@@ -787,8 +799,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             st_joint_rows += M;
 
             // ---- J: joint network on M rows
-            Seg segs[MAXSEG];
-            const int nseg = add_segments(segs, 0, p.w_out, H, 0);
+            PhaseInputs in;
+            in.w0 = p.w_out;
+            in.K0 = H;
+            in.w1 = nullptr;
+            in.K1 = 0;
             for (int it = rank; it < n_tiles * n_cg; it += C) {
                 const int ti = it / n_cg, cg = it % n_cg;
                 const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
@@ -796,10 +811,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 float rm = -INFINITY, rs = 0.0f, rdm = -INFINITY;
                 int ra = 0, rda = 0;
                 run_item<WT>(
-                    S, A, nseg, segs, n_ct, p.b_out,
-                    [&](int sgi) {
-                        const int k0 = segs[sgi].k0;
-                        stage_segment<WT>(A, segs[sgi].K, [&](int i, int k) -> float2 {
+                    S, A, in, n_ct, p.b_out,
+                    [&](const Seg &sg) {
+                        const int k0 = sg.k0;
+                        stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
                             const int r = min(ti * RT + i, M - 1);
                             const int g = S.need_list[r / Kw];
                             const int f = S.time[g] + r % Kw;

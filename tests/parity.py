@@ -10,6 +10,7 @@ the caller.
 """
 from __future__ import annotations
 
+import os
 import sys
 
 import numpy as np
@@ -18,10 +19,23 @@ TOL_MARGIN = 1e-3
 TOL_SCORE = 1e-3
 
 
+_CASE_LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out",
+                         "gpu_cases.log")
+
+
 def announce(msg: str) -> None:
-    """Name the case on the real stderr before a GPU step (survives output capture)."""
+    """Name the case before a GPU step: on the real stderr, and appended (flushed to disk) to
+    gpurun_out/gpu_cases.log, so that the last line names the case if the process dies."""
     sys.__stderr__.write("[gpu-case] " + msg + "\n")
     sys.__stderr__.flush()
+    try:
+        os.makedirs(os.path.dirname(_CASE_LOG), exist_ok=True)
+        with open(_CASE_LOG, "a") as f:
+            f.write(msg + "\n")
+            f.flush()
+            os.fsync(f.fileno())
+    except OSError:
+        pass
 
 
 def compare(oracle, omodel, cfg, enc, enc_len, gpu: dict, u_cap: int, rows=None,
