@@ -65,6 +65,8 @@ constexpr int RT = 16;       // activation rows per tile
 constexpr int CT = 16;       // weight columns per tile
 constexpr int KSEG = 1024;   // longest stretch of the reduction dimension staged at once
 constexpr int CP_LD = CT + 1;
+constexpr int kDeferPerWave = 4;                     // hypotheses per wavefront whose score term may be deferred
+constexpr int kDeferred = kDeferPerWave * kWaves;
 
 struct HypShared {
     int len[kMaxHypsPerCluster];
@@ -85,11 +87,16 @@ struct HypShared {
     float cpart[kWaves][RT][CP_LD];  // per-wavefront 16x16 partial results of one round
     float wstats[kWaves][RT][5];     // per column tile of a round: row statistics
     float bias[kWaves * CT];         // biases of the columns of the current round
+    float tab[kWaves][RT][CP_LD];    // per (row, column) addends of the current round (LSTM layer 0)
     int row_a[kMaxRowsPerPass];      // per joint row: argmax label (V = blank)
     int row_d[kMaxRowsPerPass];      //                frame step of the argmax duration class
     float row_m[kMaxRowsPerPass];    //                largest label logit
     int dec_w[kMaxHypsPerCluster];   // per searching hypothesis: window offset the walk stopped at
     unsigned char dec_found[kMaxHypsPerCluster];   // ... on a non-blank label
+    int pend_n, pend_ncg;            // hypotheses whose score term is still in flight
+    int pend_g[kDeferred];
+    float pend_m[kDeferred];
+    unsigned char pend_found[kDeferred];
     unsigned epoch;
     int aborted;
     long long tk_stage, tk_mma, tk_epi;   // thread 0: ticks spent staging / multiplying / in epilogues
@@ -305,24 +312,25 @@ template <> struct ActTile<float> {
 // stage one K segment: f(i, k) gives the two inputs (k, k+1) of row i; the tail up to a
 // multiple of 32 is zero-filled.  All loads of a wavefront are issued before the first
 // value is used, so that their latencies overlap.
-template <typename WT, typename F>
-__device__ inline void stage_segment(const ActTile<WT> &A, int K, F f)
+// f is called with in-range (i, k) only and must itself be free of branches around its
+// loads (clamp the address, mask the value): a load inside a conditional block is waited
+// for before the next one is issued.  For the same reason rows beyond nrows re-read row 0
+// and steps beyond K re-read the last step instead of being skipped.
+template <typename WT, int KIT, typename F>
+__device__ inline void stage_segment_impl(const ActTile<WT> &A, int K, int nrows, F f)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int Kpad = ((K + 31) / 32) * 32;
     constexpr int RPW = RT / kWaves;    // rows per wavefront
-    constexpr int KIT = KSEG / 128;     // 64 lanes x 2 inputs per step
-    // f is called with in-range (i, k) only and must itself be free of branches around its
-    // loads (clamp the address, mask the value): a load inside a conditional block would be
-    // waited for before the next one is issued
     float2 v[RPW][KIT];
 #pragma unroll
     for (int ii = 0; ii < RPW; ++ii)
 #pragma unroll
         for (int kk = 0; kk < KIT; ++kk) {
-            const int k = lane * 2 + kk * 128;
-            const float2 x = f(wave + ii * kWaves, k < K ? k : K - 2);
-            v[ii][kk] = make_float2(k < K ? x.x : 0.0f, k < K ? x.y : 0.0f);
+            const int i = wave + ii * kWaves, k = lane * 2 + kk * 128;
+            const bool ok = i < nrows && k < K;
+            const float2 x = f(i < nrows ? i : 0, k < K ? k : K - 2);
+            v[ii][kk] = make_float2(ok ? x.x : 0.0f, ok ? x.y : 0.0f);
         }
 #pragma unroll
     for (int ii = 0; ii < RPW; ++ii)
@@ -331,6 +339,14 @@ __device__ inline void stage_segment(const ActTile<WT> &A, int K, F f)
             const int k = lane * 2 + kk * 128;
             if (k < Kpad) A.store2(wave + ii * kWaves, k, v[ii][kk]);
         }
+}
+
+template <typename WT, typename F>
+__device__ inline void stage_segment(const ActTile<WT> &A, int K, int nrows, F f)
+{
+    // 64 lanes x 2 inputs per step: pick the unrolling that covers K without spare loads
+    if (K <= 640) stage_segment_impl<WT, 5>(A, K, nrows, f);
+    else stage_segment_impl<WT, KSEG / 128>(A, K, nrows, f);
 }
 
 // accumulators of one wavefront for one 16x16 tile
@@ -352,7 +368,7 @@ template <> struct Accum<float> {
 // of one segment to the 16x16 tile whose 16 weight rows are given per lane (l % 16).
 // The first chunk of weight fragments can be fetched ahead (before the activations are
 // staged) with weight_prefetch.
-constexpr int CH = 4;   // weight fragments in flight per wavefront
+constexpr int CH = 5;   // weight fragments in flight per wavefront
 
 struct WeightCursor {
     const uint16_t *wr;   // this lane's weight row at its k-quarter (row 0 if the column is padding)
@@ -492,18 +508,23 @@ template <> struct Backend<float> {
 // (8 / ksplit) column tiles at a time.
 //   stage(seg)                     stages Seg seg of the item's rows (stage_segment)
 //   rowidx(ct, j)    -> long long  weight row of column j of column tile ct, -1 if none
+//   pre(ct0, n)                    called by all threads at the start of a round, before the
+//                                  rows are staged: loads whose latency should hide there
 //   epi(ct0, n, ksplit)            called by all threads once S.cpart holds round results:
 //                                  tile slot t (< n) is the sum over kp < ksplit of
 //                                  S.cpart[t * ksplit + kp]; S.bias[t * 16 + j] is
 //                                  bias[rowidx(ct0 + t, j)]
 // With one segment the rows are staged once; with several they are staged again for
 // every round.
-template <typename WT, typename StageF, typename RowF, typename EpiF>
+template <typename WT, typename StageF, typename RowF, typename PreF, typename EpiF>
 __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseInputs &in, int n_ct,
-                                const float *__restrict__ bias, StageF stage, RowF rowidx, EpiF epi)
+                                const float *__restrict__ bias, const float *any_floats, StageF stage,
+                                RowF rowidx, PreF pre_round, EpiF epi)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nseg = in.count();
+    // always a readable float array with at least as many entries as there are weight rows
+    const float *bias_or_any = bias ? bias : static_cast<const float *>(any_floats);
     const int ksplit = Backend<WT>::ksplit_for(n_ct);
     const int tpr = kWaves / ksplit;          // column tiles per round
     const int tslot = wave / ksplit, kpart = wave % ksplit;
@@ -512,10 +533,16 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
         const bool mine = ct < n_ct;
         Accum<WT> acc;
         acc.clear();
-        if (threadIdx.x < tpr * CT) {   // read before the epilogue, behind two barriers
-            const long long r = base + (int)threadIdx.x / CT < n_ct ? rowidx(base + (int)threadIdx.x / CT, (int)threadIdx.x % CT) : -1;
-            S.bias[threadIdx.x] = r >= 0 ? bias[r] : 0.0f;
+        // bias of column (threadIdx.x % 16) of tile slot (threadIdx.x / 16): the load is issued
+        // here, unconditionally, and parked in LDS only after the rows have been staged
+        float bias_v;
+        {
+            const int bt = (int)(threadIdx.x % (kWaves * CT)) / CT, bj = (int)threadIdx.x % CT;
+            const long long r = base + bt < n_ct ? rowidx(base + bt, bj) : -1;
+            bias_v = bias_or_any[r >= 0 ? r : 0];
+            if (r < 0 || !bias) bias_v = 0.0f;
         }
+        pre_round(base, min(tpr, n_ct - base));
         for (int sgi = 0; sgi < nseg; ++sgi) {
             const Seg sg = in.get(sgi);
             long long tq = 0;
@@ -535,6 +562,7 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
         long long tq = 0;
         if (TDT_FINE_TIMERS && threadIdx.x == 0) tq = wall_clock64();
         if (mine) Backend<WT>::spill(S, acc, wave, lane);
+        if (threadIdx.x < kWaves * CT) S.bias[threadIdx.x] = bias_v;
         __syncthreads();
         epi(base, min(tpr, n_ct - base), ksplit);
         __syncthreads();
@@ -608,7 +636,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         S.need[g] = 0;
     }
     if (tid < TDT_MAX_DURATIONS) S.durations[tid] = p.durations[tid];
-    if (tid == 0) { S.epoch = 0; S.aborted = 0; S.tk_stage = S.tk_mma = S.tk_epi = 0; }
+    if (tid == 0) { S.epoch = 0; S.aborted = 0; S.tk_stage = S.tk_mma = S.tk_epi = 0; S.pend_n = 0; S.pend_ncg = 0; }
     __syncthreads();
 
     long long st_pred_pass = 0, st_pred_rows = 0, st_joint_pass = 0, st_joint_rows = 0, st_outer = 0;
@@ -619,6 +647,31 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         const long long now = wall_clock64();
         bucket += now - tk0;
         tk0 = now;
+    };
+    // softmax partials of the rows chosen in the last decision step, still to be summed
+    unsigned long long pend_u[kDeferPerWave];
+#pragma unroll
+    for (int j = 0; j < kDeferPerWave; ++j) pend_u[j] = 0ull;
+    auto finish_scores = [&]() {   // all threads; the loads were issued a phase ago
+        const int n = S.pend_n, ncg = S.pend_ncg;
+#pragma unroll
+        for (int j = 0; j < kDeferPerWave; ++j) {
+            const int q = wave + j * kWaves;
+            if (q < n && S.pend_found[q]) {   // uniform over the wavefront
+                float part = 0.0f;
+                if (lane < ncg) {
+                    const float pm = __uint_as_float((unsigned)pend_u[j]);
+                    const float ps = __uint_as_float((unsigned)(pend_u[j] >> 32));
+                    if (ps > 0.0f) part = ps * expf(pm - S.pend_m[q]);
+                }
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+                // log_softmax at the maximum = -log(sum exp(l - max))
+                if (lane == 0) S.score[S.pend_g[q]] -= logf(part);
+            }
+        }
+        __syncthreads();
+        if (tid == 0) S.pend_n = 0;
     };
     int pp = 0;          // which half of hbuf holds the current hidden state
     unsigned jpass = 0;  // joint passes so far (selects the exchange buffers)
@@ -642,11 +695,15 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L + l) * B * Hp;
                 const float *x_prev = l > 0 ? p.hbuf + ((size_t)(pp ^ 1) * L + (l - 1)) * B * Hp : nullptr;
                 float *cst = p.cbuf + (size_t)l * B * Hp;
+                // Layer 0: W_ih * emb[label] + b is a row of the table the host-side call built
+                // before this kernel, so only the recurrent product is left.
+                const bool folded = l == 0;
+                const float *gate_tab = p.emb_gates;   // [V+1][4*Hp]
                 PhaseInputs in;
-                in.w0 = p.w_ih[l];
-                in.K0 = in_dim;
-                in.w1 = p.w_hh[l];
-                in.K1 = Hp;
+                in.w0 = folded ? p.w_hh[l] : p.w_ih[l];
+                in.K0 = folded ? Hp : in_dim;
+                in.w1 = folded ? nullptr : p.w_hh[l];
+                in.K1 = folded ? 0 : Hp;
                 const int NT = (Hp + 3) / 4;   // a column tile = 4 hidden units x 4 gates
                 int n_ug, tpg;
                 split_tiles(Csplit, n_tiles_a, NT, NT, n_ug, tpg);
@@ -654,31 +711,43 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     const int ti = it / n_ug, ug = it % n_ug;
                     const int nrows = min(RT, n_act - ti * RT);
                     const int tile0 = ug * tpg, n_ct = min(tpg, NT - tile0);
+                    float c_old = 0.0f;   // this thread's cell value, fetched ahead of the epilogue
                     run_item<WT>(
-                        S, A, in, n_ct, bl,
+                        S, A, in, n_ct, folded ? nullptr : bl, bl,
                         [&](const Seg &sg) {
                             const int k0 = sg.k0;
-                            if (sg.part == 1 || l > 0) {   // hidden state: coherent loads
-                                const float *src = sg.part == 1 ? h_cur : x_prev;
-                                stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
-                                    const bool valid = i < nrows;
-                                    const int g = S.act_list[ti * RT + (valid ? i : 0)];
-                                    const float2 x = ld_co2(src + (size_t)(b0 + g) * Hp + k0 + k);
-                                    return make_float2(valid ? x.x : 0.0f, valid ? x.y : 0.0f);
-                                });
-                            } else {                       // embedding of the last label
-                                stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
-                                    const bool valid = i < nrows;
-                                    const int g = S.act_list[ti * RT + (valid ? i : 0)];
-                                    const float2 x = load_w2<WT>(static_cast<const WT *>(p.emb) +
-                                                                 (size_t)S.last[g] * E + k0 + k);
-                                    return make_float2(valid ? x.x : 0.0f, valid ? x.y : 0.0f);
-                                });
-                            }
+                            const float *src = (folded || sg.part == 1) ? h_cur : x_prev;
+                            stage_segment<WT>(A, sg.K, nrows, [&](int i, int k) -> float2 {
+                                const int g = S.act_list[ti * RT + i];
+                                return ld_co2(src + (size_t)(b0 + g) * Hp + k0 + k);
+                            });
                         },
                         [&](int ct, int j) -> long long {
                             const int unit = (tile0 + ct) * 4 + (j >> 2);
                             return unit < Hp ? (long long)(j & 3) * Hp + unit : -1;
+                        },
+                        [&](int base, int n) {
+                            {   // thread -> (tile slot, row, unit) as in the epilogue
+                                const int t = tid >> 6, i = (tid & 63) >> 2, uq = tid & 3;
+                                const int unit = (tile0 + base + t) * 4 + uq;
+                                const bool live = t < n && i < nrows && unit < Hp;
+                                const int g = S.act_list[ti * RT + (i < nrows ? i : 0)];
+                                const float c = ld_co(cst + (size_t)(b0 + g) * Hp + (unit < Hp ? unit : 0));
+                                c_old = live ? c : 0.0f;
+                            }
+                            if (folded) {   // addends of (row i, column j) of every tile of the round
+#pragma unroll
+                                for (int e = 0; e < kWaves * RT * CT / kThreads; ++e) {
+                                    const int idx = tid + e * kThreads;
+                                    const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
+                                    const int unit = (tile0 + base + t) * 4 + (j >> 2);
+                                    const bool live = t < n && i < nrows && unit < Hp;
+                                    const int g = S.act_list[ti * RT + (i < nrows ? i : 0)];
+                                    const float v = gate_tab[(size_t)S.last[g] * (4 * Hp) + (size_t)(j & 3) * Hp +
+                                                             (unit < Hp ? unit : 0)];
+                                    S.tab[t][i][j] = live ? v : 0.0f;
+                                }
+                            }
                         },
                         [&](int base, int n, int ksplit) {
                             // thread -> (tile slot, row, unit): all four gates, then the cell update
@@ -688,12 +757,13 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 float gate[4];
 #pragma unroll
                                 for (int q = 0; q < 4; ++q)
-                                    gate[q] = cpart_sum(S, t, ksplit, i, uq * 4 + q) + S.bias[t * CT + uq * 4 + q];
+                                    gate[q] = cpart_sum(S, t, ksplit, i, uq * 4 + q) + S.bias[t * CT + uq * 4 + q] +
+                                              (folded ? S.tab[t][i][uq * 4 + q] : 0.0f);
                                 const int g = S.act_list[ti * RT + i];
                                 const size_t o = (size_t)(b0 + g) * Hp + unit;
                                 const float ig = sigmoidf_dev(gate[0]), fg = sigmoidf_dev(gate[1]);
                                 const float gg = tanhf(gate[2]), og = sigmoidf_dev(gate[3]);
-                                const float cn = fg * ld_co(cst + o) + ig * gg;
+                                const float cn = fg * c_old + ig * gg;
                                 st_co(cst + o, cn);
                                 st_co(h_next + o, og * tanhf(cn));
                             }
@@ -722,26 +792,22 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 const int nrows = min(RT, n_act - ti * RT);
                 const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
                 run_item<WT>(
-                    S, A, in, n_ct, p.b_pred,
+                    S, A, in, n_ct, p.b_pred, p.b_pred,
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
                         if (lstm) {
-                            stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
-                                const bool valid = i < nrows;
-                                const int g = S.act_list[ti * RT + (valid ? i : 0)];
-                                const float2 x = ld_co2(dec_src + (size_t)(b0 + g) * Hp + k0 + k);
-                                return make_float2(valid ? x.x : 0.0f, valid ? x.y : 0.0f);
+                            stage_segment<WT>(A, sg.K, nrows, [&](int i, int k) -> float2 {
+                                const int g = S.act_list[ti * RT + i];
+                                return ld_co2(dec_src + (size_t)(b0 + g) * Hp + k0 + k);
                             });
                         } else {
                             // stateless: table L-1 embeds the newest label, table 0 the older one
-                            stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
-                                const bool valid = i < nrows;
-                                const int g = S.act_list[ti * RT + (valid ? i : 0)];
+                            stage_segment<WT>(A, sg.K, nrows, [&](int i, int k) -> float2 {
+                                const int g = S.act_list[ti * RT + i];
                                 const int kk = k0 + k, c = kk / E;
                                 const int tok = (c == L - 1) ? S.last[g] : S.last2[g];
-                                const float2 x = load_w2<WT>(static_cast<const WT *>(p.emb) +
-                                                             ((size_t)c * (V + 1) + tok) * E + (kk - c * E));
-                                return make_float2(valid ? x.x : 0.0f, valid ? x.y : 0.0f);
+                                return load_w2<WT>(static_cast<const WT *>(p.emb) +
+                                                   ((size_t)c * (V + 1) + tok) * E + (kk - c * E));
                             });
                         }
                     },
@@ -749,6 +815,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         const int n = (tile0 + ct) * CT + j;
                         return n < H ? n : -1;
                     },
+                    [&](int, int) {},
                     [&](int base, int n, int ksplit) {
                         for (int idx = tid; idx < n * RT * CT; idx += kThreads) {
                             const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
@@ -773,13 +840,22 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         // ---- inner loop (Alg. 3 line 12): joint passes until nobody searches any more
         while (S.n_need > 0) {
             const int n_need = S.n_need;
-            int Kw = p.window > 0 ? p.window : 512 / n_need;
-            if (Kw < 8 && p.window <= 0) Kw = 8;
+            const int NT = (O + CT - 1) / CT;
+            // Automatic window: as many rows as give every workgroup at most one work item of
+            // at most `tiles_per_item` column tiles (then one round, all wavefronts busy).
+            int Kw = p.window;
+            if (Kw <= 0) {
+                const int tiles_per_item = p.row_budget_tiles > 0 ? p.row_budget_tiles : 4;
+                const int groups = (NT + tiles_per_item - 1) / tiles_per_item;
+                int row_tiles = Csplit / groups;
+                if (row_tiles < 1) row_tiles = 1;
+                Kw = row_tiles * RT / n_need;
+                if (Kw < 4) Kw = 4;
+            }
             if (Kw > kMaxWindow) Kw = kMaxWindow;
             if (Kw * n_need > rows_cap) Kw = rows_cap / n_need;
             const int M = n_need * Kw;
             const int n_tiles = (M + RT - 1) / RT;
-            const int NT = (O + CT - 1) / CT;
             int n_cg, tpg;
             split_tiles(Csplit, n_tiles, NT, max_cg, n_cg, tpg);
             LsePartial *pbuf = pbase + (size_t)(jpass & 1u) * kPartialEntries;
@@ -811,14 +887,14 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 float rm = -INFINITY, rs = 0.0f, rdm = -INFINITY;
                 int ra = 0, rda = 0;
                 run_item<WT>(
-                    S, A, in, n_ct, p.b_out,
+                    S, A, in, n_ct, p.b_out, p.b_out,
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
-                        stage_segment<WT>(A, sg.K, [&](int i, int k) -> float2 {
-                            const int r = min(ti * RT + i, M - 1);
+                        stage_segment<WT>(A, sg.K, min(RT, M - ti * RT), [&](int i, int k) -> float2 {
+                            const int r = ti * RT + i;
                             const int g = S.need_list[r / Kw];
                             const int f = S.time[g] + r % Kw;
-                            const bool valid = ti * RT + i < M && f < S.len[g];
+                            const bool valid = f < S.len[g];
                             const float2 e2 = *reinterpret_cast<const float2 *>(
                                 p.enc_proj + ((size_t)(b0 + g) * T + (valid ? f : 0)) * H + k0 + k);
                             const float2 p2 = ld_co2(p.pred_proj + (size_t)(b0 + g) * H + k0 + k);
@@ -830,6 +906,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         const int n = (tile0 + ct) * CT + j;
                         return n < O ? n : -1;
                     },
+                    [&](int, int) {},
                     [&](int base, int n, int ksplit) {
                         // four threads share (tile slot t, row i), four columns each; lower
                         // columns win ties, so the first maximum is kept
@@ -922,17 +999,32 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 
             // ---- D: every workgroup takes the same decisions from the same cells
             // D1: one coherent load per row, all rows in flight together
-            for (int r = tid; r < M; r += kThreads) {
-                const unsigned long long best = ld_co64(row_lab + r);
-                unsigned long long bd = 0ull;
-                if (D > 0) bd = ld_co64(row_dur + r);
-                S.row_a[r] = best ? unpack_index(best) : V;
-                S.row_m[r] = unpack_value(best);
-                S.row_d[r] = D > 0 ? S.durations[unpack_index(bd) & (TDT_MAX_DURATIONS - 1)] : 0;
+            {
+                unsigned long long best[kMaxRowsPerPass / kThreads], bd[kMaxRowsPerPass / kThreads];
+#pragma unroll
+                for (int e = 0; e < kMaxRowsPerPass / kThreads; ++e) {
+                    const int r = tid + e * kThreads;
+                    best[e] = bd[e] = 0ull;
+                    if (e * kThreads < M) {   // uniform
+                        best[e] = ld_co64(row_lab + (r < M ? r : 0));
+                        if (D > 0) bd[e] = ld_co64(row_dur + (r < M ? r : 0));
+                    }
+                }
+                // while they are in flight: the score terms the previous pass left pending
+                finish_scores();
+#pragma unroll
+                for (int e = 0; e < kMaxRowsPerPass / kThreads; ++e) {
+                    const int r = tid + e * kThreads;
+                    if (r < M) {
+                        S.row_a[r] = best[e] ? unpack_index(best[e]) : V;
+                        S.row_m[r] = unpack_value(best[e]);
+                        S.row_d[r] = D > 0 ? S.durations[unpack_index(bd[e]) & (TDT_MAX_DURATIONS - 1)] : 0;
+                    }
+                }
             }
             __syncthreads();
-            // D2: walk each searching hypothesis through its window
-            for (int q = wave; q < n_need; q += kWaves) {
+            // the walk through the window of one searching hypothesis (all lanes of a wavefront)
+            auto walk = [&](int q, int &w) -> bool {
                 const int g = S.need_list[q];
                 const int nv = min(Kw, S.len[g] - S.time[g]);   // >= 1: a searching row has frames left
                 int a = V, dstep = 0;
@@ -940,7 +1032,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     a = S.row_a[q * Kw + lane];
                     dstep = S.row_d[q * Kw + lane];
                 }
-                int w = 0;
+                w = 0;
                 bool found = false;
                 if (D == 0) {   // Alg. 3 lines 10 / 18: a blank moves one frame on
                     const unsigned long long nb = __ballot(lane < nv && a != V);
@@ -952,15 +1044,76 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         w += dd > 0 ? dd : 1;
                     }
                 }
-                if (lane == 0) {
-                    S.dec_w[q] = w;
-                    S.dec_found[q] = found;
+                return found;
+            };
+            // the state update of one hypothesis (one thread): Alg. 3 line 20, Sec. 3.1 add_results
+            auto apply = [&](int q, bool found, int w) {
+                const int g = S.need_list[q];
+                const int t0 = S.time[g], len = S.len[g];
+                int sym = (w > 0 || !found) ? 0 : S.sym[g];
+                if (found) {
+                    const int k = S.row_a[q * Kw + w];
+                    int dk = S.row_d[q * Kw + w];
+                    const int frame = t0 + w, n = S.out_len[g];
+                    if (rank == 0) {
+                        p.out_labels[(size_t)(b0 + g) * p.u_cap + n] = k;
+                        p.out_frames[(size_t)(b0 + g) * p.u_cap + n] = frame;
+                    }
+                    S.out_len[g] = n + 1;
+                    S.last2[g] = S.last[g];
+                    S.last[g] = k;
+                    sym += 1;
+                    if (dk == 0 && sym >= p.max_symbols) dk = 1;
+                    int t1 = frame;
+                    if (dk > 0) { t1 = frame + dk; sym = 0; }
+                    S.time[g] = t1;
+                    bool act_now = t1 < len;
+                    if (n + 1 >= p.u_cap) { act_now = false; S.status[g] |= TDT_HYP_TRUNCATED; }
+                    S.active[g] = act_now;
+                    S.need[g] = 0;
+                } else {
+                    const int t1 = t0 + w;
+                    S.time[g] = t1;
+                    S.active[g] = t1 < len;
+                    S.need[g] = t1 < len;
                 }
-            }
-            __syncthreads();
-            // D3: softmax denominator of each chosen row, then the state update (Alg. 3 line 20,
-            // Sec. 3.1 add_results); a segment of seg lanes serves one hypothesis
-            {
+                S.sym[g] = sym;
+            };
+            if (n_need <= kDeferred) {
+                // D2: a wavefront per hypothesis walks, updates the state and only issues the
+                // loads of the chosen row's softmax partials; the score term is added later
+#pragma unroll
+                for (int j = 0; j < kDeferPerWave; ++j) {
+                    const int q = wave + j * kWaves;
+                    if (q < n_need) {   // uniform over the wavefront
+                        int w;
+                        const bool found = walk(q, w);
+                        pend_u[j] = 0ull;
+                        if (found && lane < n_cg)
+                            pend_u[j] = ld_co64(reinterpret_cast<const unsigned long long *>(
+                                pbuf + (size_t)(q * Kw + w) * n_cg + lane));
+                        if (lane == 0) {
+                            S.pend_g[q] = S.need_list[q];
+                            S.pend_found[q] = found;
+                            S.pend_m[q] = found ? S.row_m[q * Kw + w] : 0.0f;
+                            apply(q, found, w);
+                        }
+                    }
+                }
+                if (tid == 0) { S.pend_n = n_need; S.pend_ncg = n_cg; }
+            } else {
+                // D2: walk each searching hypothesis through its window
+                for (int q = wave; q < n_need; q += kWaves) {
+                    int w;
+                    const bool found = walk(q, w);
+                    if (lane == 0) {
+                        S.dec_w[q] = w;
+                        S.dec_found[q] = found;
+                    }
+                }
+                __syncthreads();
+                // D3: softmax denominator of each chosen row, then the state update; a segment of
+                // seg lanes serves one hypothesis
                 int seg = 1;
                 while (seg < n_cg) seg <<= 1;   // <= kMaxColGroups = 64
                 const int per_round = kThreads / seg;
@@ -978,37 +1131,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     }
                     for (int off = seg >> 1; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
                     if (live && cg == 0) {
-                        const int g = S.need_list[q];
-                        const int t0 = S.time[g], len = S.len[g];
-                        int sym = (w > 0 || !found) ? 0 : S.sym[g];
-                        if (found) {
-                            const int k = S.row_a[q * Kw + w];
-                            int dk = S.row_d[q * Kw + w];
-                            const int frame = t0 + w, n = S.out_len[g];
-                            if (rank == 0) {
-                                p.out_labels[(size_t)(b0 + g) * p.u_cap + n] = k;
-                                p.out_frames[(size_t)(b0 + g) * p.u_cap + n] = frame;
-                            }
-                            S.score[g] -= logf(part);   // log_softmax at the maximum = -log(sum exp(l - max))
-                            S.out_len[g] = n + 1;
-                            S.last2[g] = S.last[g];
-                            S.last[g] = k;
-                            sym += 1;
-                            if (dk == 0 && sym >= p.max_symbols) dk = 1;
-                            int t1 = frame;
-                            if (dk > 0) { t1 = frame + dk; sym = 0; }
-                            S.time[g] = t1;
-                            bool act_now = t1 < len;
-                            if (n + 1 >= p.u_cap) { act_now = false; S.status[g] |= TDT_HYP_TRUNCATED; }
-                            S.active[g] = act_now;
-                            S.need[g] = 0;
-                        } else {
-                            const int t1 = t0 + w;
-                            S.time[g] = t1;
-                            S.active[g] = t1 < len;
-                            S.need[g] = t1 < len;
-                        }
-                        S.sym[g] = sym;
+                        // log_softmax at the maximum = -log(sum exp(l - max))
+                        if (found) S.score[S.need_list[q]] -= logf(part);
+                        apply(q, found, w);
                     }
                 }
             }
@@ -1019,6 +1144,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         if (!ok) break;
         pp ^= 1;
     }
+
+    finish_scores();
+    __syncthreads();
 
     // ---- results of this cluster's hypotheses
     if (rank == 0) {
@@ -1064,7 +1192,6 @@ int kseg_max_for(const tdt_weights_t *w)
 {
     int kmax = w->h_joint;
     if (w->h_pred > kmax) kmax = w->h_pred;
-    if (w->pred_kind == TDT_PRED_LSTM && w->emb_dim > kmax) kmax = w->emb_dim;
     return kmax < KSEG ? kmax : KSEG;
 }
 

@@ -1,5 +1,8 @@
-// Encoder projection (paper Sec. 3.4; the precomputation at line 2 of Algorithm 3):
-//   out[r][n] = sum_k enc[r][k] * w_enc[n][k] + b_enc[n]
+// Dense projections computed once per call, before the label loop starts:
+//   encoder projection (paper Sec. 3.4; the precomputation at line 2 of Algorithm 3)
+//     out[r][n] = sum_k enc[r][k] * w_enc[n][k] + b_enc[n]
+//   and, with the same kernel, the table w_ih[0] * emb[label] + b_lstm[0] of the first LSTM
+//   layer's input product for every label.
 // A dense contraction over all B*T frames, so it runs on the matrix cores:
 // bf16 operands, fp32 accumulation, fp32 output (v_mfma_f32_32x32x16_bf16).
 // Both operands are K-contiguous ("NT" GEMM), which is the layout the MFMA lane
@@ -161,24 +164,27 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
 
 }  // namespace
 
-hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,
-                                     float *out, hipStream_t stream)
+hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
+                         int dtype, float *out, hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;
-    const int N = w->h_joint, K = w->d_enc;
-    if (w->dtype == 1) {
+    if (dtype == 1) {
         dim3 grid((unsigned)(((N + BN - 1) / BN) * ((rows + BM - 1) / BM)));
         hipLaunchKernelGGL(enc_proj_bf16_kernel, grid, dim3(GEMM_THREADS), 0, stream,
-                           static_cast<const uint16_t *>(enc),
-                           static_cast<const uint16_t *>(w->w_enc), w->b_enc, out,
+                           static_cast<const uint16_t *>(a), static_cast<const uint16_t *>(w), bias, out,
                            (long long)rows, N, K);
     } else {
         dim3 grid((unsigned)(((N + 63) / 64) * ((rows + 63) / 64)));
-        hipLaunchKernelGGL(enc_proj_f32_kernel, grid, dim3(256), 0, stream,
-                           static_cast<const float *>(enc), static_cast<const float *>(w->w_enc),
-                           w->b_enc, out, (long long)rows, N, K);
+        hipLaunchKernelGGL(enc_proj_f32_kernel, grid, dim3(256), 0, stream, static_cast<const float *>(a),
+                           static_cast<const float *>(w), bias, out, (long long)rows, N, K);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,
+                                     float *out, hipStream_t stream)
+{
+    return launch_linear(enc, rows, w->d_enc, w->w_enc, w->h_joint, w->b_enc, w->dtype, out, stream);
 }
 
 }  // namespace tdt

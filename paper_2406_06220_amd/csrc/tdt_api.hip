@@ -16,6 +16,9 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T)
     off = align_up(off + (size_t)B * T * w->h_joint * sizeof(float), 256);
     L.pred_proj = off;
     off = align_up(off + (size_t)B * w->h_joint * sizeof(float), 256);
+    L.emb_gates = off;
+    if (lstm_layers > 0)
+        off = align_up(off + (size_t)(w->vocab + 1) * 4 * w->h_pred * sizeof(float), 256);
     L.partials = off;
     off = align_up(off + 2 * (size_t)kPartialEntries * sizeof(LsePartial), 256);
     // everything from here on is cleared by the init kernel of every call
@@ -128,8 +131,9 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     int window = 0, n_clusters = 0, max_items = 0;
     bool reuse_enc_proj = false;
     if (options) {
-        for (int r : options->reserved)
-            if (r != 0) return TDT_ERR_UNSUPPORTED;
+        for (int i = 1; i < 4; ++i)
+            if (options->reserved[i] != 0) return TDT_ERR_UNSUPPORTED;
+        if (options->reserved[0] < 0 || options->reserved[0] > 64) return TDT_ERR_UNSUPPORTED;
         window = options->window;
         n_clusters = options->n_clusters;
         reuse_enc_proj = options->reuse_enc_proj != 0;
@@ -154,9 +158,16 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     if (launch_init(ws + L.zero_begin, L.zero_end - L.zero_begin,
                     reinterpret_cast<long long *>(out_stats), s) != hipSuccess)
         return TDT_ERR_LAUNCH;
-    if (!reuse_enc_proj &&
-        launch_encoder_projection(enc, (int64_t)B * T, weights, enc_proj, s) != hipSuccess)
-        return TDT_ERR_LAUNCH;
+    float *emb_gates = reinterpret_cast<float *>(ws + L.emb_gates);
+    if (!reuse_enc_proj) {
+        if (launch_encoder_projection(enc, (int64_t)B * T, weights, enc_proj, s) != hipSuccess)
+            return TDT_ERR_LAUNCH;
+        // first LSTM layer: its input product depends on the label only, so it is a table
+        if (weights->pred_kind == TDT_PRED_LSTM &&
+            launch_linear(weights->emb, weights->vocab + 1, weights->emb_dim, weights->w_ih[0],
+                          4 * weights->h_pred, weights->b_lstm[0], weights->dtype, emb_gates, s) != hipSuccess)
+            return TDT_ERR_LAUNCH;
+    }
 
     DecodeParams p{};
     p.B = B;
@@ -174,6 +185,7 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     p.u_cap = u_cap;
     p.window = window;
     p.max_items = max_items;
+    p.row_budget_tiles = options ? options->reserved[0] : 0;
     p.n_clusters = n_clusters;
     p.hyps_per_cluster = (B + n_clusters - 1) / n_clusters;
     for (int j = 0; j < TDT_MAX_DURATIONS; ++j) p.durations[j] = j < weights->n_dur ? durations[j] : 0;
@@ -188,6 +200,7 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     p.w_out = weights->w_out;
     p.b_out = weights->b_out;
     p.enc_proj = enc_proj;
+    p.emb_gates = emb_gates;
     p.enc_len = enc_len;
     p.out_labels = out_labels;
     p.out_frames = out_frames;

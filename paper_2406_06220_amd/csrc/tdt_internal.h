@@ -34,6 +34,7 @@ struct DecodeParams {
     int max_symbols, u_cap;
     int window;            // 0 = automatic
     int max_items;         // cap on work items per phase (0 = one per workgroup)
+    int row_budget_tiles;  // column tiles per joint work item the automatic window aims at (0 = 4)
     int kseg_max;          // longest K segment staged at once (set by launch_decode)
     int n_clusters, hyps_per_cluster;
     int durations[TDT_MAX_DURATIONS];
@@ -47,6 +48,7 @@ struct DecodeParams {
     const float *b_out;
     // inputs
     const float *enc_proj;   // [B][T][H]
+    const float *emb_gates;  // [V+1][4*h_pred]: w_ih[0] * emb[label] + b_lstm[0] (LSTM only)
     const int32_t *enc_len;  // [B]
     // outputs
     int32_t *out_labels, *out_frames, *out_len, *out_status;
@@ -66,7 +68,7 @@ struct DecodeParams {
 };
 
 struct WorkspaceLayout {
-    size_t enc_proj, hbuf, cbuf, pred_proj, partials, row_lab, row_dur, barrier, abort_flag, total;
+    size_t enc_proj, emb_gates, hbuf, cbuf, pred_proj, partials, row_lab, row_dur, barrier, abort_flag, total;
     size_t row_entries;            // uint64 entries in each of row_lab / row_dur
     size_t zero_begin, zero_end;   // byte range the init kernel clears
 };
@@ -76,6 +78,9 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T);
 // launches (each returns a hipError_t)
 hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,
                                      float *out, hipStream_t stream);
+// out[r][n] = sum_k a[r][k] * w[n][k] + bias[n]; a and w in the model's dtype, out float32
+hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
+                         int dtype, float *out, hipStream_t stream);
 hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats,
                        hipStream_t stream);
 hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid, hipStream_t stream);
