@@ -45,7 +45,7 @@ def algorithmic_bytes(cfg, stats) -> float:
             + stats["joint_rows"] * H * 4 + stats["pred_rows"] * Hp * 4)
 
 
-def time_workload(cfg, steps, warmup, window=0, n_clusters=0, max_items=0, tiles=0):
+def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0):
     import torch
     from paper_2406_06220_amd import binding, synth
     dev = "cuda:0"
@@ -54,8 +54,7 @@ def time_workload(cfg, steps, warmup, window=0, n_clusters=0, max_items=0, tiles
     u_cap = cfg.T * cfg.max_symbols
     model = binding.DeviceModel(cfg, w, dev)
     dec = binding.Decoder(model, cfg.B, cfg.T, u_cap, window=window, n_clusters=n_clusters,
-                          max_items=max_items)
-    dec.options.reserved[0] = tiles
+                          joint_tiles=joint_tiles)
     enc_d = model.upload_enc(enc)
     len_d = torch.from_numpy(ln).to(dev)
     stream = torch.cuda.current_stream(dev)

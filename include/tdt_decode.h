@@ -98,7 +98,9 @@ typedef struct {
 } tdt_weights_t;
 
 /*
- * Tuning knobs; pass NULL for defaults.  None of them changes the result.
+ * Tuning knobs; pass NULL for defaults.  None of them changes the decoding rule; the
+ * order in which a score's terms are summed, and with it the score's last bits, can
+ * differ between settings.
  *   window      frames of one hypothesis scored per joint pass while it searches
  *               for its next non-blank label (the inner loop of Algorithm 3
  *               advances one frame per pass; since the predictor output is fixed
@@ -106,17 +108,21 @@ typedef struct {
  *               and the first non-blank taken).  0 = automatic.
  *   n_clusters  the batch is split into this many groups of hypotheses that are
  *               decoded by disjoint sets of workgroups without waiting for each
- *               other.  0 = automatic.
- *   reuse_enc_proj  non-zero: the workspace still holds the encoder projection that
- *               an earlier call with the same enc, B, T and weights left there, and
- *               the projection step is skipped (decoding one encoder output again
- *               with other settings; timing the decode kernel on its own).
+ *               other.  0 = automatic (1, 2 or 4 by batch size; more when B needs it).
+ *   reuse_enc_proj  non-zero: the workspace still holds the encoder projection (and the
+ *               first LSTM layer's per-label input table) that an earlier call with the
+ *               same enc, B, T and weights left there, and these steps are skipped
+ *               (decoding one encoder output again with other settings; timing the
+ *               decode kernel on its own).
+ *   joint_tiles the automatic window is sized so that one joint pass gives every
+ *               workgroup at most one work item of this many 16-column tiles of the
+ *               output layer.  0 = default (4).  Ignored when window > 0.
  */
 typedef struct {
     int32_t window;
     int32_t n_clusters;
     int32_t reuse_enc_proj;
-    int32_t max_items;   /* most workgroups of a group that share one phase's work; 0 = all */
+    int32_t joint_tiles;
     int32_t reserved[4]; /* must be zero */
 } tdt_options_t;
 

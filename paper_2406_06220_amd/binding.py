@@ -45,7 +45,7 @@ class tdt_weights_t(C.Structure):
 
 class tdt_options_t(C.Structure):
     _fields_ = [("window", C.c_int32), ("n_clusters", C.c_int32), ("reuse_enc_proj", C.c_int32),
-                ("max_items", C.c_int32), ("reserved", C.c_int32 * 4)]
+                ("joint_tiles", C.c_int32), ("reserved", C.c_int32 * 4)]
 
 
 _lib = None
@@ -165,7 +165,7 @@ class Decoder:
     """Owns the output tensors and the workspace for one (model, B, T, u_cap)."""
 
     def __init__(self, model: DeviceModel, B: int, T: int, u_cap: int,
-                 window: int = 0, n_clusters: int = 0, max_items: int = 0):
+                 window: int = 0, n_clusters: int = 0, joint_tiles: int = 0):
         import torch
         self.model, self.B, self.T, self.u_cap = model, B, T, u_cap
         dev = model.device
@@ -181,7 +181,7 @@ class Decoder:
         self.options = tdt_options_t()
         self.options.window = window
         self.options.n_clusters = n_clusters
-        self.options.max_items = max_items
+        self.options.joint_tiles = joint_tiles
 
     def __call__(self, enc_dev, enc_len_dev, max_symbols: Optional[int] = None, stream=None):
         import torch
@@ -203,4 +203,4 @@ class Decoder:
         return dict(labels=self.labels.cpu().numpy(), frames=self.frames.cpu().numpy(),
                     len=self.lens.cpu().numpy(), score=self.score.cpu().numpy(),
                     status=self.status.cpu().numpy(),
-                    stats={n: int(st[i]) for n, i in TDT_STAT_NAMES.items()}, raw_stats=st)
+                    stats={n: int(st[i]) for n, i in TDT_STAT_NAMES.items()})

@@ -181,17 +181,16 @@ __device__ inline float unpack_value(unsigned long long p)
     return __uint_as_float(u);
 }
 
-// Barrier over the C workgroups of one cluster.  Counters only grow: the n-th
-// barrier waits for n * (arrivals per barrier).  Clusters of more than
-// kBarrierGroup workgroups arrive on one of 8 first-level counters (by rank
-// modulo 8, i.e. by XCD when the cluster spans the chip); the last arrival of a
-// group arrives on the root counter, on which everybody waits.  Every wait is
-// bounded: on a timeout, or when another workgroup has flagged an abort, the
-// barrier returns false and the caller leaves the kernel.
+// Barrier over the C workgroups of one cluster.  Every workgroup owns one flag word; to
+// arrive it stores the barrier's sequence number there (after all its earlier coherent
+// stores have completed), and it leaves once the flags of all C members have reached that
+// number -- thread t polls member t's flag, and the workgroup votes.  No read-modify-write
+// and no tree: two memory round trips after the last arrival.  Every wait is bounded: on a
+// timeout, or when another workgroup has flagged an abort, the barrier returns false and
+// the caller leaves the kernel.
 struct BarrierInfo {
-    unsigned *root;    // root counter of this cluster
-    unsigned *group;   // first-level counter of this workgroup's group (null if flat)
-    unsigned group_size, root_arrivals;
+    unsigned *my_flag;          // this workgroup's flag
+    const unsigned *poll_flag;  // flag of member `threadIdx.x` (any valid address if >= C)
 };
 
 __device__ inline bool cluster_barrier(HypShared &S, const BarrierInfo &bi, int *abort_flag, int C,
@@ -200,35 +199,31 @@ __device__ inline bool cluster_barrier(HypShared &S, const BarrierInfo &bi, int 
     // every coherent store / atomic of this wavefront has completed ...
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();   // ... and so have those of the whole workgroup
+    if (C <= 1) return true;
     if (threadIdx.x == 0) {
-        int ab = 0;
-        if (C > 1) {
-            S.epoch += 1;
-            if (bi.group) {
-                const unsigned old = __hip_atomic_fetch_add(bi.group, 1u, __ATOMIC_RELAXED, TDT_AGENT);
-                if (old + 1u == S.epoch * bi.group_size)
-                    __hip_atomic_fetch_add(bi.root, 1u, __ATOMIC_RELAXED, TDT_AGENT);
-            } else {
-                __hip_atomic_fetch_add(bi.root, 1u, __ATOMIC_RELAXED, TDT_AGENT);
-            }
-            const unsigned target = S.epoch * bi.root_arrivals;
-            const long long t0 = wall_clock64();
-            unsigned spins = 0;
-            while (__hip_atomic_load(bi.root, __ATOMIC_RELAXED, TDT_AGENT) < target) {
-                if ((++spins & 63u) == 0u) {
-                    if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, TDT_AGENT)) { ab = 1; break; }
-                    if (wall_clock64() - t0 > timeout_ticks) {
-                        __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, TDT_AGENT);
-                        ab = 1;
-                        break;
-                    }
-                }
-            }
-        }
-        S.aborted = ab;
+        S.epoch += 1;
+        __hip_atomic_store(bi.my_flag, S.epoch, __ATOMIC_RELAXED, TDT_AGENT);
     }
     __syncthreads();
-    return S.aborted == 0;
+    const unsigned epoch = S.epoch;
+    const long long t0 = wall_clock64();
+    unsigned spins = 0;
+    for (;;) {
+        const unsigned f = __hip_atomic_load(bi.poll_flag, __ATOMIC_RELAXED, TDT_AGENT);
+        if (__syncthreads_and((int)threadIdx.x >= C || (int)(f - epoch) >= 0)) return true;
+        if ((++spins & 31u) == 0u) {   // uniform over the workgroup
+            if (threadIdx.x == 0) {
+                if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, TDT_AGENT)) {
+                    S.aborted = 1;
+                } else if (wall_clock64() - t0 > timeout_ticks) {
+                    __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, TDT_AGENT);
+                    S.aborted = 1;
+                }
+            }
+            __syncthreads();
+            if (S.aborted) return false;
+        }
+    }
 }
 
 // list[0..n) = indices g < G with flag[g] set, ascending.  All threads call it.
@@ -600,23 +595,13 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     A.ldb = ActTile<WT>::row_elems(p.kseg_max);
 
     BarrierInfo bi;
-    bi.root = p.barrier + (size_t)cl * kBarrierStride;
-    if (C > kBarrierGroup) {
-        const int n_groups = 8, grp = rank % n_groups;
-        bi.group = p.barrier + ((size_t)kMaxGrid + cl + (size_t)ncl * grp) * kBarrierStride;
-        bi.group_size = (unsigned)((C - grp + n_groups - 1) / n_groups);
-        bi.root_arrivals = (unsigned)n_groups;
-    } else {
-        bi.group = nullptr;
-        bi.group_size = 0;
-        bi.root_arrivals = (unsigned)C;
-    }
+    bi.my_flag = p.barrier + (size_t)blockIdx.x * kBarrierStride;
+    bi.poll_flag = p.barrier + (size_t)((tid < C ? tid : 0) * ncl + cl) * kBarrierStride;
     LsePartial *const pbase = p.partials + (size_t)cl * (kPartialEntries / ncl);
     const int rows_cap = p.rows_per_cluster;
     unsigned long long *const rl_base = p.row_lab + (size_t)cl * kRowBufs * rows_cap;
     unsigned long long *const rd_base = p.row_dur + (size_t)cl * kRowBufs * rows_cap;
     const int max_cg = min(kMaxColGroups, kPartialEntries / ncl / kMaxRowsPerPass);
-    const int Csplit = p.max_items > 0 && p.max_items < C ? p.max_items : C;   // work items per phase
 
     // ---- Alg. 3 lines 3-4: empty hypotheses, time 0, everyone with frames is active
     for (int g = tid; g < G; g += kThreads) {
@@ -706,7 +691,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 in.K1 = folded ? 0 : Hp;
                 const int NT = (Hp + 3) / 4;   // a column tile = 4 hidden units x 4 gates
                 int n_ug, tpg;
-                split_tiles(Csplit, n_tiles_a, NT, NT, n_ug, tpg);
+                split_tiles(C, n_tiles_a, NT, NT, n_ug, tpg);
                 for (int it = rank; it < n_tiles_a * n_ug; it += C) {
                     const int ti = it / n_ug, ug = it % n_ug;
                     const int nrows = min(RT, n_act - ti * RT);
@@ -786,7 +771,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             in.K1 = 0;
             const int NT = (H + CT - 1) / CT;
             int n_cg, tpg;
-            split_tiles(Csplit, n_tiles_a, NT, NT, n_cg, tpg);
+            split_tiles(C, n_tiles_a, NT, NT, n_cg, tpg);
             for (int it = rank; it < n_tiles_a * n_cg; it += C) {
                 const int ti = it / n_cg, cg = it % n_cg;
                 const int nrows = min(RT, n_act - ti * RT);
@@ -845,9 +830,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             // at most `tiles_per_item` column tiles (then one round, all wavefronts busy).
             int Kw = p.window;
             if (Kw <= 0) {
-                const int tiles_per_item = p.row_budget_tiles > 0 ? p.row_budget_tiles : 4;
+                const int tiles_per_item = p.joint_tiles > 0 ? p.joint_tiles : 4;
                 const int groups = (NT + tiles_per_item - 1) / tiles_per_item;
-                int row_tiles = Csplit / groups;
+                int row_tiles = C / groups;
                 if (row_tiles < 1) row_tiles = 1;
                 Kw = row_tiles * RT / n_need;
                 if (Kw < 4) Kw = 4;
@@ -857,7 +842,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             const int M = n_need * Kw;
             const int n_tiles = (M + RT - 1) / RT;
             int n_cg, tpg;
-            split_tiles(Csplit, n_tiles, NT, max_cg, n_cg, tpg);
+            split_tiles(C, n_tiles, NT, max_cg, n_cg, tpg);
             LsePartial *pbuf = pbase + (size_t)(jpass & 1u) * kPartialEntries;
             unsigned long long *row_lab = rl_base + (size_t)(jpass % kRowBufs) * rows_cap;
             unsigned long long *row_dur = rd_base + (size_t)(jpass % kRowBufs) * rows_cap;

@@ -16,8 +16,7 @@ constexpr int kMaxRowsPerPass = 1024;         // (hypothesis, frame) rows of one
 constexpr int kMaxColGroups = 64;             // output-column slices of one joint pass
 constexpr int kMaxWindow = 64;                // frames of one hypothesis per joint pass
 constexpr int kPartialEntries = kMaxRowsPerPass * kMaxGrid;  // per partial buffer
-constexpr int kBarrierStride = 64;            // uint32 slots between two barrier counters
-constexpr int kBarrierGroup = 32;             // workgroups that share a first-level counter
+constexpr int kBarrierStride = 16;            // uint32 slots between two workgroups' barrier flags
 constexpr int kRowBufs = 3;                   // rotating per-row argmax buffers
 
 // Softmax-denominator share of one slice of label columns for one joint row.
@@ -33,8 +32,7 @@ struct DecodeParams {
     int pred_kind, pred_layers, h_pred, emb_dim;
     int max_symbols, u_cap;
     int window;            // 0 = automatic
-    int max_items;         // cap on work items per phase (0 = one per workgroup)
-    int row_budget_tiles;  // column tiles per joint work item the automatic window aims at (0 = 4)
+    int joint_tiles;       // column tiles per joint work item the automatic window aims at (0 = 4)
     int kseg_max;          // longest K segment staged at once (set by launch_decode)
     int n_clusters, hyps_per_cluster;
     int durations[TDT_MAX_DURATIONS];
@@ -62,7 +60,7 @@ struct DecodeParams {
     unsigned long long *row_lab;  // [n_clusters][kRowBufs][rows_per_cluster] packed (logit, ~label)
     unsigned long long *row_dur;  // same shape, packed (logit, ~duration class)
     int rows_per_cluster;
-    unsigned *barrier;       // [2 * kMaxGrid][kBarrierStride]: root counters, then group counters
+    unsigned *barrier;       // [kMaxGrid][kBarrierStride]: one flag word per workgroup
     int *abort_flag;
     long long timeout_ticks; // bound on one wait, in wall-clock ticks
 };

@@ -115,6 +115,8 @@ def test_rejects_bad_arguments_before_device_work(lib):
     assert _decode(lib, w, durations=dur, options=o) == -3
     o = binding.tdt_options_t(); o.reserved[3] = 1
     assert _decode(lib, w, durations=dur, options=o) == -3
+    o = binding.tdt_options_t(); o.joint_tiles = 65
+    assert _decode(lib, w, durations=dur, options=o) == -3
     # workspace
     assert _decode(lib, w, durations=dur, ws=None) == -5
     assert _decode(lib, w, durations=dur, ws=4096 + 8) == -5
