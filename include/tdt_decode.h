@@ -142,11 +142,10 @@ enum tdt_stat {
     TDT_STAT_TICKS_DECIDE = 11,
     TDT_STAT_TICKS_BARRIER = 12,
     TDT_STAT_TICKS_TOTAL = 13,
-    /* of which, inside the three GEMM-shaped phases: staging activations, multiplying,
-       epilogues */
-    TDT_STAT_TICKS_STAGE = 14,
-    TDT_STAT_TICKS_MMA = 15,
-    TDT_STAT_TICKS_EPILOGUE = 16,
+    /* library builds with fine timers only (zero otherwise): 9 entries, for each of the
+       predictor step, the predictor projection and the joint pass the ticks spent staging
+       activations, multiplying, and in epilogues */
+    TDT_STAT_TICKS_FINE = 14,
     TDT_STAT_COUNT = 24
 };
 

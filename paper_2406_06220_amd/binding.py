@@ -22,7 +22,9 @@ TDT_MAX_LSTM_LAYERS = 2
 TDT_STAT_NAMES = {"pred_passes": 0, "pred_rows": 1, "joint_passes": 2, "joint_rows": 3,
                   "outer_max": 4, "abort": 5, "ticks_pred": 8, "ticks_proj": 9, "ticks_joint": 10,
                   "ticks_decide": 11, "ticks_barrier": 12, "ticks_total": 13,
-                  "ticks_stage": 14, "ticks_mma": 15, "ticks_epilogue": 16}
+                  **{f"ticks_{ph}_{part}": 14 + 3 * a + b
+                     for a, ph in enumerate(("pred", "proj", "joint"))
+                     for b, part in enumerate(("stage", "mma", "epilogue"))}}
 TDT_STAT_COUNT = 24
 TDT_HYP_TRUNCATED = 1
 TDT_HYP_LEN_CLAMPED = 2

@@ -67,6 +67,7 @@ constexpr int KSEG = 1024;   // longest stretch of the reduction dimension stage
 constexpr int CP_LD = CT + 1;
 constexpr int kDeferPerWave = 4;                     // hypotheses per wavefront whose score term may be deferred
 constexpr int kDeferred = kDeferPerWave * kWaves;
+constexpr int kTabPerThread = kWaves * RT * CT / kThreads;
 
 struct HypShared {
     int len[kMaxHypsPerCluster];
@@ -99,7 +100,9 @@ struct HypShared {
     unsigned char pend_found[kDeferred];
     unsigned epoch;
     int aborted;
-    long long tk_stage, tk_mma, tk_epi;   // thread 0: ticks spent staging / multiplying / in epilogues
+    // thread 0 (profiling builds): ticks spent staging / multiplying / in epilogues, per phase P, Q, J
+    long long tk_fine[3][3];
+    int fine_phase;
 };
 
 // One stretch of the reduction dimension: `K` inputs, starting at offset k0 of input
@@ -109,6 +112,17 @@ struct HypShared {
 struct Seg {
     const void *w;
     int wld, k0, K, part;
+};
+
+// what the joint pass loads for two inputs of one row: projected encoder frame and
+// projected predictor output
+struct EncPred {
+    float2 e, p;
+};
+// where one row of a joint pass reads them (valid false: past the end of the utterance)
+struct JointRow {
+    const float *enc, *pred;
+    bool valid;
 };
 
 struct PhaseInputs {
@@ -133,16 +147,18 @@ struct PhaseInputs {
 };
 
 // ---- number formats
-template <typename WT> __device__ inline float2 load_w2(const WT *p);
-template <> __device__ inline float2 load_w2<float>(const float *p)
-{
-    return *reinterpret_cast<const float2 *>(p);
-}
-template <> __device__ inline float2 load_w2<uint16_t>(const uint16_t *p)
-{
-    const uint32_t u = *reinterpret_cast<const uint32_t *>(p);
-    return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
-}
+// two consecutive matrix entries: the load as it comes from memory, and its conversion
+template <typename WT> struct W2;
+template <> struct W2<float> {
+    typedef float2 Raw;
+    __device__ static Raw load(const float *p) { return *reinterpret_cast<const float2 *>(p); }
+    __device__ static float2 cvt(Raw r) { return r; }
+};
+template <> struct W2<uint16_t> {
+    typedef uint32_t Raw;
+    __device__ static Raw load(const uint16_t *p) { return *reinterpret_cast<const uint32_t *>(p); }
+    __device__ static float2 cvt(Raw u) { return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u)); }
+};
 
 __device__ inline float sigmoidf_dev(float x) { return 1.0f / (1.0f + expf(-x)); }
 
@@ -304,44 +320,52 @@ template <> struct ActTile<float> {
     }
 };
 
-// stage one K segment: f(i, k) gives the two inputs (k, k+1) of row i; the tail up to a
-// multiple of 32 is zero-filled.  All loads of a wavefront are issued before the first
-// value is used, so that their latencies overlap.
-// f is called with in-range (i, k) only and must itself be free of branches around its
-// loads (clamp the address, mask the value): a load inside a conditional block is waited
-// for before the next one is issued.  For the same reason rows beyond nrows re-read row 0
-// and steps beyond K re-read the last step instead of being skipped.
-template <typename WT, int KIT, typename F>
-__device__ inline void stage_segment_impl(const ActTile<WT> &A, int K, int nrows, F f)
+// stage one K segment: with c = ctx(i) computed once per row, mix(c, k, load(c, k)) gives the
+// two inputs (k, k+1) of row i; the tail up to a multiple of 32 is zero-filled.  load only
+// loads and mix only computes: all loads of a wavefront are issued before the first loaded
+// value is used, so that their latencies overlap (a use between two loads makes the
+// compiler wait for the first load before it issues the second, and so does a load inside
+// a conditional block).  For the same reason load is called for every slot -- rows beyond
+// nrows re-read row 0, steps beyond K re-read the last step -- and what it returned there
+// is dropped afterwards.
+template <typename WT, int KIT, typename CtxF, typename LoadF, typename MixF>
+__device__ inline void stage_segment_impl(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int Kpad = ((K + 31) / 32) * 32;
     constexpr int RPW = RT / kWaves;    // rows per wavefront
-    float2 v[RPW][KIT];
+    decltype(ctx(0)) c[RPW];
+#pragma unroll
+    for (int ii = 0; ii < RPW; ++ii) {
+        const int i = wave + ii * kWaves;
+        c[ii] = ctx(i < nrows ? i : 0);
+    }
+    decltype(load(c[0], 0)) v[RPW][KIT];
+#pragma unroll
+    for (int ii = 0; ii < RPW; ++ii)
+#pragma unroll
+        for (int kk = 0; kk < KIT; ++kk) {
+            const int k = lane * 2 + kk * 128;
+            v[ii][kk] = load(c[ii], k < K ? k : K - 2);
+        }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ii = 0; ii < RPW; ++ii)
 #pragma unroll
         for (int kk = 0; kk < KIT; ++kk) {
             const int i = wave + ii * kWaves, k = lane * 2 + kk * 128;
             const bool ok = i < nrows && k < K;
-            const float2 x = f(i < nrows ? i : 0, k < K ? k : K - 2);
-            v[ii][kk] = make_float2(ok ? x.x : 0.0f, ok ? x.y : 0.0f);
-        }
-#pragma unroll
-    for (int ii = 0; ii < RPW; ++ii)
-#pragma unroll
-        for (int kk = 0; kk < KIT; ++kk) {
-            const int k = lane * 2 + kk * 128;
-            if (k < Kpad) A.store2(wave + ii * kWaves, k, v[ii][kk]);
+            const float2 x = mix(c[ii], k < K ? k : K - 2, v[ii][kk]);
+            if (k < Kpad) A.store2(i, k, make_float2(ok ? x.x : 0.0f, ok ? x.y : 0.0f));
         }
 }
 
-template <typename WT, typename F>
-__device__ inline void stage_segment(const ActTile<WT> &A, int K, int nrows, F f)
+template <typename WT, typename CtxF, typename LoadF, typename MixF>
+__device__ inline void stage_segment(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
 {
     // 64 lanes x 2 inputs per step: pick the unrolling that covers K without spare loads
-    if (K <= 640) stage_segment_impl<WT, 5>(A, K, nrows, f);
-    else stage_segment_impl<WT, KSEG / 128>(A, K, nrows, f);
+    if (K <= 640) stage_segment_impl<WT, 5>(A, K, nrows, ctx, load, mix);
+    else stage_segment_impl<WT, KSEG / 128>(A, K, nrows, ctx, load, mix);
 }
 
 // accumulators of one wavefront for one 16x16 tile
@@ -382,18 +406,17 @@ __device__ inline WeightCursor weight_cursor(const Seg &sg, long long wrow, int 
     return wc;
 }
 
-// loads are unconditional (address clamped into the row, value masked) so that all CH of
-// them are in flight together
+// Loads are unconditional (address clamped into the row) and nothing uses a fragment before
+// all CH loads have been issued; what a clamped load fetched is masked where it is used.
 __device__ inline void weight_prefetch(const WeightCursor &wc, const Seg &sg, int kpart, int ksplit, int c0,
                                        uint4 (&b)[CH])
 {
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
         const int k = (kpart + (c0 + j) * ksplit) * 32 + wc.kq;
-        const bool ok = wc.live && c0 + j < wc.n_my && k < sg.K;
-        const uint4 x = *reinterpret_cast<const uint4 *>(wc.wr + (k < sg.K ? k : sg.K - 8));
-        b[j] = make_uint4(ok ? x.x : 0u, ok ? x.y : 0u, ok ? x.z : 0u, ok ? x.w : 0u);
+        b[j] = *reinterpret_cast<const uint4 *>(wc.wr + (k < sg.K ? k : sg.K - 8));
     }
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 __device__ inline void tile_accumulate(const ActTile<uint16_t> &A, const Seg &sg, const WeightCursor &wc,
@@ -408,7 +431,9 @@ __device__ inline void tile_accumulate(const ActTile<uint16_t> &A, const Seg &sg
         for (int j = 0; j < CH; ++j) {
             if (c0 + j < wc.n_my) {
                 const int s = kpart + (c0 + j) * ksplit;
-                const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&b[j]);
+                const bool ok = wc.live && s * 32 + wc.kq < sg.K;
+                const uint4 m = make_uint4(ok ? b[j].x : 0u, ok ? b[j].y : 0u, ok ? b[j].z : 0u, ok ? b[j].w : 0u);
+                const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&m);
                 const bf16x8 x0 = *reinterpret_cast<const bf16x8 *>(a0 + s * 32);
                 const bf16x8 x1 = *reinterpret_cast<const bf16x8 *>(a0 + plane + s * 32);
                 const bf16x8 x2 = *reinterpret_cast<const bf16x8 *>(a0 + 2 * plane + s * 32);
@@ -504,17 +529,19 @@ template <> struct Backend<float> {
 //   stage(seg)                     stages Seg seg of the item's rows (stage_segment)
 //   rowidx(ct, j)    -> long long  weight row of column j of column tile ct, -1 if none
 //   pre(ct0, n)                    called by all threads at the start of a round, before the
-//                                  rows are staged: loads whose latency should hide there
+//                                  rows are staged: issues loads whose latency should hide there
+//   park(ct0, n)                   called by all threads after the round's products, before the
+//                                  barrier that precedes epi: may put what pre loaded into LDS
 //   epi(ct0, n, ksplit)            called by all threads once S.cpart holds round results:
 //                                  tile slot t (< n) is the sum over kp < ksplit of
 //                                  S.cpart[t * ksplit + kp]; S.bias[t * 16 + j] is
 //                                  bias[rowidx(ct0 + t, j)]
 // With one segment the rows are staged once; with several they are staged again for
 // every round.
-template <typename WT, typename StageF, typename RowF, typename PreF, typename EpiF>
+template <typename WT, typename StageF, typename RowF, typename PreF, typename ParkF, typename EpiF>
 __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseInputs &in, int n_ct,
                                 const float *__restrict__ bias, const float *any_floats, StageF stage,
-                                RowF rowidx, PreF pre_round, EpiF epi)
+                                RowF rowidx, PreF pre_round, ParkF park, EpiF epi)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nseg = in.count();
@@ -550,18 +577,19 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
                 stage(sg);
                 __syncthreads();
             }
-            if (TDT_FINE_TIMERS && threadIdx.x == 0) { const long long n = wall_clock64(); S.tk_stage += n - tq; tq = n; }
+            if (TDT_FINE_TIMERS && threadIdx.x == 0) { const long long n = wall_clock64(); S.tk_fine[S.fine_phase][0] += n - tq; tq = n; }
             if (mine) Backend<WT>::accumulate(A, sg, rowidx, ct, kpart, ksplit, acc, lane, pre);
-            if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_mma += wall_clock64() - tq;
+            if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_fine[S.fine_phase][1] += wall_clock64() - tq;
         }
         long long tq = 0;
         if (TDT_FINE_TIMERS && threadIdx.x == 0) tq = wall_clock64();
         if (mine) Backend<WT>::spill(S, acc, wave, lane);
         if (threadIdx.x < kWaves * CT) S.bias[threadIdx.x] = bias_v;
+        park(base, min(tpr, n_ct - base));
         __syncthreads();
         epi(base, min(tpr, n_ct - base), ksplit);
         __syncthreads();
-        if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_epi += wall_clock64() - tq;
+        if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_fine[S.fine_phase][2] += wall_clock64() - tq;
     }
 }
 
@@ -621,7 +649,15 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         S.need[g] = 0;
     }
     if (tid < TDT_MAX_DURATIONS) S.durations[tid] = p.durations[tid];
-    if (tid == 0) { S.epoch = 0; S.aborted = 0; S.tk_stage = S.tk_mma = S.tk_epi = 0; S.pend_n = 0; S.pend_ncg = 0; }
+    if (tid == 0) {
+        S.epoch = 0;
+        S.aborted = 0;
+        S.pend_n = 0;
+        S.pend_ncg = 0;
+        S.fine_phase = 0;
+        for (int a = 0; a < 3; ++a)
+            for (int b = 0; b < 3; ++b) S.tk_fine[a][b] = 0;
+    }
     __syncthreads();
 
     long long st_pred_pass = 0, st_pred_rows = 0, st_joint_pass = 0, st_joint_rows = 0, st_outer = 0;
@@ -672,6 +708,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         const int n_tiles_a = (n_act + RT - 1) / RT;
 
         // ---- P: predictor step (Alg. 3 line 6)
+        if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 0;
         if (lstm) {
             for (int l = 0; l < L && ok; ++l) {
                 const int in_dim = l == 0 ? E : Hp;
@@ -697,15 +734,17 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     const int nrows = min(RT, n_act - ti * RT);
                     const int tile0 = ug * tpg, n_ct = min(tpg, NT - tile0);
                     float c_old = 0.0f;   // this thread's cell value, fetched ahead of the epilogue
+                    float tabv[kTabPerThread];   // ... and its share of the round's table addends
                     run_item<WT>(
                         S, A, in, n_ct, folded ? nullptr : bl, bl,
                         [&](const Seg &sg) {
                             const int k0 = sg.k0;
                             const float *src = (folded || sg.part == 1) ? h_cur : x_prev;
-                            stage_segment<WT>(A, sg.K, nrows, [&](int i, int k) -> float2 {
-                                const int g = S.act_list[ti * RT + i];
-                                return ld_co2(src + (size_t)(b0 + g) * Hp + k0 + k);
-                            });
+                            stage_segment<WT>(
+                                A, sg.K, nrows,
+                                [&](int i) { return src + (size_t)(b0 + S.act_list[ti * RT + i]) * Hp + k0; },
+                                [](const float *row, int k) { return ld_co2(row + k); },
+                                [](const float *, int, float2 v) { return v; });
                         },
                         [&](int ct, int j) -> long long {
                             const int unit = (tile0 + ct) * 4 + (j >> 2);
@@ -722,15 +761,25 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             }
                             if (folded) {   // addends of (row i, column j) of every tile of the round
 #pragma unroll
-                                for (int e = 0; e < kWaves * RT * CT / kThreads; ++e) {
+                                for (int e = 0; e < kTabPerThread; ++e) {
+                                    const int idx = tid + e * kThreads;
+                                    const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
+                                    const int unit = (tile0 + base + t) * 4 + (j >> 2);
+                                    const int g = S.act_list[ti * RT + (i < nrows ? i : 0)];
+                                    tabv[e] = gate_tab[(size_t)S.last[g] * (4 * Hp) + (size_t)(j & 3) * Hp +
+                                                       (unit < Hp ? unit : 0)];
+                                }
+                            }
+                        },
+                        [&](int base, int n) {
+                            if (folded) {
+#pragma unroll
+                                for (int e = 0; e < kTabPerThread; ++e) {
                                     const int idx = tid + e * kThreads;
                                     const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
                                     const int unit = (tile0 + base + t) * 4 + (j >> 2);
                                     const bool live = t < n && i < nrows && unit < Hp;
-                                    const int g = S.act_list[ti * RT + (i < nrows ? i : 0)];
-                                    const float v = gate_tab[(size_t)S.last[g] * (4 * Hp) + (size_t)(j & 3) * Hp +
-                                                             (unit < Hp ? unit : 0)];
-                                    S.tab[t][i][j] = live ? v : 0.0f;
+                                    S.tab[t][i][j] = live ? tabv[e] : 0.0f;
                                 }
                             }
                         },
@@ -762,6 +811,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         }
 
         // ---- Q: predictor output into the joint space (Sec. 3.4)
+        if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 1;
         {
             const float *dec_src = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * B * Hp : nullptr;
             PhaseInputs in;
@@ -781,25 +831,33 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
                         if (lstm) {
-                            stage_segment<WT>(A, sg.K, nrows, [&](int i, int k) -> float2 {
-                                const int g = S.act_list[ti * RT + i];
-                                return ld_co2(dec_src + (size_t)(b0 + g) * Hp + k0 + k);
-                            });
+                            stage_segment<WT>(
+                                A, sg.K, nrows,
+                                [&](int i) { return dec_src + (size_t)(b0 + S.act_list[ti * RT + i]) * Hp + k0; },
+                                [](const float *row, int k) { return ld_co2(row + k); },
+                                [](const float *, int, float2 v) { return v; });
                         } else {
                             // stateless: table L-1 embeds the newest label, table 0 the older one
-                            stage_segment<WT>(A, sg.K, nrows, [&](int i, int k) -> float2 {
-                                const int g = S.act_list[ti * RT + i];
-                                const int kk = k0 + k, c = kk / E;
-                                const int tok = (c == L - 1) ? S.last[g] : S.last2[g];
-                                return load_w2<WT>(static_cast<const WT *>(p.emb) +
-                                                   ((size_t)c * (V + 1) + tok) * E + (kk - c * E));
-                            });
+                            stage_segment<WT>(
+                                A, sg.K, nrows,
+                                [&](int i) {
+                                    const int g = S.act_list[ti * RT + i];
+                                    return make_int2(S.last[g], S.last2[g]);
+                                },
+                                [&](int2 lab, int k) {
+                                    const int kk = k0 + k, c = kk / E;
+                                    const int tok = (c == L - 1) ? lab.x : lab.y;
+                                    return W2<WT>::load(static_cast<const WT *>(p.emb) +
+                                                        ((size_t)c * (V + 1) + tok) * E + (kk - c * E));
+                                },
+                                [](int2, int, typename W2<WT>::Raw v) { return W2<WT>::cvt(v); });
                         }
                     },
                     [&](int ct, int j) -> long long {
                         const int n = (tile0 + ct) * CT + j;
                         return n < H ? n : -1;
                     },
+                    [&](int, int) {},
                     [&](int, int) {},
                     [&](int base, int n, int ksplit) {
                         for (int idx = tid; idx < n * RT * CT; idx += kThreads) {
@@ -817,6 +875,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             if (!ok) break;
         }
 
+        if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 2;
         // every active hypothesis now searches for its next non-blank label
         for (int g = tid; g < G; g += kThreads) S.need[g] = S.active[g];
         __syncthreads();
@@ -875,22 +934,35 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     S, A, in, n_ct, p.b_out, p.b_out,
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
-                        stage_segment<WT>(A, sg.K, min(RT, M - ti * RT), [&](int i, int k) -> float2 {
-                            const int r = ti * RT + i;
-                            const int g = S.need_list[r / Kw];
-                            const int f = S.time[g] + r % Kw;
-                            const bool valid = f < S.len[g];
-                            const float2 e2 = *reinterpret_cast<const float2 *>(
-                                p.enc_proj + ((size_t)(b0 + g) * T + (valid ? f : 0)) * H + k0 + k);
-                            const float2 p2 = ld_co2(p.pred_proj + (size_t)(b0 + g) * H + k0 + k);
-                            return make_float2(valid ? fmaxf(e2.x + p2.x, 0.0f) : 0.0f,
-                                               valid ? fmaxf(e2.y + p2.y, 0.0f) : 0.0f);
-                        });
+                        stage_segment<WT>(
+                            A, sg.K, min(RT, M - ti * RT),
+                            [&](int i) {
+                                const int r = ti * RT + i;
+                                const int q = r / Kw;
+                                const int g = S.need_list[q];
+                                const int f = S.time[g] + (r - q * Kw);
+                                JointRow c;
+                                c.valid = f < S.len[g];
+                                c.enc = p.enc_proj + ((size_t)(b0 + g) * T + (c.valid ? f : 0)) * H + k0;
+                                c.pred = p.pred_proj + (size_t)(b0 + g) * H + k0;
+                                return c;
+                            },
+                            [](const JointRow &c, int k) {
+                                EncPred v;
+                                v.e = *reinterpret_cast<const float2 *>(c.enc + k);
+                                v.p = ld_co2(c.pred + k);
+                                return v;
+                            },
+                            [](const JointRow &c, int, EncPred v) {
+                                return make_float2(c.valid ? fmaxf(v.e.x + v.p.x, 0.0f) : 0.0f,
+                                                   c.valid ? fmaxf(v.e.y + v.p.y, 0.0f) : 0.0f);
+                            });
                     },
                     [&](int ct, int j) -> long long {
                         const int n = (tile0 + ct) * CT + j;
                         return n < O ? n : -1;
                     },
+                    [&](int, int) {},
                     [&](int, int) {},
                     [&](int base, int n, int ksplit) {
                         // four threads share (tile slot t, row i), four columns each; lower
@@ -1157,9 +1229,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 add(TDT_STAT_TICKS_DECIDE, tk_d);
                 add(TDT_STAT_TICKS_BARRIER, tk_bar);
                 add(TDT_STAT_TICKS_TOTAL, wall_clock64() - tk_start);
-                add(TDT_STAT_TICKS_STAGE, S.tk_stage);
-                add(TDT_STAT_TICKS_MMA, S.tk_mma);
-                add(TDT_STAT_TICKS_EPILOGUE, S.tk_epi);
+                for (int a = 0; a < 3; ++a)
+                    for (int b = 0; b < 3; ++b) add(TDT_STAT_TICKS_FINE + a * 3 + b, S.tk_fine[a][b]);
             }
         }
     }
