@@ -86,7 +86,6 @@ struct HypShared {
     int wave_cnt[kWaves];
     int durations[TDT_MAX_DURATIONS];
     float cpart[kWaves][RT][CP_LD];  // per-wavefront 16x16 partial results of one round
-    float wstats[kWaves][RT][5];     // per column tile of a round: row statistics
     float bias[kWaves * CT];         // biases of the columns of the current round
     float tab[kWaves][RT][CP_LD];    // per (row, column) addends of the current round (LSTM layer 0)
     int row_a[kMaxRowsPerPass];      // per joint row: argmax label (V = blank)
@@ -927,7 +926,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             for (int it = rank; it < n_tiles * n_cg; it += C) {
                 const int ti = it / n_cg, cg = it % n_cg;
                 const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
-                // running statistics of row `tid` (tid < 16) over this item's columns
+                // running statistics of row tid / 32 over this item's columns (lanes 0 and 32)
                 float rm = -INFINITY, rs = 0.0f, rdm = -INFINITY;
                 int ra = 0, rda = 0;
                 run_item<WT>(
@@ -965,25 +964,23 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     [&](int, int) {},
                     [&](int, int) {},
                     [&](int base, int n, int ksplit) {
-                        // four threads share (tile slot t, row i), four columns each; lower
-                        // columns win ties, so the first maximum is kept
-                        const int t = tid >> 6, i = (tid >> 2) & 15, jq = tid & 3;
-                        float m = -INFINITY, s = 0.0f, dm = -INFINITY;
+                        // 32 consecutive lanes share row i and deal the round's n * 16 columns
+                        // round-robin; lower columns win ties, so the first maximum is kept
+                        const int i = tid >> 5, sub = tid & 31;
+                        float lg[kWaves * CT / 32];
+                        float m = -INFINITY, dm = -INFINITY;
                         int a = 0x7fffffff, da = 0x7fffffff;
-                        if (t < n) {
 #pragma unroll
-                            for (int jj = 0; jj < 4; ++jj) {
-                                const int j = jq * 4 + jj;
+                        for (int e = 0; e < kWaves * CT / 32; ++e) {
+                            const int c = sub + 32 * e;
+                            lg[e] = -INFINITY;
+                            if (c < n * CT) {
+                                const int t = c >> 4, j = c & 15;
                                 const int col = (tile0 + base + t) * CT + j;
-                                const float logit = cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j];
+                                const float logit = cpart_sum(S, t, ksplit, i, j) + S.bias[c];
                                 if (col <= V) {
-                                    if (logit > m) {
-                                        s = s * expf(m - logit) + 1.0f;
-                                        m = logit;
-                                        a = col;
-                                    } else {
-                                        s += expf(logit - m);
-                                    }
+                                    lg[e] = logit;
+                                    if (logit > m) { m = logit; a = col; }
                                 } else if (col < O && logit > dm) {
                                     dm = logit;
                                     da = col - (V + 1);
@@ -991,55 +988,36 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             }
                         }
 #pragma unroll
-                        for (int off = 1; off <= 2; off <<= 1) {
-                            const float om = __shfl_xor(m, off, 64), os = __shfl_xor(s, off, 64);
-                            const float odm = __shfl_xor(dm, off, 64);
+                        for (int off = 16; off > 0; off >>= 1) {
+                            const float om = __shfl_xor(m, off, 64), odm = __shfl_xor(dm, off, 64);
                             const int oa = __shfl_xor(a, off, 64), oda = __shfl_xor(da, off, 64);
-                            if (os > 0.0f) {
-                                if (om > m || (om == m && oa < a)) {
-                                    s = (s > 0.0f ? s * expf(m - om) : 0.0f) + os;
-                                    m = om;
-                                    a = oa;
+                            if (om > m || (om == m && oa < a)) { m = om; a = oa; }
+                            if (odm > dm || (odm == dm && oda < da)) { dm = odm; da = oda; }
+                        }
+                        float s = 0.0f;   // sum over the round's label columns of exp(logit - m)
+#pragma unroll
+                        for (int e = 0; e < kWaves * CT / 32; ++e)
+                            if (lg[e] > -INFINITY) s += __expf(lg[e] - m);
+#pragma unroll
+                        for (int off = 16; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+                        if (sub == 0) {   // rounds ascend through the columns: '>' keeps the first maximum
+                            if (s > 0.0f) {
+                                if (m > rm) {
+                                    rs = (rs > 0.0f ? rs * __expf(rm - m) : 0.0f) + s;
+                                    rm = m;
+                                    ra = a;
                                 } else {
-                                    s += os * expf(om - m);
+                                    rs += s * __expf(m - rm);
                                 }
                             }
-                            if (odm > dm || (odm == dm && oda < da)) {
-                                dm = odm;
-                                da = oda;
-                            }
-                        }
-                        if (t < n && jq == 0) {
-                            float *ws = S.wstats[t][i];
-                            ws[0] = m;
-                            ws[1] = __int_as_float(a);
-                            ws[2] = s;
-                            ws[3] = dm;
-                            ws[4] = __int_as_float(da);
-                        }
-                        __syncthreads();
-                        if (tid < RT) {   // tiles ascend: '>' keeps the first maximum
-                            for (int tt = 0; tt < n; ++tt) {
-                                const float *ws = S.wstats[tt][tid];
-                                const float wm = ws[0], wsum = ws[2], wd = ws[3];
-                                if (wsum > 0.0f) {
-                                    if (wm > rm) {
-                                        rs = (rs > 0.0f ? rs * expf(rm - wm) : 0.0f) + wsum;
-                                        rm = wm;
-                                        ra = __float_as_int(ws[1]);
-                                    } else {
-                                        rs += wsum * expf(wm - rm);
-                                    }
-                                }
-                                if (wd > rdm) {
-                                    rdm = wd;
-                                    rda = __float_as_int(ws[4]);
-                                }
+                            if (dm > rdm) {
+                                rdm = dm;
+                                rda = da;
                             }
                         }
                     });
-                if (tid < RT && ti * RT + tid < M) {
-                    const int r = ti * RT + tid;
+                if ((tid & 31) == 0 && ti * RT + (tid >> 5) < M) {
+                    const int r = ti * RT + (tid >> 5);
                     if (rs > 0.0f)
                         __hip_atomic_fetch_max(row_lab + r, pack_best(rm, ra), __ATOMIC_RELAXED, TDT_AGENT);
                     if (rdm > -INFINITY)
