@@ -87,7 +87,6 @@ struct HypShared {
     int durations[TDT_MAX_DURATIONS];
     float cpart[kWaves][RT][CP_LD];  // per-wavefront 16x16 partial results of one round
     float bias[kWaves * CT];         // biases of the columns of the current round
-    float tab[kWaves][RT][CP_LD];    // per (row, column) addends of the current round (LSTM layer 0)
     int row_a[kMaxRowsPerPass];      // per joint row: argmax label (V = blank)
     int row_d[kMaxRowsPerPass];      //                frame step of the argmax duration class
     float row_m[kMaxRowsPerPass];    //                largest label logit
@@ -97,7 +96,6 @@ struct HypShared {
     int pend_g[kDeferred];
     float pend_m[kDeferred];
     unsigned char pend_found[kDeferred];
-    unsigned epoch;
     int aborted;
     // thread 0 (profiling builds): ticks spent staging / multiplying / in epilogues, per phase P, Q, J
     long long tk_fine[3][3];
@@ -159,7 +157,8 @@ template <> struct W2<uint16_t> {
     __device__ static float2 cvt(Raw u) { return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u)); }
 };
 
-__device__ inline float sigmoidf_dev(float x) { return 1.0f / (1.0f + expf(-x)); }
+// hardware exponential and reciprocal: about 1e-7 absolute error on a value in (0, 1)
+__device__ inline float fast_sigmoid(float x) { return __frcp_rn(1.0f + __expf(-x)); }
 
 // ---- coherent exchange primitives (see the header comment)
 #define TDT_AGENT __HIP_MEMORY_SCOPE_AGENT
@@ -196,49 +195,62 @@ __device__ inline float unpack_value(unsigned long long p)
     return __uint_as_float(u);
 }
 
-// Barrier over the C workgroups of one cluster.  Every workgroup owns one flag word; to
-// arrive it stores the barrier's sequence number there (after all its earlier coherent
-// stores have completed), and it leaves once the flags of all C members have reached that
-// number -- thread t polls member t's flag, and the workgroup votes.  No read-modify-write
-// and no tree: two memory round trips after the last arrival.  Every wait is bounded: on a
-// timeout, or when another workgroup has flagged an abort, the barrier returns false and
-// the caller leaves the kernel.
+// Barrier over the C workgroups of one cluster.  Every workgroup owns one flag word in a
+// dense array; to arrive it stores the barrier's sequence number there (after all its
+// earlier coherent stores have completed), and it leaves once the flags of all C members
+// have reached that number.  Only the first wavefront polls -- a lane reads two
+// neighbouring flags with one 8-byte load, so one load instruction covers 128 members --
+// while the others wait at the workgroup barrier: little polling traffic, no
+// read-modify-write and no tree.  Every wait is bounded: on a timeout, or when another
+// workgroup has flagged an abort, the barrier returns false and the caller leaves the kernel.
 struct BarrierInfo {
-    unsigned *my_flag;          // this workgroup's flag
-    const unsigned *poll_flag;  // flag of member `threadIdx.x` (any valid address if >= C)
+    unsigned *flags;   // the cluster's flags, 8-byte aligned; this workgroup's is flags[rank]
+    int rank;
+    unsigned epoch;    // barriers passed so far (the same in every thread of the cluster)
 };
 
-__device__ inline bool cluster_barrier(HypShared &S, const BarrierInfo &bi, int *abort_flag, int C,
+__device__ inline bool cluster_barrier(HypShared &S, BarrierInfo &bi, int *abort_flag, int C,
                                        long long timeout_ticks)
 {
     // every coherent store / atomic of this wavefront has completed ...
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();   // ... and so have those of the whole workgroup
     if (C <= 1) return true;
-    if (threadIdx.x == 0) {
-        S.epoch += 1;
-        __hip_atomic_store(bi.my_flag, S.epoch, __ATOMIC_RELAXED, TDT_AGENT);
-    }
-    __syncthreads();
-    const unsigned epoch = S.epoch;
-    const long long t0 = wall_clock64();
-    unsigned spins = 0;
-    for (;;) {
-        const unsigned f = __hip_atomic_load(bi.poll_flag, __ATOMIC_RELAXED, TDT_AGENT);
-        if (__syncthreads_and((int)threadIdx.x >= C || (int)(f - epoch) >= 0)) return true;
-        if ((++spins & 31u) == 0u) {   // uniform over the workgroup
-            if (threadIdx.x == 0) {
-                if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, TDT_AGENT)) {
-                    S.aborted = 1;
-                } else if (wall_clock64() - t0 > timeout_ticks) {
-                    __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, TDT_AGENT);
-                    S.aborted = 1;
+    const unsigned epoch = ++bi.epoch;
+    if (threadIdx.x == 0)
+        __hip_atomic_store(bi.flags + (size_t)bi.rank * kBarrierStride, epoch, __ATOMIC_RELAXED, TDT_AGENT);
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        const long long t0 = wall_clock64();
+        unsigned spins = 0;
+        for (;;) {
+            bool all = true;
+            for (int base = 0; base < C; base += 64) {   // uniform
+                const int idx = base + lane;
+                const unsigned f = __hip_atomic_load(bi.flags + (size_t)(idx < C ? idx : 0) * kBarrierStride,
+                                                     __ATOMIC_RELAXED, TDT_AGENT);
+                all = all && (idx >= C || (int)(f - epoch) >= 0);
+            }
+            if (__ballot(!all) == 0ull) break;
+            if ((++spins & 31u) == 0u) {
+                int stop = 0;
+                if (lane == 0) {
+                    if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, TDT_AGENT)) {
+                        stop = 1;
+                    } else if (wall_clock64() - t0 > timeout_ticks) {
+                        __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, TDT_AGENT);
+                        stop = 1;
+                    }
+                }
+                if (__shfl(stop, 0, 64)) {
+                    if (lane == 0) S.aborted = 1;
+                    break;
                 }
             }
-            __syncthreads();
-            if (S.aborted) return false;
         }
     }
+    __syncthreads();
+    return S.aborted == 0;
 }
 
 // list[0..n) = indices g < G with flag[g] set, ascending.  All threads call it.
@@ -622,8 +634,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     A.ldb = ActTile<WT>::row_elems(p.kseg_max);
 
     BarrierInfo bi;
-    bi.my_flag = p.barrier + (size_t)blockIdx.x * kBarrierStride;
-    bi.poll_flag = p.barrier + (size_t)((tid < C ? tid : 0) * ncl + cl) * kBarrierStride;
+    bi.flags = p.barrier + (size_t)cl * C * kBarrierStride;
+    bi.rank = rank;
+    bi.epoch = 0;
     LsePartial *const pbase = p.partials + (size_t)cl * (kPartialEntries / ncl);
     const int rows_cap = p.rows_per_cluster;
     unsigned long long *const rl_base = p.row_lab + (size_t)cl * kRowBufs * rows_cap;
@@ -649,7 +662,6 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     }
     if (tid < TDT_MAX_DURATIONS) S.durations[tid] = p.durations[tid];
     if (tid == 0) {
-        S.epoch = 0;
         S.aborted = 0;
         S.pend_n = 0;
         S.pend_ncg = 0;
@@ -732,8 +744,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     const int ti = it / n_ug, ug = it % n_ug;
                     const int nrows = min(RT, n_act - ti * RT);
                     const int tile0 = ug * tpg, n_ct = min(tpg, NT - tile0);
-                    float c_old = 0.0f;   // this thread's cell value, fetched ahead of the epilogue
-                    float tabv[kTabPerThread];   // ... and its share of the round's table addends
+                    // A round holds up to 8 tiles x 16 rows x 16 pre-activations (4 units x 4 gates
+                    // a tile): entry idx = tid + e * 512 is (tile slot idx / 256, row idx / 16 % 16,
+                    // column idx % 16), so the four gates of a unit sit in four neighbouring lanes.
+                    float c_old[kTabPerThread];   // the unit's cell value (used by the lane of gate 0)
+                    float tabv[kTabPerThread];    // the entry's table addend
                     run_item<WT>(
                         S, A, in, n_ct, folded ? nullptr : bl, bl,
                         [&](const Seg &sg) {
@@ -749,56 +764,41 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             const int unit = (tile0 + ct) * 4 + (j >> 2);
                             return unit < Hp ? (long long)(j & 3) * Hp + unit : -1;
                         },
-                        [&](int base, int n) {
-                            {   // thread -> (tile slot, row, unit) as in the epilogue
-                                const int t = tid >> 6, i = (tid & 63) >> 2, uq = tid & 3;
-                                const int unit = (tile0 + base + t) * 4 + uq;
-                                const bool live = t < n && i < nrows && unit < Hp;
+                        [&](int base, int) {   // loads only; their values are used in the epilogue
+#pragma unroll
+                            for (int e = 0; e < kTabPerThread; ++e) {
+                                const int idx = tid + e * kThreads;
+                                const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
+                                const int unit = (tile0 + base + t) * 4 + (j >> 2);
+                                const int uc = unit < Hp ? unit : 0;
                                 const int g = S.act_list[ti * RT + (i < nrows ? i : 0)];
-                                const float c = ld_co(cst + (size_t)(b0 + g) * Hp + (unit < Hp ? unit : 0));
-                                c_old = live ? c : 0.0f;
-                            }
-                            if (folded) {   // addends of (row i, column j) of every tile of the round
-#pragma unroll
-                                for (int e = 0; e < kTabPerThread; ++e) {
-                                    const int idx = tid + e * kThreads;
-                                    const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
-                                    const int unit = (tile0 + base + t) * 4 + (j >> 2);
-                                    const int g = S.act_list[ti * RT + (i < nrows ? i : 0)];
-                                    tabv[e] = gate_tab[(size_t)S.last[g] * (4 * Hp) + (size_t)(j & 3) * Hp +
-                                                       (unit < Hp ? unit : 0)];
-                                }
+                                c_old[e] = ld_co(cst + (size_t)(b0 + g) * Hp + uc);
+                                tabv[e] = folded ? gate_tab[(size_t)S.last[g] * (4 * Hp) + (size_t)(j & 3) * Hp + uc]
+                                                 : 0.0f;
                             }
                         },
-                        [&](int base, int n) {
-                            if (folded) {
-#pragma unroll
-                                for (int e = 0; e < kTabPerThread; ++e) {
-                                    const int idx = tid + e * kThreads;
-                                    const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
-                                    const int unit = (tile0 + base + t) * 4 + (j >> 2);
-                                    const bool live = t < n && i < nrows && unit < Hp;
-                                    S.tab[t][i][j] = live ? tabv[e] : 0.0f;
-                                }
-                            }
-                        },
+                        [&](int, int) {},
                         [&](int base, int n, int ksplit) {
-                            // thread -> (tile slot, row, unit): all four gates, then the cell update
-                            const int t = tid >> 6, i = (tid & 63) >> 2, uq = tid & 3;
-                            const int unit = (tile0 + base + t) * 4 + uq;
-                            if (t < n && i < nrows && unit < Hp) {
-                                float gate[4];
 #pragma unroll
-                                for (int q = 0; q < 4; ++q)
-                                    gate[q] = cpart_sum(S, t, ksplit, i, uq * 4 + q) + S.bias[t * CT + uq * 4 + q] +
-                                              (folded ? S.tab[t][i][uq * 4 + q] : 0.0f);
-                                const int g = S.act_list[ti * RT + i];
-                                const size_t o = (size_t)(b0 + g) * Hp + unit;
-                                const float ig = sigmoidf_dev(gate[0]), fg = sigmoidf_dev(gate[1]);
-                                const float gg = tanhf(gate[2]), og = sigmoidf_dev(gate[3]);
-                                const float cn = fg * c_old + ig * gg;
-                                st_co(cst + o, cn);
-                                st_co(h_next + o, og * tanhf(cn));
+                            for (int e = 0; e < kTabPerThread; ++e) {
+                                const int idx = tid + e * kThreads;
+                                const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15, q = j & 3;
+                                if (t < n) {   // uniform over the wavefront
+                                    const int unit = (tile0 + base + t) * 4 + (j >> 2);
+                                    const float pre = cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j] + tabv[e];
+                                    // gates 0, 1, 3: sigmoid(x); gate 2: tanh(x) = 2 sigmoid(2x) - 1
+                                    const float sg = fast_sigmoid(q == 2 ? 2.0f * pre : pre);
+                                    const float act = q == 2 ? 2.0f * sg - 1.0f : sg;
+                                    const float fg = __shfl_down(act, 1, 4), gg = __shfl_down(act, 2, 4);
+                                    const float og = __shfl_down(act, 3, 4);
+                                    if (q == 0 && i < nrows && unit < Hp) {
+                                        const float cn = fg * c_old[e] + act * gg;
+                                        const int g = S.act_list[ti * RT + i];
+                                        const size_t o = (size_t)(b0 + g) * Hp + unit;
+                                        st_co(cst + o, cn);
+                                        st_co(h_next + o, og * (2.0f * fast_sigmoid(2.0f * cn) - 1.0f));
+                                    }
+                                }
                             }
                         });
                 }

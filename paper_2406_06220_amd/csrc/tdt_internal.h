@@ -16,7 +16,7 @@ constexpr int kMaxRowsPerPass = 1024;         // (hypothesis, frame) rows of one
 constexpr int kMaxColGroups = 64;             // output-column slices of one joint pass
 constexpr int kMaxWindow = 64;                // frames of one hypothesis per joint pass
 constexpr int kPartialEntries = kMaxRowsPerPass * kMaxGrid;  // per partial buffer
-constexpr int kBarrierStride = 16;            // uint32 slots between two workgroups' barrier flags
+constexpr int kBarrierStride = 32;            // uint32 slots between two workgroups' barrier flags
 constexpr int kRowBufs = 3;                   // rotating per-row argmax buffers
 
 // Softmax-denominator share of one slice of label columns for one joint row.
@@ -60,7 +60,7 @@ struct DecodeParams {
     unsigned long long *row_lab;  // [n_clusters][kRowBufs][rows_per_cluster] packed (logit, ~label)
     unsigned long long *row_dur;  // same shape, packed (logit, ~duration class)
     int rows_per_cluster;
-    unsigned *barrier;       // [kMaxGrid][kBarrierStride]: one flag word per workgroup
+    unsigned *barrier;       // one flag word per workgroup, a cluster's flags side by side
     int *abort_flag;
     long long timeout_ticks; // bound on one wait, in wall-clock ticks
 };
