@@ -195,31 +195,38 @@ __device__ inline float unpack_value(unsigned long long p)
     return __uint_as_float(u);
 }
 
-// Barrier over the C workgroups of one cluster.  Every workgroup owns one flag word in a
-// dense array; to arrive it stores the barrier's sequence number there (after all its
-// earlier coherent stores have completed), and it leaves once the flags of all C members
-// have reached that number.  Only the first wavefront polls -- a lane reads two
-// neighbouring flags with one 8-byte load, so one load instruction covers 128 members --
-// while the others wait at the workgroup barrier: little polling traffic, no
-// read-modify-write and no tree.  Every wait is bounded: on a timeout, or when another
-// workgroup has flagged an abort, the barrier returns false and the caller leaves the kernel.
+// Barrier over the C workgroups of one cluster, in two halves.  Every workgroup owns one
+// flag word, a cache line apart from the next.  To arrive it stores the barrier's sequence
+// number there, after all its earlier coherent stores have completed.  To wait, its first
+// wavefront polls the flags of all C members (lane l reads member l, l + 64, ...) until they
+// have reached that number, while the other wavefronts rest at the workgroup barrier: little
+// polling traffic, no read-modify-write and no tree.  Work that does not depend on what the
+// other workgroups wrote (setting up the next work item, fetching weights) goes between the
+// two halves and hides the flags' way through memory.  Every wait is bounded: on a timeout,
+// or when another workgroup has flagged an abort, the wait returns false and the caller
+// leaves the kernel.
 struct BarrierInfo {
-    unsigned *flags;   // the cluster's flags, 8-byte aligned; this workgroup's is flags[rank]
+    unsigned *flags;   // the cluster's flags; this workgroup's is flags[rank * kBarrierStride]
     int rank;
-    unsigned epoch;    // barriers passed so far (the same in every thread of the cluster)
+    unsigned epoch;    // barriers arrived at so far (the same in every thread of the cluster)
 };
 
-__device__ inline bool cluster_barrier(HypShared &S, BarrierInfo &bi, int *abort_flag, int C,
-                                       long long timeout_ticks)
+__device__ inline void barrier_arrive(BarrierInfo &bi, int C)
 {
     // every coherent store / atomic of this wavefront has completed ...
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();   // ... and so have those of the whole workgroup
-    if (C <= 1) return true;
     const unsigned epoch = ++bi.epoch;
-    if (threadIdx.x == 0)
+    if (C > 1 && threadIdx.x == 0)
         __hip_atomic_store(bi.flags + (size_t)bi.rank * kBarrierStride, epoch, __ATOMIC_RELAXED, TDT_AGENT);
-    if (threadIdx.x < 64) {
+}
+
+// ends with a workgroup barrier
+__device__ inline bool barrier_wait(HypShared &S, const BarrierInfo &bi, int *abort_flag, int C,
+                                    long long timeout_ticks)
+{
+    const unsigned epoch = bi.epoch;
+    if (C > 1 && threadIdx.x < 64) {
         const int lane = threadIdx.x;
         const long long t0 = wall_clock64();
         unsigned spins = 0;
@@ -251,6 +258,13 @@ __device__ inline bool cluster_barrier(HypShared &S, BarrierInfo &bi, int *abort
     }
     __syncthreads();
     return S.aborted == 0;
+}
+
+__device__ inline bool cluster_barrier(HypShared &S, BarrierInfo &bi, int *abort_flag, int C,
+                                       long long timeout_ticks)
+{
+    barrier_arrive(bi, C);
+    return barrier_wait(S, bi, abort_flag, C, timeout_ticks);
 }
 
 // list[0..n) = indices g < G with flag[g] set, ascending.  All threads call it.
@@ -543,16 +557,19 @@ template <> struct Backend<float> {
 //                                  rows are staged: issues loads whose latency should hide there
 //   park(ct0, n)                   called by all threads after the round's products, before the
 //                                  barrier that precedes epi: may put what pre loaded into LDS
+//   wait()                         called by all threads once, before the first rows are staged
+//                                  (after the first weights have been requested); must contain
+//                                  a workgroup barrier
 //   epi(ct0, n, ksplit)            called by all threads once S.cpart holds round results:
 //                                  tile slot t (< n) is the sum over kp < ksplit of
 //                                  S.cpart[t * ksplit + kp]; S.bias[t * 16 + j] is
 //                                  bias[rowidx(ct0 + t, j)]
 // With one segment the rows are staged once; with several they are staged again for
 // every round.
-template <typename WT, typename StageF, typename RowF, typename PreF, typename ParkF, typename EpiF>
+template <typename WT, typename StageF, typename RowF, typename PreF, typename ParkF, typename EpiF, typename WaitF>
 __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseInputs &in, int n_ct,
                                 const float *__restrict__ bias, const float *any_floats, StageF stage,
-                                RowF rowidx, PreF pre_round, ParkF park, EpiF epi)
+                                RowF rowidx, PreF pre_round, ParkF park, EpiF epi, WaitF wait)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nseg = in.count();
@@ -584,7 +601,9 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
             // the weights do not depend on the activations: fetch the first of them now
             if (mine) Backend<WT>::prefetch(pre, sg, rowidx, ct, kpart, ksplit, lane);
             if (nseg > 1 || base == 0) {
-                __syncthreads();   // previous readers of the tile are done
+                // previous readers of the tile are done
+                if (base == 0 && sgi == 0) wait();
+                else __syncthreads();
                 stage(sg);
                 __syncthreads();
             }
@@ -708,6 +727,22 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     int pp = 0;          // which half of hbuf holds the current hidden state
     unsigned jpass = 0;  // joint passes so far (selects the exchange buffers)
     bool ok = true;
+    // A barrier this workgroup has arrived at but not yet waited for, and the timer bucket of
+    // the phase that runs meanwhile.  The wait happens where the next phase first needs what
+    // the other workgroups wrote: before its first rows are staged (run_item's wait hook), or
+    // after its item loop in a workgroup that got no item.
+    bool bar_pending = false;
+    long long *phase_bucket = &tk_p;
+    auto finish_barrier = [&]() {
+        lap(*phase_bucket);
+        ok = barrier_wait(S, bi, p.abort_flag, C, p.timeout_ticks) && ok;
+        lap(tk_bar);
+        bar_pending = false;
+    };
+    auto wait_hook = [&]() {
+        if (bar_pending) finish_barrier();   // uniform over the workgroup
+        else __syncthreads();
+    };
 
     while (ok) {   // ---- Alg. 3 line 5: while any hypothesis is active
         build_list(S, S.active, G, S.act_list, &S.n_act);
@@ -720,6 +755,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 
         // ---- P: predictor step (Alg. 3 line 6)
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 0;
+        phase_bucket = &tk_p;
         if (lstm) {
             for (int l = 0; l < L && ok; ++l) {
                 const int in_dim = l == 0 ? E : Hp;
@@ -800,17 +836,21 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                     }
                                 }
                             }
-                        });
+                        },
+                        wait_hook);
                 }
+                if (bar_pending) finish_barrier();
+                if (!ok) break;
                 lap(tk_p);
-                ok = cluster_barrier(S, bi, p.abort_flag, C, p.timeout_ticks);
-                lap(tk_bar);
+                barrier_arrive(bi, C);
+                bar_pending = true;
             }
             if (!ok) break;
         }
 
         // ---- Q: predictor output into the joint space (Sec. 3.4)
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 1;
+        phase_bucket = &tk_q;
         {
             const float *dec_src = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * B * Hp : nullptr;
             PhaseInputs in;
@@ -866,15 +906,18 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 st_co(p.pred_proj + (size_t)(b0 + S.act_list[ti * RT + i]) * H + col,
                                       cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j]);
                         }
-                    });
+                    },
+                    wait_hook);
             }
-            lap(tk_q);
-            ok = cluster_barrier(S, bi, p.abort_flag, C, p.timeout_ticks);
-            lap(tk_bar);
+            if (bar_pending) finish_barrier();
             if (!ok) break;
+            lap(tk_q);
+            barrier_arrive(bi, C);
+            bar_pending = true;
         }
 
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 2;
+        phase_bucket = &tk_j;
         // every active hypothesis now searches for its next non-blank label
         for (int g = tid; g < G; g += kThreads) S.need[g] = S.active[g];
         __syncthreads();
@@ -1015,7 +1058,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 rda = da;
                             }
                         }
-                    });
+                    },
+                    wait_hook);
                 if ((tid & 31) == 0 && ti * RT + (tid >> 5) < M) {
                     const int r = ti * RT + (tid >> 5);
                     if (rs > 0.0f)
@@ -1027,6 +1071,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     st_co64(reinterpret_cast<unsigned long long *>(pbuf + (size_t)r * n_cg + cg), lp);
                 }
             }
+            if (bar_pending) finish_barrier();
+            if (!ok) break;
             lap(tk_j);
             ok = cluster_barrier(S, bi, p.abort_flag, C, p.timeout_ticks);
             lap(tk_bar);
