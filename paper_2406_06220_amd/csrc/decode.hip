@@ -97,6 +97,10 @@ struct HypShared {
     float pend_m[kDeferred];
     unsigned char pend_found[kDeferred];
     int aborted;
+    // kept by thread 0 only: work counters and wall-clock ticks per phase
+    long long st[5];   // predictor passes, predictor rows, joint passes, joint rows, label-loop iterations
+    long long tk[5];   // P, Q, J, D, barrier
+    long long tk_last, tk_start;
     // thread 0 (profiling builds): ticks spent staging / multiplying / in epilogues, per phase P, Q, J
     long long tk_fine[3][3];
     int fine_phase;
@@ -690,14 +694,17 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     }
     __syncthreads();
 
-    long long st_pred_pass = 0, st_pred_rows = 0, st_joint_pass = 0, st_joint_rows = 0, st_outer = 0;
-    long long tk_p = 0, tk_q = 0, tk_j = 0, tk_d = 0, tk_bar = 0;   // wall-clock ticks per phase
-    long long tk0 = wall_clock64();
-    const long long tk_start = tk0;
-    auto lap = [&](long long &bucket) {
-        const long long now = wall_clock64();
-        bucket += now - tk0;
-        tk0 = now;
+    enum { kTkP = 0, kTkQ, kTkJ, kTkD, kTkBar };
+    if (tid == 0) {
+        for (int a = 0; a < 5; ++a) S.st[a] = S.tk[a] = 0;
+        S.tk_last = S.tk_start = wall_clock64();
+    }
+    auto lap = [&](int bucket) {   // thread 0 books the time since the last call
+        if (tid == 0) {
+            const long long now = wall_clock64();
+            S.tk[bucket] += now - S.tk_last;
+            S.tk_last = now;
+        }
     };
     // softmax partials of the rows chosen in the last decision step, still to be summed
     unsigned long long pend_u[kDeferPerWave];
@@ -732,11 +739,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     // the other workgroups wrote: before its first rows are staged (run_item's wait hook), or
     // after its item loop in a workgroup that got no item.
     bool bar_pending = false;
-    long long *phase_bucket = &tk_p;
+    int phase_bucket = kTkP;
     auto finish_barrier = [&]() {
-        lap(*phase_bucket);
+        lap(phase_bucket);
         ok = barrier_wait(S, bi, p.abort_flag, C, p.timeout_ticks) && ok;
-        lap(tk_bar);
+        lap(kTkBar);
         bar_pending = false;
     };
     auto wait_hook = [&]() {
@@ -748,14 +755,16 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         build_list(S, S.active, G, S.act_list, &S.n_act);
         const int n_act = S.n_act;
         if (n_act == 0) break;
-        ++st_outer;
-        ++st_pred_pass;
-        st_pred_rows += n_act;
+        if (tid == 0) {
+            S.st[4] += 1;
+            S.st[0] += 1;
+            S.st[1] += n_act;
+        }
         const int n_tiles_a = (n_act + RT - 1) / RT;
 
         // ---- P: predictor step (Alg. 3 line 6)
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 0;
-        phase_bucket = &tk_p;
+        phase_bucket = kTkP;
         if (lstm) {
             for (int l = 0; l < L && ok; ++l) {
                 const int in_dim = l == 0 ? E : Hp;
@@ -841,7 +850,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 }
                 if (bar_pending) finish_barrier();
                 if (!ok) break;
-                lap(tk_p);
+                lap(kTkP);
                 barrier_arrive(bi, C);
                 bar_pending = true;
             }
@@ -850,7 +859,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 
         // ---- Q: predictor output into the joint space (Sec. 3.4)
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 1;
-        phase_bucket = &tk_q;
+        phase_bucket = kTkQ;
         {
             const float *dec_src = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * B * Hp : nullptr;
             PhaseInputs in;
@@ -911,13 +920,13 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             }
             if (bar_pending) finish_barrier();
             if (!ok) break;
-            lap(tk_q);
+            lap(kTkQ);
             barrier_arrive(bi, C);
             bar_pending = true;
         }
 
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 2;
-        phase_bucket = &tk_j;
+        phase_bucket = kTkJ;
         // every active hypothesis now searches for its next non-blank label
         for (int g = tid; g < G; g += kThreads) S.need[g] = S.active[g];
         __syncthreads();
@@ -957,8 +966,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 }
             }
             ++jpass;
-            ++st_joint_pass;
-            st_joint_rows += M;
+            if (tid == 0) {
+                S.st[2] += 1;
+                S.st[3] += M;
+            }
 
             // ---- J: joint network on M rows
             PhaseInputs in;
@@ -1073,9 +1084,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             }
             if (bar_pending) finish_barrier();
             if (!ok) break;
-            lap(tk_j);
+            lap(kTkJ);
             ok = cluster_barrier(S, bi, p.abort_flag, C, p.timeout_ticks);
-            lap(tk_bar);
+            lap(kTkBar);
             if (!ok) break;
 
             // ---- D: every workgroup takes the same decisions from the same cells
@@ -1220,7 +1231,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             }
             __syncthreads();
             build_list(S, S.need, G, S.need_list, &S.n_need);
-            lap(tk_d);
+            lap(kTkD);
         }
         if (!ok) break;
         pp ^= 1;
@@ -1240,19 +1251,19 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             auto add = [&](int slot, long long v) {
                 atomicAdd((unsigned long long *)&p.out_stats[slot], (unsigned long long)v);
             };
-            add(TDT_STAT_PRED_PASSES, st_pred_pass);
-            add(TDT_STAT_PRED_ROWS, st_pred_rows);
-            add(TDT_STAT_JOINT_PASSES, st_joint_pass);
-            add(TDT_STAT_JOINT_ROWS, st_joint_rows);
-            atomicMax((unsigned long long *)&p.out_stats[TDT_STAT_OUTER_MAX], (unsigned long long)st_outer);
+            add(TDT_STAT_PRED_PASSES, S.st[0]);
+            add(TDT_STAT_PRED_ROWS, S.st[1]);
+            add(TDT_STAT_JOINT_PASSES, S.st[2]);
+            add(TDT_STAT_JOINT_ROWS, S.st[3]);
+            atomicMax((unsigned long long *)&p.out_stats[TDT_STAT_OUTER_MAX], (unsigned long long)S.st[4]);
             if (!ok) add(TDT_STAT_ABORT, 1);
             if (cl == 0) {   // where the first cluster's time went, in wall-clock ticks
-                add(TDT_STAT_TICKS_PRED, tk_p);
-                add(TDT_STAT_TICKS_PROJ, tk_q);
-                add(TDT_STAT_TICKS_JOINT, tk_j);
-                add(TDT_STAT_TICKS_DECIDE, tk_d);
-                add(TDT_STAT_TICKS_BARRIER, tk_bar);
-                add(TDT_STAT_TICKS_TOTAL, wall_clock64() - tk_start);
+                add(TDT_STAT_TICKS_PRED, S.tk[kTkP]);
+                add(TDT_STAT_TICKS_PROJ, S.tk[kTkQ]);
+                add(TDT_STAT_TICKS_JOINT, S.tk[kTkJ]);
+                add(TDT_STAT_TICKS_DECIDE, S.tk[kTkD]);
+                add(TDT_STAT_TICKS_BARRIER, S.tk[kTkBar]);
+                add(TDT_STAT_TICKS_TOTAL, wall_clock64() - S.tk_start);
                 for (int a = 0; a < 3; ++a)
                     for (int b = 0; b < 3; ++b) add(TDT_STAT_TICKS_FINE + a * 3 + b, S.tk_fine[a][b]);
             }
