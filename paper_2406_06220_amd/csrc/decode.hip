@@ -766,22 +766,48 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 0;
         phase_bucket = kTkP;
         if (lstm) {
-            for (int l = 0; l < L && ok; ++l) {
-                const int in_dim = l == 0 ? E : Hp;
+            {
+                // Layer 0 needs no product here.  W_ih * emb[label] + b is a row of the table that
+                // the host-side call built before this kernel, and W_hh * h was computed right
+                // after h itself (phase Q of the previous label, below), before the label was
+                // known.  What is left is the cell update, one thread per (hypothesis, unit).
+                float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L) * B * Hp;
+                float *cst = p.cbuf;
+                const int total = n_act * Hp;
+                const int per_wg = (total + C - 1) / C;
+                const int c_end = min(total, (rank + 1) * per_wg);
+                for (int c = rank * per_wg + tid; c < c_end; c += kThreads) {
+                    const int i = c / Hp, unit = c - i * Hp;
+                    const int g = S.act_list[i];
+                    const size_t o = (size_t)(b0 + g) * Hp + unit;
+                    const float2 r01 = ld_co2(p.rgate + o * 4), r23 = ld_co2(p.rgate + o * 4 + 2);
+                    const float4 t4 =
+                        *reinterpret_cast<const float4 *>(p.emb_gates + ((size_t)S.last[g] * Hp + unit) * 4);
+                    const float c_old = ld_co(cst + o);
+                    const float ig = fast_sigmoid(r01.x + t4.x), fg = fast_sigmoid(r01.y + t4.y);
+                    const float gg = 2.0f * fast_sigmoid(2.0f * (r23.x + t4.z)) - 1.0f;
+                    const float og = fast_sigmoid(r23.y + t4.w);
+                    const float cn = fg * c_old + ig * gg;
+                    st_co(cst + o, cn);
+                    st_co(h_next + o, og * (2.0f * fast_sigmoid(2.0f * cn) - 1.0f));
+                }
+                if (bar_pending) finish_barrier();
+                if (!ok) break;
+                lap(kTkP);
+                barrier_arrive(bi, C);
+                bar_pending = true;
+            }
+            for (int l = 1; l < L && ok; ++l) {   // deeper layers: [W_ih, W_hh] . [h of the layer below, own h]
                 const float *bl = p.b_lstm[l];
                 const float *h_cur = p.hbuf + ((size_t)pp * L + l) * B * Hp;
                 float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L + l) * B * Hp;
-                const float *x_prev = l > 0 ? p.hbuf + ((size_t)(pp ^ 1) * L + (l - 1)) * B * Hp : nullptr;
+                const float *x_prev = p.hbuf + ((size_t)(pp ^ 1) * L + (l - 1)) * B * Hp;
                 float *cst = p.cbuf + (size_t)l * B * Hp;
-                // Layer 0: W_ih * emb[label] + b is a row of the table the host-side call built
-                // before this kernel, so only the recurrent product is left.
-                const bool folded = l == 0;
-                const float *gate_tab = p.emb_gates;   // [V+1][4*Hp]
                 PhaseInputs in;
-                in.w0 = folded ? p.w_hh[l] : p.w_ih[l];
-                in.K0 = folded ? Hp : in_dim;
-                in.w1 = folded ? nullptr : p.w_hh[l];
-                in.K1 = folded ? 0 : Hp;
+                in.w0 = p.w_ih[l];
+                in.K0 = Hp;
+                in.w1 = p.w_hh[l];
+                in.K1 = Hp;
                 const int NT = (Hp + 3) / 4;   // a column tile = 4 hidden units x 4 gates
                 int n_ug, tpg;
                 split_tiles(C, n_tiles_a, NT, NT, n_ug, tpg);
@@ -793,12 +819,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     // a tile): entry idx = tid + e * 512 is (tile slot idx / 256, row idx / 16 % 16,
                     // column idx % 16), so the four gates of a unit sit in four neighbouring lanes.
                     float c_old[kTabPerThread];   // the unit's cell value (used by the lane of gate 0)
-                    float tabv[kTabPerThread];    // the entry's table addend
                     run_item<WT>(
-                        S, A, in, n_ct, folded ? nullptr : bl, bl,
+                        S, A, in, n_ct, bl, bl,
                         [&](const Seg &sg) {
                             const int k0 = sg.k0;
-                            const float *src = (folded || sg.part == 1) ? h_cur : x_prev;
+                            const float *src = sg.part == 1 ? h_cur : x_prev;
                             stage_segment<WT>(
                                 A, sg.K, nrows,
                                 [&](int i) { return src + (size_t)(b0 + S.act_list[ti * RT + i]) * Hp + k0; },
@@ -815,11 +840,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 const int idx = tid + e * kThreads;
                                 const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
                                 const int unit = (tile0 + base + t) * 4 + (j >> 2);
-                                const int uc = unit < Hp ? unit : 0;
                                 const int g = S.act_list[ti * RT + (i < nrows ? i : 0)];
-                                c_old[e] = ld_co(cst + (size_t)(b0 + g) * Hp + uc);
-                                tabv[e] = folded ? gate_tab[(size_t)S.last[g] * (4 * Hp) + (size_t)(j & 3) * Hp + uc]
-                                                 : 0.0f;
+                                c_old[e] = ld_co(cst + (size_t)(b0 + g) * Hp + (unit < Hp ? unit : 0));
                             }
                         },
                         [&](int, int) {},
@@ -830,7 +852,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15, q = j & 3;
                                 if (t < n) {   // uniform over the wavefront
                                     const int unit = (tile0 + base + t) * 4 + (j >> 2);
-                                    const float pre = cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j] + tabv[e];
+                                    const float pre = cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j];
                                     // gates 0, 1, 3: sigmoid(x); gate 2: tanh(x) = 2 sigmoid(2x) - 1
                                     const float sg = fast_sigmoid(q == 2 ? 2.0f * pre : pre);
                                     const float act = q == 2 ? 2.0f * sg - 1.0f : sg;
@@ -857,31 +879,40 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             if (!ok) break;
         }
 
-        // ---- Q: predictor output into the joint space (Sec. 3.4)
+        // ---- Q: everything that is a product with the new predictor state: its projection into
+        // the joint space (Sec. 3.4), and for an LSTM the recurrent part W_hh * h of the first
+        // layer's next step.  Two sections of column tiles, each with its matrix and its input.
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 1;
         phase_bucket = kTkQ;
         {
-            const float *dec_src = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * B * Hp : nullptr;
-            PhaseInputs in;
-            in.w0 = p.w_pred;
-            in.K0 = Hp;
-            in.w1 = nullptr;
-            in.K1 = 0;
-            const int NT = (H + CT - 1) / CT;
-            int n_cg, tpg;
-            split_tiles(C, n_tiles_a, NT, NT, n_cg, tpg);
-            for (int it = rank; it < n_tiles_a * n_cg; it += C) {
-                const int ti = it / n_cg, cg = it % n_cg;
+            const float *src_a = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * B * Hp : nullptr;
+            const float *src_b = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L) * B * Hp : nullptr;
+            const int NT_A = (H + CT - 1) / CT, NT_B = lstm ? (Hp + 3) / 4 : 0;
+            // fewest tiles per work item that give every workgroup at most one item
+            int tpg = ((NT_A + NT_B) * n_tiles_a + C - 1) / C;
+            while (((NT_A + tpg - 1) / tpg + (NT_B + tpg - 1) / tpg) * n_tiles_a > C && tpg < NT_A + NT_B) ++tpg;
+            const int g_a = (NT_A + tpg - 1) / tpg, g_b = (NT_B + tpg - 1) / tpg;
+            const int n_grp = g_a + g_b;
+            for (int it = rank; it < n_tiles_a * n_grp; it += C) {
+                const int ti = it / n_grp, grp = it % n_grp;
+                const bool sec_b = grp >= g_a;
                 const int nrows = min(RT, n_act - ti * RT);
-                const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
+                const int tile0 = (sec_b ? grp - g_a : grp) * tpg;
+                const int n_ct = min(tpg, (sec_b ? NT_B : NT_A) - tile0);
+                const float *src = sec_b ? src_b : src_a;
+                PhaseInputs in;
+                in.w0 = sec_b ? p.w_hh[0] : p.w_pred;
+                in.K0 = Hp;
+                in.w1 = nullptr;
+                in.K1 = 0;
                 run_item<WT>(
-                    S, A, in, n_ct, p.b_pred, p.b_pred,
+                    S, A, in, n_ct, sec_b ? nullptr : p.b_pred, p.b_pred,
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
                         if (lstm) {
                             stage_segment<WT>(
                                 A, sg.K, nrows,
-                                [&](int i) { return dec_src + (size_t)(b0 + S.act_list[ti * RT + i]) * Hp + k0; },
+                                [&](int i) { return src + (size_t)(b0 + S.act_list[ti * RT + i]) * Hp + k0; },
                                 [](const float *row, int k) { return ld_co2(row + k); },
                                 [](const float *, int, float2 v) { return v; });
                         } else {
@@ -902,6 +933,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         }
                     },
                     [&](int ct, int j) -> long long {
+                        if (sec_b) {   // a column tile = 4 hidden units x 4 gates
+                            const int unit = (tile0 + ct) * 4 + (j >> 2);
+                            return unit < Hp ? (long long)(j & 3) * Hp + unit : -1;
+                        }
                         const int n = (tile0 + ct) * CT + j;
                         return n < H ? n : -1;
                     },
@@ -910,10 +945,16 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     [&](int base, int n, int ksplit) {
                         for (int idx = tid; idx < n * RT * CT; idx += kThreads) {
                             const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
-                            const int col = (tile0 + base + t) * CT + j;
-                            if (i < nrows && col < H)
-                                st_co(p.pred_proj + (size_t)(b0 + S.act_list[ti * RT + i]) * H + col,
-                                      cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j]);
+                            if (i >= nrows) continue;
+                            const size_t b = (size_t)(b0 + S.act_list[ti * RT + i]);
+                            const float v = cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j];
+                            if (sec_b) {   // [hypothesis][unit][gate]
+                                const int unit = (tile0 + base + t) * 4 + (j >> 2);
+                                if (unit < Hp) st_co(p.rgate + (b * Hp + unit) * 4 + (j & 3), v);
+                            } else {
+                                const int col = (tile0 + base + t) * CT + j;
+                                if (col < H) st_co(p.pred_proj + b * H + col, v);
+                            }
                         }
                     },
                     wait_hook);

@@ -25,7 +25,7 @@ __device__ inline int lds_off(int row, int chunk) { return row * BK + ((chunk ^ 
 
 __global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
-    float *__restrict__ C, long long M, int N, int K)
+    float *__restrict__ C, long long M, int N, int K, int group)
 {
     __shared__ __align__(16) uint16_t As[BM * BK];
     __shared__ __align__(16) uint16_t Bs[BN * BK];
@@ -104,10 +104,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(
             const int n = n0 + wn * 64 + j * 32 + (lane & 31);
             if (n >= N) continue;
             const float bn = bias[n];
+            const int nc = group > 0 ? (n % group) * (N / group) + n / group : n;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const long long m = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                if (m < M) C[m * N + n] = acc[i][j][e] + bn;
+                if (m < M) C[m * N + nc] = acc[i][j][e] + bn;
             }
         }
 }
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(
 // float32 models (small): classic 64x64 tile, 4x4 outputs per thread.
 __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
     const float *__restrict__ A, const float *__restrict__ W, const float *__restrict__ bias,
-    float *__restrict__ C, long long M, int N, int K)
+    float *__restrict__ C, long long M, int N, int K, int group)
 {
     __shared__ float As[16][65];
     __shared__ float Ws[16][65];
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + tx * 4 + j;
-            if (n < N) C[m * N + n] = acc[i][j] + bias[n];
+            if (n < N) C[m * N + (group > 0 ? (n % group) * (N / group) + n / group : n)] = acc[i][j] + bias[n];
         }
     }
 }
@@ -165,18 +166,18 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
 }  // namespace
 
 hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
-                         int dtype, float *out, hipStream_t stream)
+                         int dtype, int group, float *out, hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;
     if (dtype == 1) {
         dim3 grid((unsigned)(((N + BN - 1) / BN) * ((rows + BM - 1) / BM)));
         hipLaunchKernelGGL(enc_proj_bf16_kernel, grid, dim3(GEMM_THREADS), 0, stream,
                            static_cast<const uint16_t *>(a), static_cast<const uint16_t *>(w), bias, out,
-                           (long long)rows, N, K);
+                           (long long)rows, N, K, group);
     } else {
         dim3 grid((unsigned)(((N + 63) / 64) * ((rows + 63) / 64)));
         hipLaunchKernelGGL(enc_proj_f32_kernel, grid, dim3(256), 0, stream, static_cast<const float *>(a),
-                           static_cast<const float *>(w), bias, out, (long long)rows, N, K);
+                           static_cast<const float *>(w), bias, out, (long long)rows, N, K, group);
     }
     return hipGetLastError();
 }
@@ -184,7 +185,7 @@ hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int 
 hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,
                                      float *out, hipStream_t stream)
 {
-    return launch_linear(enc, rows, w->d_enc, w->w_enc, w->h_joint, w->b_enc, w->dtype, out, stream);
+    return launch_linear(enc, rows, w->d_enc, w->w_enc, w->h_joint, w->b_enc, w->dtype, 0, out, stream);
 }
 
 }  // namespace tdt

@@ -34,6 +34,8 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T)
     off = align_up(off + 2 * lstm_layers * B * w->h_pred * sizeof(float), 256);
     L.cbuf = off;
     off = align_up(off + lstm_layers * B * w->h_pred * sizeof(float), 256);
+    L.rgate = off;
+    if (lstm_layers > 0) off = align_up(off + (size_t)B * 4 * w->h_pred * sizeof(float), 256);
     L.barrier = off;
     off = align_up(off + (size_t)kMaxGrid * kBarrierStride * sizeof(unsigned), 256);
     L.abort_flag = off;
@@ -168,10 +170,12 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     if (!reuse_enc_proj) {
         if (launch_encoder_projection(enc, (int64_t)B * T, weights, enc_proj, s) != hipSuccess)
             return TDT_ERR_LAUNCH;
-        // first LSTM layer: its input product depends on the label only, so it is a table
+        // first LSTM layer: its input product depends on the label only, so it is a table,
+        // stored [label][unit][gate]
         if (weights->pred_kind == TDT_PRED_LSTM &&
             launch_linear(weights->emb, weights->vocab + 1, weights->emb_dim, weights->w_ih[0],
-                          4 * weights->h_pred, weights->b_lstm[0], weights->dtype, emb_gates, s) != hipSuccess)
+                          4 * weights->h_pred, weights->b_lstm[0], weights->dtype, weights->h_pred, emb_gates,
+                          s) != hipSuccess)
             return TDT_ERR_LAUNCH;
     }
 
@@ -215,6 +219,7 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     p.out_stats = reinterpret_cast<long long *>(out_stats);
     p.hbuf = reinterpret_cast<float *>(ws + L.hbuf);
     p.cbuf = reinterpret_cast<float *>(ws + L.cbuf);
+    p.rgate = reinterpret_cast<float *>(ws + L.rgate);
     p.pred_proj = reinterpret_cast<float *>(ws + L.pred_proj);
     p.partials = reinterpret_cast<LsePartial *>(ws + L.partials);
     p.row_lab = reinterpret_cast<unsigned long long *>(ws + L.row_lab);

@@ -46,7 +46,7 @@ struct DecodeParams {
     const float *b_out;
     // inputs
     const float *enc_proj;   // [B][T][H]
-    const float *emb_gates;  // [V+1][4*h_pred]: w_ih[0] * emb[label] + b_lstm[0] (LSTM only)
+    const float *emb_gates;  // [V+1][h_pred][4 gates]: w_ih[0] * emb[label] + b_lstm[0] (LSTM only)
     const int32_t *enc_len;  // [B]
     // outputs
     int32_t *out_labels, *out_frames, *out_len, *out_status;
@@ -55,6 +55,7 @@ struct DecodeParams {
     // workspace
     float *hbuf;             // [2][layers][B][h_pred]  ping-pong hidden state
     float *cbuf;             // [layers][B][h_pred]
+    float *rgate;            // [B][h_pred][4]: W_hh[0] . h of the first layer, for its next step
     float *pred_proj;        // [B][H]
     LsePartial *partials;    // [2][kPartialEntries]
     unsigned long long *row_lab;  // [n_clusters][kRowBufs][rows_per_cluster] packed (logit, ~label)
@@ -66,7 +67,7 @@ struct DecodeParams {
 };
 
 struct WorkspaceLayout {
-    size_t enc_proj, emb_gates, hbuf, cbuf, pred_proj, partials, row_lab, row_dur, barrier, abort_flag, total;
+    size_t enc_proj, emb_gates, hbuf, cbuf, rgate, pred_proj, partials, row_lab, row_dur, barrier, abort_flag, total;
     size_t row_entries;            // uint64 entries in each of row_lab / row_dur
     size_t zero_begin, zero_end;   // byte range the init kernel clears
 };
@@ -76,9 +77,11 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T);
 // launches (each returns a hipError_t)
 hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,
                                      float *out, hipStream_t stream);
-// out[r][n] = sum_k a[r][k] * w[n][k] + bias[n]; a and w in the model's dtype, out float32
+// out[r][c(n)] = sum_k a[r][k] * w[n][k] + bias[n]; a and w in the model's dtype, out float32.
+// c(n) = n, or with group > 0 (N a multiple of group): c(n) = (n % group) * (N / group) + n / group,
+// which puts the N / group outputs n, n + group, n + 2 group, ... side by side.
 hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
-                         int dtype, float *out, hipStream_t stream);
+                         int dtype, int group, float *out, hipStream_t stream);
 hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats,
                        hipStream_t stream);
 hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid, hipStream_t stream);
