@@ -11,8 +11,13 @@
 // the cluster's workgroups and separated by cluster-wide barriers:
 //
 //   P  predictor step     LSTM layer(s) for the hypotheses that are still active
-//                         (Alg. 3 line 6; the state is kept for every row)
-//   Q  predictor projection into the joint space (Sec. 3.4)
+//                         (Alg. 3 line 6; the state is kept for every row).  The
+//                         first layer is only a cell update here: its input
+//                         product is a per-label table row, its recurrent product
+//                         was formed in phase Q of the previous label.
+//   Q  products with the new predictor state: the projection into the joint
+//                         space (Sec. 3.4) and W_hh . h of the first LSTM layer
+//                         for the next label, which does not depend on that label
 //   J  joint pass         relu(enc_proj[b, t..t+W) + pred_proj[b]) . w_out, scored
 //                         for a window of W upcoming frames of every hypothesis
 //                         that still searches for its next non-blank label
@@ -37,7 +42,7 @@
 //
 // Exchange between workgroups.  Data one workgroup writes for another (hidden and
 // cell state, projected predictor output, per-row argmax cells, softmax partials,
-// barrier counters) is written and read only with agent-scope relaxed atomic
+// barrier flags) is written and read only with agent-scope relaxed atomic
 // stores / loads / RMWs, which the hardware performs at the device's coherence
 // point, bypassing the per-CU L1 and the per-XCD L2.  A producer waits for the
 // completion of its stores (s_waitcnt vmcnt(0)) before it arrives at a barrier;
