@@ -436,7 +436,8 @@ __device__ inline WeightCursor weight_cursor(const Seg &sg, long long wrow, int 
     wc.live = wrow >= 0;
     wc.wr = static_cast<const uint16_t *>(sg.w) + (wc.live ? wrow : 0) * sg.wld + sg.k0;
     const int nsteps = (sg.K + 31) / 32;
-    wc.n_my = nsteps > kpart ? (nsteps - kpart + ksplit - 1) / ksplit : 0;
+    // ksplit is a power of two
+    wc.n_my = nsteps > kpart ? (nsteps - kpart + ksplit - 1) >> __builtin_ctz(ksplit) : 0;
     return wc;
 }
 
@@ -585,8 +586,9 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
     // always a readable float array with at least as many entries as there are weight rows
     const float *bias_or_any = bias ? bias : static_cast<const float *>(any_floats);
     const int ksplit = Backend<WT>::ksplit_for(n_ct);
-    const int tpr = kWaves / ksplit;          // column tiles per round
-    const int tslot = wave / ksplit, kpart = wave % ksplit;
+    const int ksh = __builtin_ctz(ksplit);    // ksplit is 1, 2, 4 or 8
+    const int tpr = kWaves >> ksh;            // column tiles per round
+    const int tslot = wave >> ksh, kpart = wave & (ksplit - 1);
     for (int base = 0; base < n_ct; base += tpr) {
         const int ct = base + tslot;
         const bool mine = ct < n_ct;
@@ -736,6 +738,14 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         __syncthreads();
         if (tid == 0) S.pend_n = 0;
     };
+    // Automatic window: as many rows as give every workgroup at most one joint work item of at
+    // most `joint_tiles` column tiles (then one round, all wavefronts busy).
+    int auto_rows;
+    {
+        const int tiles_per_item = p.joint_tiles > 0 ? p.joint_tiles : 4;
+        const int groups = ((O + CT - 1) / CT + tiles_per_item - 1) / tiles_per_item;
+        auto_rows = max(1, C / groups) * RT;
+    }
     int pp = 0;          // which half of hbuf holds the current hidden state
     unsigned jpass = 0;  // joint passes so far (selects the exchange buffers)
     bool ok = true;
@@ -982,15 +992,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         while (S.n_need > 0) {
             const int n_need = S.n_need;
             const int NT = (O + CT - 1) / CT;
-            // Automatic window: as many rows as give every workgroup at most one work item of
-            // at most `tiles_per_item` column tiles (then one round, all wavefronts busy).
             int Kw = p.window;
             if (Kw <= 0) {
-                const int tiles_per_item = p.joint_tiles > 0 ? p.joint_tiles : 4;
-                const int groups = (NT + tiles_per_item - 1) / tiles_per_item;
-                int row_tiles = C / groups;
-                if (row_tiles < 1) row_tiles = 1;
-                Kw = row_tiles * RT / n_need;
+                Kw = auto_rows / n_need;
                 if (Kw < 4) Kw = 4;
             }
             if (Kw > kMaxWindow) Kw = kMaxWindow;
