@@ -23,12 +23,15 @@ def gpu():
     return binding
 
 
-def run_gpu(binding, cfg, w, enc, ln, u_cap, window=0, n_clusters=0, max_symbols=None, repeat=1):
+def run_gpu(binding, cfg, w, enc, ln, u_cap, window=0, n_clusters=0, joint_tiles=0, max_symbols=None,
+            repeat=1):
     import torch
     parity.announce(f"tdt_greedy_decode cfg={cfg.name} B={len(ln)} T={enc.shape[1]} u_cap={u_cap} "
-                    f"window={window} n_clusters={n_clusters} S={max_symbols or cfg.max_symbols}")
+                    f"window={window} n_clusters={n_clusters} joint_tiles={joint_tiles} "
+                    f"S={max_symbols or cfg.max_symbols}")
     model = binding.DeviceModel(cfg, w)
-    dec = binding.Decoder(model, len(ln), enc.shape[1], u_cap, window=window, n_clusters=n_clusters)
+    dec = binding.Decoder(model, len(ln), enc.shape[1], u_cap, window=window, n_clusters=n_clusters,
+                          joint_tiles=joint_tiles)
     enc_d = model.upload_enc(enc)
     len_d = torch.from_numpy(np.ascontiguousarray(ln, np.int32)).to(model.device)
     out = None
@@ -114,6 +117,14 @@ SMALL = [
     synth.small_config("g_rnnt_lstm_bf16_wide", dtype="bf16", pred_kind="lstm", d_enc=136,
                        h_pred=200, emb_dim=72, h_joint=264, vocab=300, B=33, T=50, len_lo=20,
                        len_hi=50, seed=56, default_blank_bias=1.5, max_symbols=3),
+    # two LSTM layers on the matrix cores, reduction lengths that are no multiple of 32
+    synth.small_config("g_tdt_lstm2_bf16", dtype="bf16", pred_kind="lstm", pred_layers=2,
+                       durations=(0, 1, 2, 3), d_enc=40, h_pred=72, emb_dim=24, h_joint=104, vocab=45,
+                       B=18, T=64, len_lo=0, len_hi=64, seed=57, default_blank_bias=0.6, max_symbols=5),
+    # reduction lengths beyond one staged stretch (1024): two K segments per product
+    synth.small_config("g_rnnt_lstm_bf16_long", dtype="bf16", pred_kind="lstm", d_enc=64,
+                       h_pred=1096, emb_dim=32, h_joint=1288, vocab=37, B=3, T=24, len_lo=10,
+                       len_hi=24, seed=58, default_blank_bias=1.0, max_symbols=3),
 ]
 
 
@@ -202,10 +213,42 @@ def test_config2_cluster_and_window_variants(oracle_lib, gpu):
     u_cap = cfg.T * cfg.max_symbols
     om = oracle_lib.OracleModel(cfg, w)
     orc = oracle_lib.decode_batch(om, enc, ln, cfg.max_symbols, u_cap)
-    for window, n_clusters in [(1, 1), (8, 8), (16, 32), (64, 2)]:
-        out = run_gpu(gpu, cfg, w, enc, ln, u_cap, window=window, n_clusters=n_clusters)
+    for window, n_clusters, joint_tiles in [(1, 1, 0), (8, 8, 0), (16, 32, 0), (64, 2, 0), (0, 0, 1), (0, 1, 8),
+                                            (0, 4, 64)]:
+        out = run_gpu(gpu, cfg, w, enc, ln, u_cap, window=window, n_clusters=n_clusters,
+                      joint_tiles=joint_tiles)
         res = parity.compare(oracle_lib, om, cfg, enc, ln, out, u_cap, orc=orc)
         assert res["replayed"] <= 3, res
+
+
+def test_reuse_of_the_encoder_projection(oracle_lib, gpu):
+    """A second call that reuses the projection (and the LSTM table) left in the workspace gives
+    the same hypotheses as the first."""
+    import torch
+    cfg = synth.CFG3
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    u_cap = cfg.T * cfg.max_symbols
+    parity.announce(f"tdt_greedy_decode cfg={cfg.name} twice, second call with reuse_enc_proj")
+    model = gpu.DeviceModel(cfg, w)
+    dec = gpu.Decoder(model, cfg.B, cfg.T, u_cap)
+    enc_d = model.upload_enc(enc)
+    len_d = torch.from_numpy(np.ascontiguousarray(ln, np.int32)).to(model.device)
+    dec(enc_d, len_d)
+    first = dec.results()
+    dec.options.reuse_enc_proj = 1
+    dec(enc_d, len_d)
+    second = dec.results()
+    assert first["stats"]["abort"] == 0 and second["stats"]["abort"] == 0
+    for k in ("len", "score", "status"):
+        assert (first[k] == second[k]).all(), k
+    for b in range(cfg.B):
+        n = first["len"][b]
+        assert (first["labels"][b, :n] == second["labels"][b, :n]).all()
+        assert (first["frames"][b, :n] == second["frames"][b, :n]).all()
+    om = oracle_lib.OracleModel(cfg, w)
+    res = parity.compare(oracle_lib, om, cfg, enc, ln, second, u_cap)
+    assert res["replayed"] <= 3, res
 
 
 @pytest.mark.timeout(900)
