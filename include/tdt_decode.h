@@ -116,7 +116,8 @@ typedef struct {
  *               decode kernel on its own).
  *   joint_tiles the automatic window is sized so that one joint pass gives every
  *               workgroup at most one work item of this many 16-column tiles of the
- *               output layer.  0 = default (4).  Ignored when window > 0.
+ *               output layer.  0 = automatic (4, more for many hypotheses per group).
+ *               Ignored when window > 0.
  */
 typedef struct {
     int32_t window;

@@ -75,6 +75,7 @@ constexpr int kDeferred = kDeferPerWave * kWaves;
 constexpr int kTabPerThread = kWaves * RT * CT / kThreads;
 
 struct HypShared {
+    int gid[kMaxHypsPerCluster];     // the caller's index of the hypothesis in each slot
     int len[kMaxHypsPerCluster];
     int time[kMaxHypsPerCluster];
     int sym[kMaxHypsPerCluster];
@@ -650,12 +651,47 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ncl = p.n_clusters;
     const int cl = blockIdx.x % ncl, rank = blockIdx.x / ncl, C = gridDim.x / ncl;
-    const int b0 = cl * p.hyps_per_cluster;
-    int G = p.B - b0;
-    if (G > p.hyps_per_cluster) G = p.hyps_per_cluster;
-    if (G <= 0) return;   // the whole cluster leaves together
-
     const int B = p.B, T = p.T, H = p.H, V = p.V, D = p.D, O = p.O;
+    // Which hypotheses this cluster decodes.  A cluster runs as long as its longest utterance
+    // and costs more per step the more of its hypotheses are still active, so the clusters are
+    // made alike: the batch is ranked by length (longest first, ties by index) and dealt in
+    // rounds of ncl that alternate direction (0 .. ncl-1, ncl-1 .. 0, ...), so that no cluster
+    // always gets the longest of a round.  Every workgroup ranks the whole batch itself
+    // (B^2 / 512 comparisons per thread, up to kMaxRankedBatch).  Workspace rows are
+    // addressed by (cluster, slot): row b0 + g; only enc_len, enc_proj and the outputs see
+    // the caller's index S.gid[g].
+    const int b0 = cl * p.hyps_per_cluster;
+    const int Bw = ncl * p.hyps_per_cluster;   // rows of the per-hypothesis workspace arrays (>= B)
+    const bool ranked = ncl > 1 && B <= kMaxRankedBatch;
+    int G;
+    if (ranked) {
+        const int full = B / ncl, rem = B % ncl;   // the last, partial round has rem members
+        const int pos_in_last = (full & 1) ? ncl - 1 - cl : cl;
+        G = full + (pos_in_last < rem ? 1 : 0);
+    } else {
+        G = B - b0;
+        if (G > p.hyps_per_cluster) G = p.hyps_per_cluster;
+    }
+    if (G <= 0) return;   // the whole cluster leaves together
+    if (ranked) {
+        int *lens = reinterpret_cast<int *>(dyn_lds);   // the activation tile is not in use yet
+        for (int b = tid; b < B; b += kThreads) lens[b] = min(max(p.enc_len[b], 0), p.T);
+        __syncthreads();
+        for (int b = tid; b < B; b += kThreads) {
+            const int lb = lens[b];
+            int r = 0;
+            for (int b2 = 0; b2 < B; ++b2) {
+                const int l2 = lens[b2];
+                r += (l2 > lb || (l2 == lb && b2 < b)) ? 1 : 0;
+            }
+            const int round = r / ncl, pos = r - round * ncl;
+            if (((round & 1) ? ncl - 1 - pos : pos) == cl) S.gid[round] = b;
+        }
+    } else {
+        for (int g = tid; g < G; g += kThreads) S.gid[g] = b0 + g;
+    }
+    __syncthreads();
+
     const int Hp = p.h_pred, E = p.emb_dim, L = p.pred_layers;
     const bool lstm = p.pred_kind == TDT_PRED_LSTM;
 
@@ -675,7 +711,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 
     // ---- Alg. 3 lines 3-4: empty hypotheses, time 0, everyone with frames is active
     for (int g = tid; g < G; g += kThreads) {
-        int len = p.enc_len[b0 + g];
+        int len = p.enc_len[S.gid[g]];
         int st = 0;
         if (len < 0) { len = 0; st = TDT_HYP_LEN_CLAMPED; }
         if (len > T) { len = T; st = TDT_HYP_LEN_CLAMPED; }
@@ -739,11 +775,20 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         if (tid == 0) S.pend_n = 0;
     };
     // Automatic window: as many rows as give every workgroup at most one joint work item of at
-    // most `joint_tiles` column tiles (then one round, all wavefronts busy).
+    // most `tiles_per_item` column tiles (then one round, all wavefronts busy).  Unless the
+    // caller fixes it, a work item takes 4 column tiles, more (up to 8, one round) where the group's
+    // hypotheses with the smallest window of 4 frames would otherwise make more items than
+    // there are workgroups.
     int auto_rows;
     {
-        const int tiles_per_item = p.joint_tiles > 0 ? p.joint_tiles : 4;
-        const int groups = ((O + CT - 1) / CT + tiles_per_item - 1) / tiles_per_item;
+        const int NT = (O + CT - 1) / CT;
+        int tiles_per_item = p.joint_tiles;
+        if (tiles_per_item <= 0) {
+            const int row_tiles_min = (G * 4 + RT - 1) / RT;
+            const int groups_fit = max(1, C / row_tiles_min);
+            tiles_per_item = min(8, max(4, (NT + groups_fit - 1) / groups_fit));
+        }
+        const int groups = (NT + tiles_per_item - 1) / tiles_per_item;
         auto_rows = max(1, C / groups) * RT;
     }
     int pp = 0;          // which half of hbuf holds the current hidden state
@@ -786,7 +831,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 // the host-side call built before this kernel, and W_hh * h was computed right
                 // after h itself (phase Q of the previous label, below), before the label was
                 // known.  What is left is the cell update, one thread per (hypothesis, unit).
-                float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L) * B * Hp;
+                float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L) * Bw * Hp;
                 float *cst = p.cbuf;
                 const int total = n_act * Hp;
                 const int per_wg = (total + C - 1) / C;
@@ -814,10 +859,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             }
             for (int l = 1; l < L && ok; ++l) {   // deeper layers: [W_ih, W_hh] . [h of the layer below, own h]
                 const float *bl = p.b_lstm[l];
-                const float *h_cur = p.hbuf + ((size_t)pp * L + l) * B * Hp;
-                float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L + l) * B * Hp;
-                const float *x_prev = p.hbuf + ((size_t)(pp ^ 1) * L + (l - 1)) * B * Hp;
-                float *cst = p.cbuf + (size_t)l * B * Hp;
+                const float *h_cur = p.hbuf + ((size_t)pp * L + l) * Bw * Hp;
+                float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L + l) * Bw * Hp;
+                const float *x_prev = p.hbuf + ((size_t)(pp ^ 1) * L + (l - 1)) * Bw * Hp;
+                float *cst = p.cbuf + (size_t)l * Bw * Hp;
                 PhaseInputs in;
                 in.w0 = p.w_ih[l];
                 in.K0 = Hp;
@@ -900,8 +945,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 1;
         phase_bucket = kTkQ;
         {
-            const float *src_a = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * B * Hp : nullptr;
-            const float *src_b = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L) * B * Hp : nullptr;
+            const float *src_a = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * Bw * Hp : nullptr;
+            const float *src_b = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L) * Bw * Hp : nullptr;
             const int NT_A = (H + CT - 1) / CT, NT_B = lstm ? (Hp + 3) / 4 : 0;
             // fewest tiles per work item that give every workgroup at most one item
             int tpg = ((NT_A + NT_B) * n_tiles_a + C - 1) / C;
@@ -1046,7 +1091,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 const int f = S.time[g] + (r - q * Kw);
                                 JointRow c;
                                 c.valid = f < S.len[g];
-                                c.enc = p.enc_proj + ((size_t)(b0 + g) * T + (c.valid ? f : 0)) * H + k0;
+                                c.enc = p.enc_proj + ((size_t)S.gid[g] * T + (c.valid ? f : 0)) * H + k0;
                                 c.pred = p.pred_proj + (size_t)(b0 + g) * H + k0;
                                 return c;
                             },
@@ -1198,8 +1243,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     int dk = S.row_d[q * Kw + w];
                     const int frame = t0 + w, n = S.out_len[g];
                     if (rank == 0) {
-                        p.out_labels[(size_t)(b0 + g) * p.u_cap + n] = k;
-                        p.out_frames[(size_t)(b0 + g) * p.u_cap + n] = frame;
+                        p.out_labels[(size_t)S.gid[g] * p.u_cap + n] = k;
+                        p.out_frames[(size_t)S.gid[g] * p.u_cap + n] = frame;
                     }
                     S.out_len[g] = n + 1;
                     S.last2[g] = S.last[g];
@@ -1293,9 +1338,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     // ---- results of this cluster's hypotheses
     if (rank == 0) {
         for (int g = tid; g < G; g += kThreads) {
-            p.out_len[b0 + g] = S.out_len[g];
-            p.out_score[b0 + g] = S.score[g];
-            p.out_status[b0 + g] = S.status[g];
+            p.out_len[S.gid[g]] = S.out_len[g];
+            p.out_score[S.gid[g]] = S.score[g];
+            p.out_status[S.gid[g]] = S.status[g];
         }
         if (tid == 0 && p.out_stats) {
             auto add = [&](int slot, long long v) {
@@ -1339,8 +1384,11 @@ int kseg_max_for(const tdt_weights_t *w)
 size_t lds_bytes_for(const tdt_weights_t *w)
 {
     const int k = kseg_max_for(w);
-    if (w->dtype == 1) return (size_t)3 * RT * ActTile<uint16_t>::row_elems(k) * sizeof(uint16_t);
-    return (size_t)RT * ActTile<float>::row_elems(k) * sizeof(float);
+    const size_t tile = w->dtype == 1 ? (size_t)3 * RT * ActTile<uint16_t>::row_elems(k) * sizeof(uint16_t)
+                                      : (size_t)RT * ActTile<float>::row_elems(k) * sizeof(float);
+    // before the first tile is staged the same memory holds the batch's lengths while they are ranked
+    const size_t lens = (size_t)kMaxRankedBatch * sizeof(int);
+    return tile > lens ? tile : lens;
 }
 
 }  // namespace

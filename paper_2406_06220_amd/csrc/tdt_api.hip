@@ -12,10 +12,12 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T)
     WorkspaceLayout L{};
     size_t off = 0;
     const size_t lstm_layers = w->pred_kind == TDT_PRED_LSTM ? (size_t)w->pred_layers : 0;
+    // per-hypothesis arrays are addressed by (cluster, slot): n_clusters * ceil(B / n_clusters) rows
+    const size_t rows = (size_t)B + kMaxGrid;
     L.enc_proj = off;
     off = align_up(off + (size_t)B * T * w->h_joint * sizeof(float), 256);
     L.pred_proj = off;
-    off = align_up(off + (size_t)B * w->h_joint * sizeof(float), 256);
+    off = align_up(off + rows * w->h_joint * sizeof(float), 256);
     L.emb_gates = off;
     if (lstm_layers > 0)
         off = align_up(off + (size_t)(w->vocab + 1) * 4 * w->h_pred * sizeof(float), 256);
@@ -31,11 +33,11 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T)
     L.row_dur = off;
     off = align_up(off + L.row_entries * sizeof(unsigned long long), 256);
     L.hbuf = off;
-    off = align_up(off + 2 * lstm_layers * B * w->h_pred * sizeof(float), 256);
+    off = align_up(off + 2 * lstm_layers * rows * w->h_pred * sizeof(float), 256);
     L.cbuf = off;
-    off = align_up(off + lstm_layers * B * w->h_pred * sizeof(float), 256);
+    off = align_up(off + lstm_layers * rows * w->h_pred * sizeof(float), 256);
     L.rgate = off;
-    if (lstm_layers > 0) off = align_up(off + (size_t)B * 4 * w->h_pred * sizeof(float), 256);
+    if (lstm_layers > 0) off = align_up(off + rows * 4 * w->h_pred * sizeof(float), 256);
     L.barrier = off;
     off = align_up(off + (size_t)kMaxGrid * kBarrierStride * sizeof(unsigned), 256);
     L.abort_flag = off;

@@ -17,6 +17,7 @@ constexpr int kMaxColGroups = 64;             // output-column slices of one joi
 constexpr int kMaxWindow = 64;                // frames of one hypothesis per joint pass
 constexpr int kPartialEntries = kMaxRowsPerPass * kMaxGrid;  // per partial buffer
 constexpr int kBarrierStride = 32;            // uint32 slots between two workgroups' barrier flags
+constexpr int kMaxRankedBatch = 1024;          // largest batch whose hypotheses are dealt to the clusters by length
 constexpr int kRowBufs = 3;                   // rotating per-row argmax buffers
 
 // Softmax-denominator share of one slice of label columns for one joint row.
