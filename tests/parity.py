@@ -51,12 +51,14 @@ def compare(oracle, omodel, cfg, enc, enc_len, gpu: dict, u_cap: int, rows=None,
     else:
         orc_rows = {b: b for b in rows}
     n_exact = n_replayed = n_tie = 0
+    score_err = 0.0
     for b in rows:
         i = orc_rows[b]
         n, no = int(gpu["len"][b]), int(orc["len"][i])
         gl, gf = gpu["labels"][b, :n], gpu["frames"][b, :n]
         same = n == no and (gl == orc["labels"][i, :no]).all() and (gf == orc["frames"][i, :no]).all()
         if same:
+            score_err = max(score_err, abs(float(gpu["score"][b]) - float(orc["score"][i])))
             assert abs(float(gpu["score"][b]) - float(orc["score"][i])) <= TOL_SCORE, \
                 f"row {b}: score {gpu['score'][b]} vs oracle {orc['score'][i]}"
             assert bool(gpu["status"][b] & 1) == bool(orc["status"][i]), f"row {b}: status"
@@ -68,7 +70,8 @@ def compare(oracle, omodel, cfg, enc, enc_len, gpu: dict, u_cap: int, rows=None,
         assert rp["ok"], (f"row {b}: GPU hypothesis (len {n}) differs from the oracle's (len {no}) "
                           f"at label {first} and is not a greedy decode within {TOL_MARGIN}")
         assert rp["n_tie"] >= 1
+        score_err = max(score_err, abs(float(gpu["score"][b]) - rp["score"]))
         assert abs(float(gpu["score"][b]) - rp["score"]) <= TOL_SCORE, f"row {b}: replayed score"
         n_replayed += 1
         n_tie += rp["n_tie"]
-    return dict(exact=n_exact, replayed=n_replayed, ties=n_tie, rows=len(rows))
+    return dict(exact=n_exact, replayed=n_replayed, ties=n_tie, rows=len(rows), max_score_err=score_err)
