@@ -1040,7 +1040,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             int Kw = p.window;
             if (Kw <= 0) {
                 Kw = auto_rows / n_need;
-                if (Kw < 4) Kw = 4;
+                if (Kw < 3) Kw = 3;
             }
             if (Kw > kMaxWindow) Kw = kMaxWindow;
             if (Kw * n_need > rows_cap) Kw = rows_cap / n_need;

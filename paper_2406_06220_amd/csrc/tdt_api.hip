@@ -154,8 +154,8 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     if (n_clusters == 0) {
         // Measured on the paper-sized models: two clusters beat one from a few dozen
         // hypotheses on (shorter joint passes outweigh the thinner spread of the matrices),
-        // four from about a hundred.
-        n_clusters = B >= 128 ? 4 : B >= 16 ? 2 : 1;
+        // eight from about a hundred.
+        n_clusters = B >= 128 ? 8 : B >= 16 ? 2 : 1;
         if (n_clusters < min_clusters) n_clusters = min_clusters;
     }
     if (n_clusters < min_clusters || n_clusters > max_grid) return TDT_ERR_UNSUPPORTED;
