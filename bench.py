@@ -191,9 +191,16 @@ def main():
     if not args.no_extra and args.workload == "cfg2_rnnt_lstm":
         cfg_b = synth.CONFIGS["cfg2_rnnt_lstm_b128"]
         rb = time_workload(cfg_b, max(args.steps // 2, 3), max(args.warmup, 1), args.window, args.clusters)
+        alg_b = algorithmic_bytes(cfg_b, rb["out"]["stats"])
+        ach_b = alg_b / (rb["decode_kernel_ms"] * 1e-3) / 1e9
         line["b128"] = {"workload": cfg_b.name, "value": rb["frames"] / rb["sec_per_step"],
                         "unit": "frames/s", "us_per_batch": rb["sec_per_step"] * 1e6,
-                        "frames_per_batch": rb["frames"], "decode_stats": rb["out"]["stats"]}
+                        "frames_per_batch": rb["frames"],
+                        "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": ach_b,
+                                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach_b / HBM_PEAK_GBS,
+                                     "algorithmic_bytes_per_launch": alg_b,
+                                     "kernel_ms": rb["decode_kernel_ms"], "traffic": None},
+                        "decode_stats": rb["out"]["stats"]}
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(res)
     print(json.dumps(line))
