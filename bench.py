@@ -141,8 +141,8 @@ def main():
                          "known HBM traffic")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU (the batch would shard across GPUs without "
-              "any exchange, see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU (hypotheses are independent, so a batch would "
+              "shard across GPUs without any exchange); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2406_06220_amd import binding, synth

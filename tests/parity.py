@@ -25,7 +25,7 @@ _CASE_LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file_
 
 def announce(msg: str) -> None:
     """Name the case before a GPU step: on the real stderr, and appended (flushed to disk) to
-    gpurun_out/gpu_cases.log, so that the last line names the case if the process dies."""
+    the case log, so that its last line names the case if the process dies."""
     sys.__stderr__.write("[gpu-case] " + msg + "\n")
     sys.__stderr__.flush()
     try:
