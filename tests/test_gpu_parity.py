@@ -251,6 +251,56 @@ def test_reuse_of_the_encoder_projection(oracle_lib, gpu):
     assert res["replayed"] <= 3, res
 
 
+def test_side_stream_and_back_to_back_calls(oracle_lib, gpu):
+    """Calls queued on a stream of the caller's (default priority), two decoders sharing nothing
+    but the stream, no synchronisation between the calls: each gives its own oracle result."""
+    import torch
+    s = torch.cuda.Stream()
+    jobs = []
+    with torch.cuda.stream(s):
+        for cfg in (SMALL[3], synth.CFG1, SMALL[4]):
+            w = synth.generate_model(cfg)
+            enc, ln = synth.generate_inputs(cfg)
+            u_cap = cfg.T * cfg.max_symbols
+            parity.announce(f"tdt_greedy_decode cfg={cfg.name} queued on a side stream")
+            model = gpu.DeviceModel(cfg, w)
+            dec = gpu.Decoder(model, cfg.B, cfg.T, u_cap)
+            enc_d = model.upload_enc(enc)
+            len_d = torch.from_numpy(np.ascontiguousarray(ln, np.int32)).to(model.device)
+            jobs.append((cfg, w, enc, ln, u_cap, model, dec, enc_d, len_d))
+        s.synchronize()
+        for j in jobs:
+            j[6](j[7], j[8], stream=s)      # three launches in a row, nothing in between
+    s.synchronize()
+    for cfg, w, enc, ln, u_cap, model, dec, _, _ in jobs:
+        out = dec.results()
+        assert out["stats"]["abort"] == 0
+        om = oracle_lib.OracleModel(cfg, w)
+        res = parity.compare(oracle_lib, om, cfg, enc, ln, out, u_cap)
+        assert res["replayed"] <= 2, res
+
+
+def test_pass_counters_match_the_loop_structure(oracle_lib, gpu):
+    """With one group and a window of one frame the kernel is Algorithm 3 step for step: the number
+    of predictor passes is the length of the longest hypothesis (plus the start-of-sequence step
+    unless that hypothesis ended on its last label), and every (hypothesis, frame) decision of the
+    oracle is one scored row."""
+    cfg = synth.CFG3
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    u_cap = cfg.T * cfg.max_symbols
+    out = run_gpu(gpu, cfg, w, enc, ln, u_cap, window=1, n_clusters=1)
+    om = oracle_lib.OracleModel(cfg, w)
+    orc = oracle_lib.decode_batch(om, enc, ln, cfg.max_symbols, u_cap)
+    res = parity.compare(oracle_lib, om, cfg, enc, ln, out, u_cap, orc=orc)
+    assert res["replayed"] == 0, res
+    longest = int(orc["len"].max())
+    assert out["stats"]["pred_passes"] in (longest, longest + 1)
+    assert out["stats"]["outer_max"] == out["stats"]["pred_passes"]
+    assert out["stats"]["pred_rows"] in range(int(orc["len"].sum()), int(orc["len"].sum()) + cfg.B + 1)
+    assert out["stats"]["joint_rows"] == int(orc["n_joint"].sum())
+
+
 @pytest.mark.timeout(900)
 def test_config5_large_tdt_sampled_rows(oracle_lib, gpu):
     """Full B=256, T=1500 on the GPU; the oracle decodes a sample of the rows (rows are
