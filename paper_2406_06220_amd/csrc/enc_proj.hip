@@ -18,6 +18,7 @@ namespace {
 
 constexpr int BM = 128, BN = 128, BK = 64;   // workgroup tile
 constexpr int GEMM_THREADS = 256;            // 4 wavefronts, each a 64x64 sub-tile
+constexpr int kXcds = 8;                     // accelerator dies of an MI355X, workgroups are dealt to them in turn
 
 // 16-byte chunk index c of a row is stored at chunk (c ^ (row & 7)) so that the
 // 32 rows a wavefront reads for one k-slice spread over all LDS banks.
@@ -31,11 +32,17 @@ __global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(
     __shared__ __align__(16) uint16_t Bs[BN * BK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    // 1-D grid, column tiles fastest: the workgroups that share a row tile of
-    // `A` are dispatched back to back
+    // 1-D grid.  Consecutive workgroups go to consecutive XCDs, each with an L2 of its own, so
+    // the workgroups that share a row tile of `A` (all its column tiles) are given to one XCD:
+    // row tiles are dealt round robin to the XCDs, and the j-th workgroup of an XCD takes
+    // column tile j % nt_n of that XCD's (j / nt_n)-th row tile.  `A` then comes from HBM once
+    // instead of once per XCD; `W` is small and stays in every L2.
     const int nt_n = (N + BN - 1) / BN;
-    const long long m0 = (long long)(blockIdx.x / nt_n) * BM;
-    const int n0 = (blockIdx.x % nt_n) * BN;
+    const long long j = blockIdx.x / kXcds;
+    const long long mt = (j / nt_n) * kXcds + blockIdx.x % kXcds;
+    const long long m0 = mt * BM;
+    const int n0 = (int)(j % nt_n) * BN;
+    if (m0 >= M) return;   // the last round of row tiles may be partial (uniform over the workgroup)
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -170,7 +177,8 @@ hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int 
 {
     if (rows <= 0) return hipSuccess;
     if (dtype == 1) {
-        dim3 grid((unsigned)(((N + BN - 1) / BN) * ((rows + BM - 1) / BM)));
+        const long long row_tiles = (rows + BM - 1) / BM, rounds = (row_tiles + kXcds - 1) / kXcds;
+        dim3 grid((unsigned)(rounds * kXcds * ((N + BN - 1) / BN)));
         hipLaunchKernelGGL(enc_proj_bf16_kernel, grid, dim3(GEMM_THREADS), 0, stream,
                            static_cast<const uint16_t *>(a), static_cast<const uint16_t *>(w), bias, out,
                            (long long)rows, N, K, group);
