@@ -199,7 +199,8 @@ def main():
                         "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": ach_b,
                                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach_b / HBM_PEAK_GBS,
                                      "algorithmic_bytes_per_launch": alg_b,
-                                     "kernel_ms": rb["decode_kernel_ms"], "traffic": None},
+                                     "kernel_ms": rb["decode_kernel_ms"],
+                                     "traffic": traffic_from_profiles(cfg_b.name)},
                         "decode_stats": rb["out"]["stats"]}
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(res)

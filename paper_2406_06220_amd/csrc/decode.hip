@@ -650,7 +650,21 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ncl = p.n_clusters;
-    const int cl = blockIdx.x % ncl, rank = blockIdx.x / ncl, C = gridDim.x / ncl;
+    const int C = gridDim.x / ncl;
+    // Workgroups go to the chip's kXcds dies round-robin by blockIdx, and each die has its own
+    // L2.  A workgroup's rank decides which weight columns it multiplies, so each die gets a
+    // contiguous eighth of the ranks of every cluster: then its L2 holds an eighth of the
+    // matrices whatever the number of clusters (with one cluster per die each L2 would have
+    // to hold all of them, which it cannot, and every pass would fetch them again).
+    int cl, rank;
+    if (C % kXcds == 0) {
+        const int die = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
+        cl = j % ncl;
+        rank = die * (C / kXcds) + j / ncl;
+    } else {
+        cl = blockIdx.x % ncl;
+        rank = blockIdx.x / ncl;
+    }
     const int B = p.B, T = p.T, H = p.H, V = p.V, D = p.D, O = p.O;
     // Which hypotheses this cluster decodes.  A cluster runs as long as its longest utterance
     // and costs more per step the more of its hypotheses are still active, so the clusters are

@@ -18,7 +18,6 @@ namespace {
 
 constexpr int BM = 128, BN = 128, BK = 64;   // workgroup tile
 constexpr int GEMM_THREADS = 256;            // 4 wavefronts, each a 64x64 sub-tile
-constexpr int kXcds = 8;                     // accelerator dies of an MI355X, workgroups are dealt to them in turn
 
 // 16-byte chunk index c of a row is stored at chunk (c ^ (row & 7)) so that the
 // 32 rows a wavefront reads for one k-slice spread over all LDS banks.

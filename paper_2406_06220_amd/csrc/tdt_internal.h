@@ -16,6 +16,7 @@ constexpr int kMaxRowsPerPass = 1024;         // (hypothesis, frame) rows of one
 constexpr int kMaxColGroups = 64;             // output-column slices of one joint pass
 constexpr int kMaxWindow = 64;                // frames of one hypothesis per joint pass
 constexpr int kPartialEntries = kMaxRowsPerPass * kMaxGrid;  // per partial buffer
+constexpr int kXcds = 8;                      // accelerator dies of an MI355X; workgroups are dealt to them in turn
 constexpr int kBarrierStride = 32;            // uint32 slots between two workgroups' barrier flags
 constexpr int kMaxRankedBatch = 1024;          // largest batch whose hypotheses are dealt to the clusters by length
 constexpr int kRowBufs = 3;                   // rotating per-row argmax buffers
