@@ -3,8 +3,9 @@
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this module.  It compiles ``transducer_oracle.c`` with gcc
 on first use and exposes the frame-looping greedy decoder (Algorithm 1 of the
-paper, extended with TDT durations and the symbols-per-frame cap), the tolerant
-replay check, and the model primitives that test-side re-orderings of the loops
+paper, extended with TDT durations and the symbols-per-frame cap), its
+chunk-by-chunk form with a carried state, the tolerant replay check, and the
+model primitives that test-side re-orderings of the loops
 call row by row.
 """
 from __future__ import annotations
@@ -61,6 +62,7 @@ def _load():
         _lib = C.CDLL(build())
         _lib.orc_decode_utt.restype = C.c_int
         _lib.orc_decode_batch.restype = C.c_int
+        _lib.orc_decode_batch_chunk.restype = C.c_int
         _lib.orc_replay_utt.restype = C.c_int
         _lib.orc_num_threads.restype = C.c_int
     return _lib
@@ -190,6 +192,38 @@ def decode_batch(model: OracleModel, enc: np.ndarray, enc_len: np.ndarray, max_s
         _fp(score), _ip(status), counts.ctypes.data_as(_i64p), C.c_int(n_threads))
     return dict(labels=labels, frames=frames, durs=durs, len=lens, score=score, status=status,
                 n_pred=counts[:, 0].copy(), n_joint=counts[:, 1].copy(), threads=int(used))
+
+
+def stream_state(model: OracleModel, B: int) -> dict:
+    """State of B utterances none of which has been decoded yet (all zero)."""
+    cfg = model.cfg
+    n = cfg.pred_layers * cfg.h_pred if cfg.pred_kind == "lstm" else 1
+    return dict(started=np.zeros(B, np.int32), time=np.zeros(B, np.int32),
+                ctx=np.zeros((B, 2), np.int32), h=np.zeros((B, n), np.float32),
+                c=np.zeros((B, n), np.float32))
+
+
+def decode_batch_chunk(model: OracleModel, enc: np.ndarray, enc_len: np.ndarray, max_symbols: int,
+                       u_cap: int, state: dict, n_threads: int = 0) -> dict:
+    """The next chunk of B utterances decoded piece by piece; `state` is updated in place.
+    Frames are counted from the chunk's start, the score is the chunk's own sum."""
+    lib = _load()
+    enc = np.ascontiguousarray(enc, np.float32)
+    B, T, _ = enc.shape
+    enc_len = np.ascontiguousarray(enc_len, np.int32)
+    labels = np.zeros((B, u_cap), np.int32)
+    frames = np.zeros((B, u_cap), np.int32)
+    lens = np.zeros(B, np.int32)
+    score = np.zeros(B, np.float32)
+    status = np.zeros(B, np.int32)
+    for k in ("started", "time", "ctx", "h", "c"):
+        assert state[k].flags["C_CONTIGUOUS"] and state[k].shape[0] == B
+    lib.orc_decode_batch_chunk(
+        C.byref(model.c), _fp(enc), _ip(enc_len), C.c_int(B), C.c_int(T), _ip(model.durations),
+        C.c_int(max_symbols), C.c_int(u_cap), _ip(labels), _ip(frames), _ip(lens), _fp(score),
+        _ip(status), _ip(state["started"]), _ip(state["time"]), _ip(state["ctx"]),
+        _fp(state["h"]), _fp(state["c"]), C.c_int(n_threads))
+    return dict(labels=labels, frames=frames, len=lens, score=score, status=status)
 
 
 def replay_utt(model: OracleModel, enc: np.ndarray, length: int, max_symbols: int, u_cap: int,

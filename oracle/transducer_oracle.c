@@ -36,7 +36,9 @@
  * with test-side label-looping (Algorithm 3) and batched frame-looping
  * (Algorithm 2) decoders; closed forms with the predictor switched off, with
  * durations {0} and {1}, with an extreme blank bias; row independence and
- * causality.  Parity unpinned: the score definition, the BOS convention and
+ * causality; for decoding in chunks, equality with the whole utterance under
+ * random, even and frame-by-frame cuts, the figure's example cut in two, and the
+ * carried predictor state against a replay of the emitted labels.  Parity unpinned: the score definition, the BOS convention and
  * the joiner's internal shape are readings of points the paper does not fix;
  * the pins check them only against an independent re-statement of the same
  * readings, not against a value the paper prints.
@@ -114,6 +116,24 @@ static void state_free(orc_state_t *s)
 }
 
 /*
+ * The predictor's output as a function of its state alone: the concatenated
+ * embeddings of the context labels (stateless), or the top layer's h (LSTM).
+ */
+static void predictor_output(const orc_model_t *m, const orc_state_t *s, float *dec)
+{
+    const int Hp = m->h_pred, E = m->emb_dim, V1 = m->vocab + 1;
+    if (m->pred_kind == 0) {
+        for (int i = 0; i < m->pred_layers; ++i) {
+            const float *row = m->emb + ((size_t)i * V1 + s->ctx[i]) * E;
+            for (int k = 0; k < E; ++k) dec[i * E + k] = row[k];
+        }
+    } else {
+        const float *top = s->h + (size_t)(m->pred_layers - 1) * Hp;
+        for (int n = 0; n < Hp; ++n) dec[n] = top[n];
+    }
+}
+
+/*
  * One predictor call (Algorithm 1, "dec, new_state = predictor(state, label)").
  * The state is updated in place: callers invoke it only when the new state is
  * to be kept (after BOS and after every non-blank label), which is the same
@@ -122,15 +142,12 @@ static void state_free(orc_state_t *s)
 static void predictor_step(const orc_model_t *m, orc_state_t *s, int label, float *dec,
                            float *scratch /* [4*Hp] */)
 {
-    const int Hp = m->h_pred, E = m->emb_dim, V1 = m->vocab + 1;
+    const int Hp = m->h_pred, E = m->emb_dim;
     if (m->pred_kind == 0) {
         const int ctx = m->pred_layers;
         for (int i = 0; i + 1 < ctx; ++i) s->ctx[i] = s->ctx[i + 1];
         s->ctx[ctx - 1] = label;
-        for (int i = 0; i < ctx; ++i) {
-            const float *row = m->emb + ((size_t)i * V1 + s->ctx[i]) * E;
-            for (int k = 0; k < E; ++k) dec[i * E + k] = row[k];
-        }
+        predictor_output(m, s, dec);
         return;
     }
     float *gates = scratch; /* [4*Hp] */
@@ -158,7 +175,7 @@ static void predictor_step(const orc_model_t *m, orc_state_t *s, int label, floa
         x = h;
         in_dim = Hp;
     }
-    for (int n = 0; n < Hp; ++n) dec[n] = x[n];
+    predictor_output(m, s, dec);
 }
 
 static void joint_logits(const orc_model_t *m, const float *enc_proj, const float *pred_proj,
@@ -248,14 +265,35 @@ typedef struct {
 } orc_trace_t;
 
 /*
+ * What one utterance carries from one chunk of its frames to the next when it
+ * is decoded piece by piece (an extension beyond the paper, defined by one
+ * requirement: decoding the chunks in order gives the hypothesis of decoding
+ * their concatenation, with frame indices counted from each chunk's start).
+ * All zero = nothing decoded yet.
+ */
+typedef struct {
+    int32_t started; /* the start-of-sequence predictor call has been made */
+    int32_t time;    /* frames of the next chunk already stepped over (a TDT duration
+                        can reach past the end of a chunk) */
+    int32_t ctx[ORC_MAX_CTX]; /* stateless predictor: its context labels, oldest first */
+    float *h, *c;    /* LSTM: [layers][Hp] each (unused for a stateless predictor) */
+} orc_stream_t;
+
+/*
  * Returns the status: 0 = complete, 1 = stopped at u_cap labels.
  * enc: [len or more][d_enc].  durations: [n_dur] frame increments, NULL if n_dur == 0.
  * out_durs may be NULL.  counts (may be NULL): [0] predictor calls, [1] joint calls.
+ * stream == NULL: a whole utterance.  Otherwise the frames are the next chunk of
+ * a longer utterance: decoding continues from *stream, which is updated.  The
+ * start-of-sequence call is made in the first chunk that has a frame to look at.
+ * The symbols-per-frame counter is never carried: a chunk ends by moving past
+ * its last frame, which resets it.  A hypothesis stopped at u_cap loses the rest
+ * of its chunk.
  */
-int orc_decode_utt(const orc_model_t *m, const float *enc, int len, const int32_t *durations,
-                   int max_symbols, int u_cap, int32_t *out_labels, int32_t *out_frames,
-                   int32_t *out_durs, int32_t *out_len, float *out_score, orc_trace_t *trace,
-                   int64_t *counts)
+static int decode_frames(const orc_model_t *m, const float *enc, int len, const int32_t *durations,
+                         int max_symbols, int u_cap, int32_t *out_labels, int32_t *out_frames,
+                         int32_t *out_durs, int32_t *out_len, float *out_score, orc_trace_t *trace,
+                         int64_t *counts, orc_stream_t *stream)
 {
     const int H = m->h_joint, V = m->vocab, D = m->n_dur, O = V + 1 + D;
     float *enc_proj = (float *)malloc(sizeof(float) * (size_t)H);
@@ -270,10 +308,26 @@ int orc_decode_utt(const orc_model_t *m, const float *enc, int len, const int32_
     float score = 0.0f;
     if (trace) trace->n = 0;
 
-    /* BOS call; its state is kept */
-    predictor_step(m, &st, V, dec, scratch);
-    ++n_pred;
-    linear(m->w_pred, m->b_pred, dec, H, m->h_pred, pred_proj);
+    const int n_state = m->pred_kind == 1 ? m->pred_layers * m->h_pred : 0;
+    int started = 1;
+    if (stream) {
+        t = stream->time;
+        started = stream->started;
+        if (started) { /* take up the predictor where the last chunk left it */
+            memcpy(st.h, stream->h, sizeof(float) * (size_t)n_state);
+            memcpy(st.c, stream->c, sizeof(float) * (size_t)n_state);
+            for (int i = 0; i < ORC_MAX_CTX; ++i) st.ctx[i] = stream->ctx[i];
+            predictor_output(m, &st, dec);
+        } else if (t < len) {
+            started = 1;
+        }
+    }
+    if (!stream || (!stream->started && started)) {
+        /* BOS call; its state is kept */
+        predictor_step(m, &st, V, dec, scratch);
+        ++n_pred;
+    }
+    if (started) linear(m->w_pred, m->b_pred, dec, H, m->h_pred, pred_proj);
 
     while (t < len && u_cap > 0) {
         if (t_proj != t) { /* same value for every visit of frame t */
@@ -332,6 +386,15 @@ int orc_decode_utt(const orc_model_t *m, const float *enc, int len, const int32_
         counts[0] = n_pred;
         counts[1] = n_joint;
     }
+    if (stream) {
+        stream->time = t > len ? t - len : 0;
+        if (started) {
+            stream->started = 1;
+            memcpy(stream->h, st.h, sizeof(float) * (size_t)n_state);
+            memcpy(stream->c, st.c, sizeof(float) * (size_t)n_state);
+            for (int i = 0; i < ORC_MAX_CTX; ++i) stream->ctx[i] = st.ctx[i];
+        }
+    }
     state_free(&st);
     free(enc_proj);
     free(pred_proj);
@@ -340,6 +403,55 @@ int orc_decode_utt(const orc_model_t *m, const float *enc, int len, const int32_
     free(logits);
     free(scratch);
     return status;
+}
+
+int orc_decode_utt(const orc_model_t *m, const float *enc, int len, const int32_t *durations,
+                   int max_symbols, int u_cap, int32_t *out_labels, int32_t *out_frames,
+                   int32_t *out_durs, int32_t *out_len, float *out_score, orc_trace_t *trace,
+                   int64_t *counts)
+{
+    return decode_frames(m, enc, len, durations, max_symbols, u_cap, out_labels, out_frames,
+                         out_durs, out_len, out_score, trace, counts, NULL);
+}
+
+/*
+ * The next chunk of every utterance of a batch.  Per-utterance state in arrays:
+ * started, time [B]; ctx [B][ORC_MAX_CTX]; h, c [B][layers*Hp] (LSTM only).
+ */
+int orc_decode_batch_chunk(const orc_model_t *m, const float *enc, const int32_t *enc_len, int B,
+                           int T, const int32_t *durations, int max_symbols, int u_cap,
+                           int32_t *out_labels, int32_t *out_frames, int32_t *out_len,
+                           float *out_score, int32_t *out_status, int32_t *st_started,
+                           int32_t *st_time, int32_t *st_ctx, float *st_h, float *st_c,
+                           int n_threads)
+{
+    const size_t n_state = m->pred_kind == 1 ? (size_t)m->pred_layers * m->h_pred : 0;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads <= 0) n_threads = omp_get_max_threads();
+    used = n_threads < B ? n_threads : B;
+    if (used < 1) used = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(used)
+#endif
+    for (int b = 0; b < B; ++b) {
+        int len = enc_len[b];
+        if (len < 0) len = 0;
+        if (len > T) len = T;
+        orc_stream_t s;
+        s.started = st_started[b];
+        s.time = st_time[b];
+        for (int i = 0; i < ORC_MAX_CTX; ++i) s.ctx[i] = st_ctx[b * ORC_MAX_CTX + i];
+        s.h = st_h + (size_t)b * n_state;
+        s.c = st_c + (size_t)b * n_state;
+        out_status[b] = decode_frames(
+            m, enc + (size_t)b * T * m->d_enc, len, durations, max_symbols, u_cap,
+            out_labels + (size_t)b * u_cap, out_frames + (size_t)b * u_cap, NULL, out_len + b,
+            out_score + b, NULL, NULL, &s);
+        st_started[b] = s.started;
+        st_time[b] = s.time;
+        for (int i = 0; i < ORC_MAX_CTX; ++i) st_ctx[b * ORC_MAX_CTX + i] = s.ctx[i];
+    }
+    return used;
 }
 
 /*

@@ -19,6 +19,7 @@ from __future__ import annotations
 import numpy as np
 import pytest
 
+import chunks
 import dense_lattice
 import fig2_model
 import loops
@@ -361,3 +362,83 @@ def test_replay_tolerates_only_near_ties(oracle_lib):
                                       tol=0.0)
         assert exact["ok"] and exact["n_tie"] == 0
     assert hit >= 1
+
+
+# --------------------------------------------------------------------------- P11
+# Piecewise decoding (an extension beyond the paper) is defined by one requirement:
+# the chunks of an utterance, decoded in order with the carried state, give the
+# hypothesis of the whole utterance.  The whole-utterance decoder is pinned above.
+@pytest.mark.parametrize("mode,n_chunks", [("random", 4), ("random", 9), ("even", 2), ("single", 0)],
+                         ids=["random4", "random9", "halves", "frame_by_frame"])
+@pytest.mark.parametrize("cfg", SMALL + [synth.CFG1], ids=IDS + ["cfg1"])
+def test_chunks_decode_like_the_whole(oracle_lib, cfg, mode, n_chunks):
+    w, enc, ln, m = _setup(oracle_lib, cfg)
+    S, u_cap = cfg.max_symbols, cfg.T * cfg.max_symbols
+    whole = oracle_lib.decode_batch(m, enc, ln, S, u_cap)
+    rng = np.random.default_rng(100 + n_chunks)
+    bounds = chunks.split_plan(ln, n_chunks, rng, mode)
+    state = oracle_lib.stream_state(m, cfg.B)
+    parts = []
+    for c in range(bounds.shape[1] - 1):
+        ec, lc = chunks.make_chunk(enc, bounds, c, rng)
+        parts.append(oracle_lib.decode_batch_chunk(m, ec, lc, S, u_cap, state))
+        # what is carried over is how far the last step reached past the chunk's end
+        assert (state["time"] >= 0).all()
+        assert (state["time"] <= (max(cfg.durations) if cfg.durations else 1)).all()
+    got = chunks.stitch(parts, bounds, u_cap)
+    assert (got["len"] == whole["len"]).all()
+    for b in range(cfg.B):
+        n = whole["len"][b]
+        assert (got["labels"][b, :n] == whole["labels"][b, :n]).all()
+        assert (got["frames"][b, :n] == whole["frames"][b, :n]).all()
+    np.testing.assert_allclose(got["score"], whole["score"], rtol=0, atol=2e-5 * (1 + whole["len"].max()))
+    # the carried predictor state is the state after start-of-sequence and the emitted labels
+    for b in range(cfg.B):
+        if ln[b] == 0:
+            assert state["started"][b] == 0
+            continue
+        assert state["started"][b] == 1
+        st = m.init_state()
+        for lab in [cfg.vocab] + whole["labels"][b, :whole["len"][b]].tolist():
+            _, st = m.predictor_step(st, lab)
+        if cfg.pred_kind == "lstm":
+            n = cfg.pred_layers * cfg.h_pred
+            assert (state["h"][b] == st[0][:n]).all() and (state["c"][b] == st[0][n:]).all()
+        else:
+            assert (state["ctx"][b, :cfg.pred_layers] == st[1][:cfg.pred_layers]).all()
+
+
+def test_fig2_in_two_chunks(oracle_lib):
+    """The caption's example cut between frames 1 and 2: C | A T and D | O G."""
+    ex = fig2_model.build()
+    cfg, w, enc, ln = fig2_model.real_model(ex)
+    m = oracle_lib.OracleModel(cfg, w)
+    state = oracle_lib.stream_state(m, ex["B"])
+    two = np.full(ex["B"], 2, np.int32)
+    first = oracle_lib.decode_batch_chunk(m, enc[:, :2], two, cfg.max_symbols, 16, state)
+    second = oracle_lib.decode_batch_chunk(m, enc[:, 2:4], two, cfg.max_symbols, 16, state)
+    for b, em in enumerate(ex["expected"]):
+        a = [(k, t) for k, t in em if t < 2]
+        z = [(k, t - 2) for k, t in em if t >= 2]
+        assert list(zip(first["labels"][b, :first["len"][b]], first["frames"][b, :first["len"][b]])) == a
+        assert list(zip(second["labels"][b, :second["len"][b]], second["frames"][b, :second["len"][b]])) == z
+
+
+def test_chunk_stopped_at_capacity_loses_its_rest(oracle_lib):
+    """A chunk whose hypothesis fills its label capacity is flagged; the next chunk starts
+    at its own first frame with the predictor state of the labels kept so far."""
+    cfg = SMALL[2]
+    w, enc, ln, m = _setup(oracle_lib, cfg, bias=-3.0)   # many labels
+    S = cfg.max_symbols
+    state = oracle_lib.stream_state(m, cfg.B)
+    r = oracle_lib.decode_batch_chunk(m, enc, ln, S, 3, state)
+    assert (r["status"][ln > 0] == 1).all() and (r["len"][ln > 0] == 3).all()
+    assert (state["time"] == 0).all()
+    for b in range(cfg.B):
+        if ln[b] == 0:
+            continue
+        st = m.init_state()
+        for lab in [cfg.vocab] + r["labels"][b, :3].tolist():
+            _, st = m.predictor_step(st, lab)
+        n = cfg.pred_layers * cfg.h_pred
+        assert (state["h"][b] == st[0][:n]).all()
