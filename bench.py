@@ -86,6 +86,53 @@ def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0):
                 frames=frames, u_cap=u_cap)
 
 
+def time_chunked(cfg, chunk_frames, steps, warmup):
+    """The same batch fed in chunks of `chunk_frames` frames per utterance through
+    tdt_greedy_decode_chunk (state cleared, then every chunk in turn = one step)."""
+    import torch
+    from paper_2406_06220_amd import binding, synth
+    dev = "cuda:0"
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    ln = np.clip(ln, 0, cfg.T)
+    model = binding.DeviceModel(cfg, w, dev)
+    state = binding.StreamState(model, cfg.B)
+    dec = binding.ChunkDecoder(model, cfg.B, chunk_frames, chunk_frames * cfg.max_symbols, state)
+    n_chunks = (int(ln.max()) + chunk_frames - 1) // chunk_frames
+    feeds = []
+    for c in range(n_chunks):
+        lc = np.clip(ln - c * chunk_frames, 0, chunk_frames).astype(np.int32)
+        ec = np.ascontiguousarray(enc[:, c * chunk_frames:(c + 1) * chunk_frames])
+        if ec.shape[1] < chunk_frames:
+            ec = np.concatenate([ec, np.zeros((cfg.B, chunk_frames - ec.shape[1], cfg.d_enc), np.float32)], 1)
+        feeds.append((model.upload_enc(ec), torch.from_numpy(lc).to(dev)))
+    stream = torch.cuda.current_stream(dev)
+
+    def one_pass():
+        state.reset()
+        for e, l in feeds:
+            dec(e, l, stream=stream)
+
+    labels = 0
+    for _ in range(max(warmup, 1)):
+        state.reset()
+        labels = 0
+        for e, l in feeds:
+            dec(e, l, stream=stream)
+            r = dec.results()
+            assert r["stats"]["abort"] == 0, "device-side wait timed out"
+            labels += int(r["len"].sum())
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_pass()
+    torch.cuda.synchronize(dev)
+    dt = (time.perf_counter() - t0) / steps
+    frames = int(ln.sum())
+    return dict(workload=cfg.name, chunk_frames=chunk_frames, chunks=n_chunks, value=frames / dt,
+                unit="frames/s", us_per_chunk=dt / n_chunks * 1e6, labels=labels)
+
+
 def cpu_baseline(res, min_seconds=10.0, max_runs=64):
     """The oracle as it stands on the host cores: the same batch decoded again and again with
     all threads until about `min_seconds` of wall time have passed (one utterance per
@@ -202,6 +249,9 @@ def main():
                                      "kernel_ms": rb["decode_kernel_ms"],
                                      "traffic": traffic_from_profiles(cfg_b.name)},
                         "decode_stats": rb["out"]["stats"]}
+        # the same batch fed piece by piece (50 frames = 2 s of audio at config 2's frame rate)
+        line["chunked"] = time_chunked(cfg, 50, max(args.steps // 2, 3), max(args.warmup, 1))
+        line["chunked"]["labels_match_whole"] = bool(line["chunked"]["labels"] == int(res["out"]["len"].sum()))
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(res)
     print(json.dumps(line))

@@ -166,8 +166,8 @@ int tdt_workspace_bytes(const tdt_weights_t *weights, int B, int T, int u_cap, s
  *   enc_len     DEVICE [B] int32 valid frames per utterance; values outside
  *               [0, T] are clamped and flagged in out_status.
  *   durations   HOST [n_dur] frame increments of the duration classes
- *               (e.g. {0,1,2,3,4}); NULL iff n_dur == 0.  A blank with increment 0
- *               advances one frame.
+ *               (e.g. {0,1,2,3,4}), each in [0, 2^20], at least one positive; NULL
+ *               iff n_dur == 0.  A blank with increment 0 advances one frame.
  *   max_symbols most labels a hypothesis may emit without its frame index moving;
  *               on the max_symbols-th the frame index is advanced by one.
  *   u_cap       label capacity per hypothesis; a hypothesis that reaches it stops
@@ -192,6 +192,47 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
                       float *out_score, int32_t *out_status, int64_t *out_stats,
                       void *workspace, size_t workspace_bytes, const tdt_options_t *options,
                       void *stream);
+
+/*
+ * Decoding utterances chunk by chunk (an extension beyond the paper, in the spirit of
+ * its device-resident batched hypotheses, Sec. 3.1): the frames of each utterance
+ * arrive in pieces, and every call decodes the next piece of all B utterances.  The
+ * chunks of an utterance, decoded in order, give the labels of decoding their
+ * concatenation with tdt_greedy_decode; out_frames count from the start of each
+ * chunk and out_score is the sum over the labels emitted in the chunk.
+ *
+ * What an utterance carries from chunk to chunk sits in `state`, DEVICE memory of
+ * tdt_state_bytes() bytes, 256-byte aligned, owned by the caller, read and
+ * updated in place by every call:
+ *
+ *   int32 started[B]  the start-of-sequence predictor step has been taken (it is
+ *                     taken in the first chunk in which the utterance has a frame to look at)
+ *   int32 time[B]     frames of the NEXT chunk already stepped over (a TDT duration can
+ *                     reach past the end of a chunk); >= 0
+ *   int32 last[B]     newest label the predictor has seen, and
+ *   int32 last2[B]    the one before (blank index V = none yet)
+ *   float h[layers][B][h_pred], c[layers][B][h_pred]      LSTM predictor only
+ *
+ * each array starting at the next multiple of 256 bytes.  All bytes zero = nothing
+ * decoded yet: the caller clears the state (or one utterance's entries in it) to
+ * start a new stream.  Rows are independent, so a caller may move an utterance to
+ * another batch slot by moving its entries.  The symbols-per-frame counter is not
+ * carried: a chunk ends by stepping past its last frame, which resets it.  A
+ * hypothesis that fills u_cap within a chunk is flagged TDT_HYP_TRUNCATED and
+ * gives up the rest of that chunk; its state is that after its last kept label.
+ *
+ * All other arguments, the workspace and the error codes are those of
+ * tdt_greedy_decode (T, enc_len and u_cap describe the chunk); TDT_ERR_NULL for a
+ * NULL state, TDT_ERR_WORKSPACE for a misaligned one.  Calls that share a state
+ * must not overlap.
+ */
+int tdt_state_bytes(const tdt_weights_t *weights, int B, size_t *bytes);
+int tdt_greedy_decode_chunk(const void *enc, const int32_t *enc_len, int B, int T,
+                            const tdt_weights_t *weights, const int32_t *durations,
+                            int max_symbols, int u_cap, int32_t *out_labels, int32_t *out_frames,
+                            int32_t *out_len, float *out_score, int32_t *out_status,
+                            int64_t *out_stats, void *state, void *workspace,
+                            size_t workspace_bytes, const tdt_options_t *options, void *stream);
 
 /*
  * The encoder projection alone (Sec. 3.4, the precomputation at line 2 of

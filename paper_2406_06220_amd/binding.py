@@ -29,8 +29,8 @@ TDT_STAT_COUNT = 24
 TDT_HYP_TRUNCATED = 1
 TDT_HYP_LEN_CLAMPED = 2
 
-EXPORTS = ("tdt_workspace_bytes", "tdt_greedy_decode", "tdt_encoder_projection",
-           "tdt_status_string")
+EXPORTS = ("tdt_workspace_bytes", "tdt_greedy_decode", "tdt_state_bytes",
+           "tdt_greedy_decode_chunk", "tdt_encoder_projection", "tdt_status_string")
 
 
 class tdt_weights_t(C.Structure):
@@ -69,6 +69,14 @@ def load_library():
             C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(tdt_weights_t),
             C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+            C.POINTER(tdt_options_t), C.c_void_p]
+        lib.tdt_state_bytes.restype = C.c_int
+        lib.tdt_state_bytes.argtypes = [C.POINTER(tdt_weights_t), C.c_int, C.POINTER(C.c_size_t)]
+        lib.tdt_greedy_decode_chunk.restype = C.c_int
+        lib.tdt_greedy_decode_chunk.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(tdt_weights_t),
+            C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
             C.POINTER(tdt_options_t), C.c_void_p]
         lib.tdt_encoder_projection.restype = C.c_int
         lib.tdt_encoder_projection.argtypes = [C.c_void_p, C.c_int64, C.POINTER(tdt_weights_t),
@@ -121,6 +129,27 @@ def tdt_greedy_decode(enc_ptr: int, enc_len_ptr: int, B: int, T: int, weights: t
         enc_ptr, enc_len_ptr, B, T, C.byref(weights), dur, max_symbols, u_cap, out_labels_ptr,
         out_frames_ptr, out_len_ptr, out_score_ptr, out_status_ptr, out_stats_ptr, workspace_ptr,
         workspace_bytes, C.byref(options) if options is not None else None, stream))
+
+
+def tdt_state_bytes(weights: tdt_weights_t, B: int) -> int:
+    n = C.c_size_t(0)
+    _check(load_library().tdt_state_bytes(C.byref(weights), B, C.byref(n)))
+    return int(n.value)
+
+
+def tdt_greedy_decode_chunk(enc_ptr: int, enc_len_ptr: int, B: int, T: int, weights: tdt_weights_t,
+                            durations: Optional[Sequence[int]], max_symbols: int, u_cap: int,
+                            out_labels_ptr: int, out_frames_ptr: int, out_len_ptr: int,
+                            out_score_ptr: int, out_status_ptr: int, out_stats_ptr: int,
+                            state_ptr: int, workspace_ptr: int, workspace_bytes: int,
+                            options: Optional[tdt_options_t] = None, stream: int = 0) -> None:
+    dur = None
+    if durations is not None and len(durations):
+        dur = (C.c_int32 * len(durations))(*[int(d) for d in durations])
+    _check(load_library().tdt_greedy_decode_chunk(
+        enc_ptr, enc_len_ptr, B, T, C.byref(weights), dur, max_symbols, u_cap, out_labels_ptr,
+        out_frames_ptr, out_len_ptr, out_score_ptr, out_status_ptr, out_stats_ptr, state_ptr,
+        workspace_ptr, workspace_bytes, C.byref(options) if options is not None else None, stream))
 
 
 # ----------------------------------------------------------------------------
@@ -206,3 +235,57 @@ class Decoder:
                     len=self.lens.cpu().numpy(), score=self.score.cpu().numpy(),
                     status=self.status.cpu().numpy(),
                     stats={n: int(st[i]) for n, i in TDT_STAT_NAMES.items()})
+
+
+class StreamState:
+    """The device memory ``tdt_greedy_decode_chunk`` keeps between the chunks of B utterances."""
+
+    def __init__(self, model: DeviceModel, B: int):
+        import torch
+        self.model, self.B = model, B
+        self.bytes = tdt_state_bytes(model.c, B)
+        self.buf = torch.zeros(self.bytes + 256, dtype=torch.uint8, device=model.device)
+        self.ptr = (self.buf.data_ptr() + 255) // 256 * 256
+
+    def reset(self):
+        self.buf.zero_()
+
+    def download(self) -> dict:
+        """The arrays of the state as the header lays them out (synchronises)."""
+        cfg, B = self.model.cfg, self.B
+        off = self.ptr - self.buf.data_ptr()
+        raw = self.buf.cpu().numpy()[off:off + self.bytes]
+        ints = (B * 4 + 255) // 256 * 256
+        get = lambda i: raw[i * ints:i * ints + 4 * B].view(np.int32).copy()
+        out = dict(started=get(0), time=get(1), last=get(2), last2=get(3))
+        if cfg.pred_kind == "lstm":
+            n = cfg.pred_layers * B * cfg.h_pred
+            fl = (n * 4 + 255) // 256 * 256
+            shape = (cfg.pred_layers, B, cfg.h_pred)
+            out["h"] = raw[4 * ints:4 * ints + 4 * n].view(np.float32).reshape(shape).copy()
+            out["c"] = raw[4 * ints + fl:4 * ints + fl + 4 * n].view(np.float32).reshape(shape).copy()
+        return out
+
+
+class ChunkDecoder(Decoder):
+    """``Decoder`` for chunks: each call decodes the next chunk (at most T frames each) of the
+    B utterances whose state ``state`` holds."""
+
+    def __init__(self, model: DeviceModel, B: int, T: int, u_cap: int, state: StreamState, **kw):
+        super().__init__(model, B, T, u_cap, **kw)
+        self.state = state
+
+    def __call__(self, enc_dev, enc_len_dev, T: Optional[int] = None,
+                 max_symbols: Optional[int] = None, stream=None):
+        import torch
+        cfg = self.model.cfg
+        T = self.T if T is None else T
+        assert 1 <= T <= self.T, "the workspace was sized for chunks of at most self.T frames"
+        s = stream if stream is not None else torch.cuda.current_stream(self.model.device)
+        tdt_greedy_decode_chunk(
+            enc_dev.data_ptr(), enc_len_dev.data_ptr(), self.B, T, self.model.c,
+            list(cfg.durations) if cfg.durations else None,
+            cfg.max_symbols if max_symbols is None else max_symbols, self.u_cap,
+            self.labels.data_ptr(), self.frames.data_ptr(), self.lens.data_ptr(),
+            self.score.data_ptr(), self.status.data_ptr(), self.stats.data_ptr(),
+            self.state.ptr, self.ws_ptr, self.ws_bytes, self.options, s.cuda_stream)

@@ -86,6 +86,9 @@ struct HypShared {
     float score[kMaxHypsPerCluster];
     unsigned char active[kMaxHypsPerCluster];
     unsigned char need[kMaxHypsPerCluster];
+    unsigned char started[kMaxHypsPerCluster];   // the start-of-sequence predictor step is done (chunked decoding)
+    unsigned char took_part[kMaxHypsPerCluster]; // was active in this call
+    unsigned char hpar[kMaxHypsPerCluster];      // which half of hbuf holds the hypothesis's newest state
     int act_list[kMaxHypsPerCluster];
     int need_list[kMaxHypsPerCluster];
     int n_act, n_need;
@@ -723,22 +726,40 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     unsigned long long *const rd_base = p.row_dur + (size_t)cl * kRowBufs * rows_cap;
     const int max_cg = min(kMaxColGroups, kPartialEntries / ncl / kMaxRowsPerPass);
 
+    const bool chunked = p.st_started != nullptr;
     // ---- Alg. 3 lines 3-4: empty hypotheses, time 0, everyone with frames is active
     for (int g = tid; g < G; g += kThreads) {
         int len = p.enc_len[S.gid[g]];
         int st = 0;
         if (len < 0) { len = 0; st = TDT_HYP_LEN_CLAMPED; }
         if (len > T) { len = T; st = TDT_HYP_LEN_CLAMPED; }
+        // A chunk of a longer utterance takes up what the previous chunk left: the frames
+        // its last step reached past its end, and the labels the predictor saw last.
+        int t0 = 0, last = V, last2 = V;   // V: the start-of-sequence label
+        bool started = false;
+        if (chunked) {
+            const int b = S.gid[g];
+            started = p.st_started[b] != 0;
+            t0 = max(p.st_time[b], 0);
+            if (started) {
+                last = min(max(p.st_last[b], 0), V);
+                last2 = min(max(p.st_last2[b], 0), V);
+            }
+        }
+        const bool active = t0 < len;
         S.len[g] = len;
-        S.time[g] = 0;
+        S.time[g] = t0;
         S.sym[g] = 0;
-        S.last[g] = V;    // start-of-sequence label
-        S.last2[g] = V;
+        S.last[g] = last;
+        S.last2[g] = last2;
         S.out_len[g] = 0;
         S.status[g] = st;
         S.score[g] = 0.0f;
-        S.active[g] = len > 0;
-        S.need[g] = 0;
+        S.active[g] = active;
+        S.need[g] = active && !started;   // who takes the first predictor step
+        S.started[g] = started || active;
+        S.took_part[g] = active;
+        S.hpar[g] = 1;
     }
     if (tid < TDT_MAX_DURATIONS) S.durations[tid] = p.durations[tid];
     if (tid == 0) {
@@ -806,6 +827,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         auto_rows = max(1, C / groups) * RT;
     }
     int pp = 0;          // which half of hbuf holds the current hidden state
+    bool first = true;   // the first label-loop iteration of this call
     unsigned jpass = 0;  // joint passes so far (selects the exchange buffers)
     bool ok = true;
     // A barrier this workgroup has arrived at but not yet waited for, and the timer bucket of
@@ -832,11 +854,38 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         if (tid == 0) {
             S.st[4] += 1;
             S.st[0] += 1;
-            S.st[1] += n_act;
         }
         const int n_tiles_a = (n_act + RT - 1) / RT;
+        // Who takes the predictor step: every active hypothesis -- except in the first
+        // iteration of a chunk, where the hypotheses that bring a state along keep it and
+        // only those at their start of sequence step.
+        const int *plist = S.act_list;
+        int n_p = n_act;
+        if (first) {
+            build_list(S, S.need, G, S.need_list, &S.n_need);
+            plist = S.need_list;
+            n_p = S.n_need;
+            if (chunked && lstm) {
+                // the state brought along goes where this iteration's step would have put it
+                const int per = L * Hp;
+                for (int idx = rank * kThreads + tid; idx < n_act * per; idx += C * kThreads) {
+                    const int i = idx / per, r = idx - i * per, l = r / Hp, u = r - l * Hp;
+                    const int g = S.act_list[i];
+                    if (!S.need[g]) {
+                        const size_t src = ((size_t)l * B + S.gid[g]) * Hp + u;
+                        const size_t dst = ((size_t)l * Bw + b0 + g) * Hp + u;
+                        st_co(p.hbuf + (size_t)L * Bw * Hp + dst, p.st_h[src]);
+                        st_co(p.cbuf + dst, p.st_c[src]);
+                    }
+                }
+            }
+            first = false;
+        }
+        for (int i = tid; i < n_act; i += kThreads) S.hpar[S.act_list[i]] = (unsigned char)(pp ^ 1);
+        const int n_tiles_p = (n_p + RT - 1) / RT;
 
         // ---- P: predictor step (Alg. 3 line 6)
+        if (tid == 0) S.st[1] += n_p;
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 0;
         phase_bucket = kTkP;
         if (lstm) {
@@ -847,12 +896,12 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 // known.  What is left is the cell update, one thread per (hypothesis, unit).
                 float *h_next = p.hbuf + ((size_t)(pp ^ 1) * L) * Bw * Hp;
                 float *cst = p.cbuf;
-                const int total = n_act * Hp;
+                const int total = n_p * Hp;
                 const int per_wg = (total + C - 1) / C;
                 const int c_end = min(total, (rank + 1) * per_wg);
                 for (int c = rank * per_wg + tid; c < c_end; c += kThreads) {
                     const int i = c / Hp, unit = c - i * Hp;
-                    const int g = S.act_list[i];
+                    const int g = plist[i];
                     const size_t o = (size_t)(b0 + g) * Hp + unit;
                     const float2 r01 = ld_co2(p.rgate + o * 4), r23 = ld_co2(p.rgate + o * 4 + 2);
                     const float4 t4 =
@@ -884,10 +933,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 in.K1 = Hp;
                 const int NT = (Hp + 3) / 4;   // a column tile = 4 hidden units x 4 gates
                 int n_ug, tpg;
-                split_tiles(C, n_tiles_a, NT, NT, n_ug, tpg);
-                for (int it = rank; it < n_tiles_a * n_ug; it += C) {
+                split_tiles(C, n_tiles_p, NT, NT, n_ug, tpg);
+                for (int it = rank; it < n_tiles_p * n_ug; it += C) {
                     const int ti = it / n_ug, ug = it % n_ug;
-                    const int nrows = min(RT, n_act - ti * RT);
+                    const int nrows = min(RT, n_p - ti * RT);
                     const int tile0 = ug * tpg, n_ct = min(tpg, NT - tile0);
                     // A round holds up to 8 tiles x 16 rows x 16 pre-activations (4 units x 4 gates
                     // a tile): entry idx = tid + e * 512 is (tile slot idx / 256, row idx / 16 % 16,
@@ -900,7 +949,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             const float *src = sg.part == 1 ? h_cur : x_prev;
                             stage_segment<WT>(
                                 A, sg.K, nrows,
-                                [&](int i) { return src + (size_t)(b0 + S.act_list[ti * RT + i]) * Hp + k0; },
+                                [&](int i) { return src + (size_t)(b0 + plist[ti * RT + i]) * Hp + k0; },
                                 [](const float *row, int k) { return ld_co2(row + k); },
                                 [](const float *, int, float2 v) { return v; });
                         },
@@ -914,7 +963,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 const int idx = tid + e * kThreads;
                                 const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
                                 const int unit = (tile0 + base + t) * 4 + (j >> 2);
-                                const int g = S.act_list[ti * RT + (i < nrows ? i : 0)];
+                                const int g = plist[ti * RT + (i < nrows ? i : 0)];
                                 c_old[e] = ld_co(cst + (size_t)(b0 + g) * Hp + (unit < Hp ? unit : 0));
                             }
                         },
@@ -934,7 +983,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                     const float og = __shfl_down(act, 3, 4);
                                     if (q == 0 && i < nrows && unit < Hp) {
                                         const float cn = fg * c_old[e] + act * gg;
-                                        const int g = S.act_list[ti * RT + i];
+                                        const int g = plist[ti * RT + i];
                                         const size_t o = (size_t)(b0 + g) * Hp + unit;
                                         st_co(cst + o, cn);
                                         st_co(h_next + o, og * (2.0f * fast_sigmoid(2.0f * cn) - 1.0f));
@@ -1043,7 +1092,14 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 2;
         phase_bucket = kTkJ;
         // every active hypothesis now searches for its next non-blank label
-        for (int g = tid; g < G; g += kThreads) S.need[g] = S.active[g];
+        for (int g = tid; g < G; g += kThreads) {
+            bool a = S.active[g];
+            if (a && chunked && (S.time[g] >= S.len[g] || (S.status[g] & TDT_HYP_TRUNCATED))) {
+                a = false;   // had only stayed for the predictor step of its last label
+                S.active[g] = 0;
+            }
+            S.need[g] = a;
+        }
         __syncthreads();
         build_list(S, S.need, G, S.need_list, &S.n_need);
 
@@ -1270,7 +1326,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     S.time[g] = t1;
                     bool act_now = t1 < len;
                     if (n + 1 >= p.u_cap) { act_now = false; S.status[g] |= TDT_HYP_TRUNCATED; }
-                    S.active[g] = act_now;
+                    // In a chunk a hypothesis that is done still takes the predictor step of its
+                    // last label, so that the state it carries on has seen it.
+                    S.active[g] = act_now || chunked;
                     S.need[g] = 0;
                 } else {
                     const int t1 = t0 + w;
@@ -1348,6 +1406,34 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 
     finish_scores();
     __syncthreads();
+
+    // ---- what the next chunk takes up (every step that wrote these rows was followed by a
+    // barrier of the cluster before its hypothesis could go inactive)
+    if (chunked && ok) {
+        if (lstm) {
+            const int per = L * Hp;
+            for (int idx = rank * kThreads + tid; idx < G * per; idx += C * kThreads) {
+                const int g = idx / per, r = idx - g * per, l = r / Hp, u = r - l * Hp;
+                if (S.took_part[g]) {
+                    const size_t src = ((size_t)l * Bw + b0 + g) * Hp + u;
+                    const size_t dst = ((size_t)l * B + S.gid[g]) * Hp + u;
+                    p.st_h[dst] = ld_co(p.hbuf + (size_t)S.hpar[g] * L * Bw * Hp + src);
+                    p.st_c[dst] = ld_co(p.cbuf + src);
+                }
+            }
+        }
+        if (rank == 0) {
+            for (int g = tid; g < G; g += kThreads) {
+                const int b = S.gid[g];
+                p.st_started[b] = S.started[g];
+                // frames of the next chunk already stepped over; a hypothesis stopped at its
+                // label capacity gives up the rest of this chunk
+                p.st_time[b] = max(S.time[g] - S.len[g], 0);
+                p.st_last[b] = S.last[g];
+                p.st_last2[b] = S.last2[g];
+            }
+        }
+    }
 
     // ---- results of this cluster's hypotheses
     if (rank == 0) {

@@ -47,6 +47,22 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T)
     return L;
 }
 
+StateLayout state_layout(const tdt_weights_t *w, int B)
+{
+    StateLayout L{};
+    const size_t ints = align_up((size_t)B * sizeof(int32_t), 256);
+    L.started = 0;
+    L.time = ints;
+    L.last = 2 * ints;
+    L.last2 = 3 * ints;
+    L.h = 4 * ints;
+    const size_t fl = w->pred_kind == TDT_PRED_LSTM
+                          ? align_up((size_t)w->pred_layers * B * w->h_pred * sizeof(float), 256) : 0;
+    L.c = L.h + fl;
+    L.total = L.c + fl;
+    return L;
+}
+
 static int check_model(const tdt_weights_t *w)
 {
     if (!w) return TDT_ERR_NULL;
@@ -109,11 +125,23 @@ int tdt_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w
     return TDT_OK;
 }
 
-int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
-                      const tdt_weights_t *weights, const int32_t *durations, int max_symbols,
-                      int u_cap, int32_t *out_labels, int32_t *out_frames, int32_t *out_len,
-                      float *out_score, int32_t *out_status, int64_t *out_stats, void *workspace,
-                      size_t workspace_bytes, const tdt_options_t *options, void *stream)
+int tdt_state_bytes(const tdt_weights_t *weights, int B, size_t *bytes)
+{
+    if (!weights || !bytes) return TDT_ERR_NULL;
+    if (B < 1) return TDT_ERR_SHAPE;
+    const int st = check_model(weights);
+    if (st != TDT_OK) return st;
+    *bytes = state_layout(weights, B).total;
+    return TDT_OK;
+}
+
+// the body of both decode entry points; `state` is null for whole utterances
+static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
+                         const tdt_weights_t *weights, const int32_t *durations, int max_symbols,
+                         int u_cap, int32_t *out_labels, int32_t *out_frames, int32_t *out_len,
+                         float *out_score, int32_t *out_status, int64_t *out_stats, void *state,
+                         void *workspace, size_t workspace_bytes, const tdt_options_t *options,
+                         void *stream)
 {
     if (!weights) return TDT_ERR_NULL;
     int st = check_model(weights);
@@ -123,12 +151,12 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     st = check_model_pointers(weights, true);
     if (st != TDT_OK) return st;
     if (B < 1 || T < 1 || u_cap < 1 || max_symbols < 1) return TDT_ERR_SHAPE;
-    if ((int64_t)B * T > ((int64_t)1 << 31) || (int64_t)B * u_cap > ((int64_t)1 << 40)) return TDT_ERR_SHAPE;
+    if ((int64_t)B * T > ((int64_t)1 << 31) || T > (1 << 30) || (int64_t)B * u_cap > ((int64_t)1 << 40)) return TDT_ERR_SHAPE;
     // durations (Sec. 3.3): one non-negative frame increment per class, at least one positive
     if ((weights->n_dur == 0) != (durations == nullptr)) return TDT_ERR_DURATIONS;
     bool any_pos = weights->n_dur == 0;
     for (int j = 0; j < weights->n_dur; ++j) {
-        if (durations[j] < 0 || durations[j] > T + 1) return TDT_ERR_DURATIONS;
+        if (durations[j] < 0 || durations[j] > kMaxDuration) return TDT_ERR_DURATIONS;
         any_pos |= durations[j] > 0;
     }
     if (!any_pos) return TDT_ERR_DURATIONS;
@@ -219,6 +247,16 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     p.out_status = out_status;
     p.out_score = out_score;
     p.out_stats = reinterpret_cast<long long *>(out_stats);
+    if (state) {
+        const StateLayout SL = state_layout(weights, B);
+        char *sp = static_cast<char *>(state);
+        p.st_started = reinterpret_cast<int32_t *>(sp + SL.started);
+        p.st_time = reinterpret_cast<int32_t *>(sp + SL.time);
+        p.st_last = reinterpret_cast<int32_t *>(sp + SL.last);
+        p.st_last2 = reinterpret_cast<int32_t *>(sp + SL.last2);
+        p.st_h = reinterpret_cast<float *>(sp + SL.h);
+        p.st_c = reinterpret_cast<float *>(sp + SL.c);
+    }
     p.hbuf = reinterpret_cast<float *>(ws + L.hbuf);
     p.cbuf = reinterpret_cast<float *>(ws + L.cbuf);
     p.rgate = reinterpret_cast<float *>(ws + L.rgate);
@@ -240,6 +278,31 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
     }
     if (launch_decode(p, weights, grid, s) != hipSuccess) return TDT_ERR_LAUNCH;
     return TDT_OK;
+}
+
+int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
+                      const tdt_weights_t *weights, const int32_t *durations, int max_symbols,
+                      int u_cap, int32_t *out_labels, int32_t *out_frames, int32_t *out_len,
+                      float *out_score, int32_t *out_status, int64_t *out_stats, void *workspace,
+                      size_t workspace_bytes, const tdt_options_t *options, void *stream)
+{
+    return decode_common(enc, enc_len, B, T, weights, durations, max_symbols, u_cap, out_labels,
+                         out_frames, out_len, out_score, out_status, out_stats, nullptr, workspace,
+                         workspace_bytes, options, stream);
+}
+
+int tdt_greedy_decode_chunk(const void *enc, const int32_t *enc_len, int B, int T,
+                            const tdt_weights_t *weights, const int32_t *durations, int max_symbols,
+                            int u_cap, int32_t *out_labels, int32_t *out_frames, int32_t *out_len,
+                            float *out_score, int32_t *out_status, int64_t *out_stats, void *state,
+                            void *workspace, size_t workspace_bytes, const tdt_options_t *options,
+                            void *stream)
+{
+    if (!state) return TDT_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(state) & 255) != 0) return TDT_ERR_WORKSPACE;
+    return decode_common(enc, enc_len, B, T, weights, durations, max_symbols, u_cap, out_labels,
+                         out_frames, out_len, out_score, out_status, out_stats, state, workspace,
+                         workspace_bytes, options, stream);
 }
 
 const char *tdt_status_string(int status)

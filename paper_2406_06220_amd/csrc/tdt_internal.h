@@ -19,6 +19,7 @@ constexpr int kPartialEntries = kMaxRowsPerPass * kMaxGrid;  // per partial buff
 constexpr int kXcds = 8;                      // accelerator dies of an MI355X; workgroups are dealt to them in turn
 constexpr int kBarrierStride = 32;            // uint32 slots between two workgroups' barrier flags
 constexpr int kMaxRankedBatch = 1024;          // largest batch whose hypotheses are dealt to the clusters by length
+constexpr int kMaxDuration = 1 << 20;          // largest frame increment of a duration class
 constexpr int kRowBufs = 3;                   // rotating per-row argmax buffers
 
 // Softmax-denominator share of one slice of label columns for one joint row.
@@ -54,6 +55,9 @@ struct DecodeParams {
     int32_t *out_labels, *out_frames, *out_len, *out_status;
     float *out_score;
     long long *out_stats;    // may be null
+    // state carried between the chunks of longer utterances; all null for whole utterances
+    int32_t *st_started, *st_time, *st_last, *st_last2;   // [B] each
+    float *st_h, *st_c;      // [layers][B][h_pred] (LSTM only)
     // workspace
     float *hbuf;             // [2][layers][B][h_pred]  ping-pong hidden state
     float *cbuf;             // [layers][B][h_pred]
@@ -75,6 +79,12 @@ struct WorkspaceLayout {
 };
 
 WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T);
+
+// the caller-held state of tdt_greedy_decode_chunk: byte offsets of its arrays
+struct StateLayout {
+    size_t started, time, last, last2, h, c, total;
+};
+StateLayout state_layout(const tdt_weights_t *w, int B);
 
 // launches (each returns a hipError_t)
 hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,

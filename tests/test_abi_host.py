@@ -125,3 +125,41 @@ def test_rejects_bad_arguments_before_device_work(lib):
     assert lib.tdt_encoder_projection(None, 10, C.byref(w), 4096, None) == -1
     assert lib.tdt_encoder_projection(4096, -1, C.byref(w), 4096, None) == -2
     assert lib.tdt_encoder_projection(4096, 10, None, 4096, None) == -1
+
+
+def test_chunk_entry_point_rejects_before_device_work(lib):
+    cfg = synth.CFG3
+    w = _weights(cfg)
+    dur = (C.c_int32 * len(cfg.durations))(*cfg.durations)
+
+    def call(state, **kw):
+        a = dict(enc=4096, B=2, T=10, S=3, u_cap=30, ws=4096)
+        a.update(kw)
+        return lib.tdt_greedy_decode_chunk(a["enc"], 4096, a["B"], a["T"], C.byref(w), dur, a["S"],
+                                           a["u_cap"], 4096, 4096, 4096, 4096, 4096, None, state,
+                                           a["ws"], 1 << 40, None, None)
+
+    assert call(None) == -1                  # no state
+    assert call(4096 + 4) == -5              # misaligned state
+    assert call(4096, enc=None) == -1        # then the checks of tdt_greedy_decode
+    assert call(4096, B=0) == -2
+    assert call(4096, ws=None) == -5
+    # a chunk may be shorter than the longest duration
+    dur_long = (C.c_int32 * 5)(0, 1, 2, 3, 1 << 21)
+    assert lib.tdt_greedy_decode_chunk(4096, 4096, 2, 1, C.byref(w), dur_long, 3, 30, 4096, 4096,
+                                       4096, 4096, 4096, None, 4096, None, 0, None, None) == -4
+    assert call(4096, T=1, ws=None) == -5    # durations {0..4} pass with one-frame chunks
+
+
+def test_state_bytes(lib):
+    cfg = synth.CFG5                          # two LSTM layers
+    w = _weights(cfg)
+    n = binding.tdt_state_bytes(w, cfg.B)
+    ints = (cfg.B * 4 + 255) // 256 * 256
+    fl = (cfg.pred_layers * cfg.B * cfg.h_pred * 4 + 255) // 256 * 256
+    assert n == 4 * ints + 2 * fl
+    assert binding.tdt_state_bytes(_weights(synth.CFG4), 128) == 4 * 512      # stateless: labels only
+    size = C.c_size_t()
+    assert lib.tdt_state_bytes(None, 1, C.byref(size)) == -1
+    assert lib.tdt_state_bytes(C.byref(w), 0, C.byref(size)) == -2
+    assert lib.tdt_state_bytes(C.byref(w), 1, None) == -1

@@ -1,0 +1,229 @@
+"""GPU parity of tdt_greedy_decode_chunk: utterances decoded piece by piece through the C ABI
+against the CPU oracle.  The chunks' hypotheses, stitched together, go through the same rule as
+whole utterances (tests/parity.py); the state left after the last chunk is compared with the
+state the oracle's chunked decode leaves."""
+from __future__ import annotations
+
+import dataclasses
+
+import numpy as np
+import pytest
+
+import chunks
+import fig2_model
+import parity
+from paper_2406_06220_amd import synth
+from test_gpu_parity import SMALL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2406_06220_amd import binding
+    binding.load_library()
+    return binding
+
+
+class Stream:
+    """One batch of slots decoded chunk by chunk on the GPU."""
+
+    def __init__(self, binding, cfg, w, B, t_max, u_cap, **opts):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.model = binding.DeviceModel(cfg, w)
+        self.state = binding.StreamState(self.model, B)
+        self.dec = binding.ChunkDecoder(self.model, B, t_max, u_cap, self.state, **opts)
+        self.opts = opts
+
+    def feed(self, enc_chunk, len_chunk, max_symbols=None):
+        parity.announce(f"tdt_greedy_decode_chunk cfg={self.cfg.name} B={len(len_chunk)} "
+                        f"T={enc_chunk.shape[1]} lens={len_chunk.tolist()[:8]} opts={self.opts}")
+        enc_d = self.model.upload_enc(enc_chunk)
+        len_d = self.torch.from_numpy(np.ascontiguousarray(len_chunk, np.int32)).to(self.model.device)
+        self.dec(enc_d, len_d, T=enc_chunk.shape[1], max_symbols=max_symbols)
+        out = self.dec.results()
+        assert out["stats"]["abort"] == 0, "a device-side wait timed out"
+        return out
+
+
+def decode_in_chunks(binding, cfg, w, enc, ln, bounds, u_cap, seed=0, **opts):
+    rng = np.random.default_rng(seed)
+    t_max = int(max(int((bounds[:, 1:] - bounds[:, :-1]).max()), 1))
+    st = Stream(binding, cfg, w, len(ln), t_max, u_cap, **opts)
+    parts = []
+    for c in range(bounds.shape[1] - 1):
+        ec, lc = chunks.make_chunk(enc, bounds, c, rng)
+        parts.append(st.feed(ec, lc))
+    return chunks.stitch(parts, bounds, u_cap), st.state.download(), parts
+
+
+def oracle_in_chunks(oracle, om, cfg, enc, ln, bounds, u_cap, seed=0):
+    rng = np.random.default_rng(seed)
+    state = oracle.stream_state(om, len(ln))
+    parts = []
+    for c in range(bounds.shape[1] - 1):
+        ec, lc = chunks.make_chunk(enc, bounds, c, rng)
+        parts.append(oracle.decode_batch_chunk(om, ec, lc, cfg.max_symbols, u_cap, state))
+    return chunks.stitch(parts, bounds, u_cap), state, parts
+
+
+def check_state(cfg, got, ref, rows):
+    """Carried state of the rows whose hypotheses agree exactly."""
+    for b in rows:
+        assert got["started"][b] == ref["started"][b], f"row {b}: started"
+        assert got["time"][b] == ref["time"][b], f"row {b}: time"
+        if not ref["started"][b]:
+            continue
+        if cfg.pred_kind == "lstm":
+            n = cfg.pred_layers * cfg.h_pred
+            np.testing.assert_allclose(got["h"][:, b].reshape(-1), ref["h"][b][:n], atol=1e-4, rtol=0)
+            np.testing.assert_allclose(got["c"][:, b].reshape(-1), ref["c"][b][:n], atol=2e-4, rtol=0)
+        elif cfg.pred_layers == 2:
+            assert (got["last2"][b], got["last"][b]) == tuple(ref["ctx"][b, :2]), f"row {b}: context"
+        else:
+            assert got["last"][b] == ref["ctx"][b, 0], f"row {b}: context"
+
+
+def check_chunks(oracle, binding, cfg, mode, n_chunks, w=None, enc=None, ln=None,
+                 max_replayed_frac=0.1, **opts):
+    w = synth.generate_model(cfg) if w is None else w
+    if enc is None:
+        enc, ln = synth.generate_inputs(cfg)
+    u_cap = cfg.T * cfg.max_symbols
+    bounds = chunks.split_plan(ln, n_chunks, np.random.default_rng(7 + n_chunks), mode)
+    got, state, _ = decode_in_chunks(binding, cfg, w, enc, ln, bounds, u_cap, **opts)
+    om = oracle.OracleModel(cfg, w)
+    res = parity.compare(oracle, om, cfg, enc, ln, got, u_cap)
+    assert res["replayed"] <= max(1, int(max_replayed_frac * res["rows"])), res
+    ref, ref_state, _ = oracle_in_chunks(oracle, om, cfg, enc, ln, bounds, u_cap)
+    exact = [b for b in range(len(ln)) if got["len"][b] == ref["len"][b]
+             and (got["labels"][b] == ref["labels"][b]).all() and (got["frames"][b] == ref["frames"][b]).all()]
+    assert len(exact) >= res["exact"]
+    check_state(cfg, state, ref_state, exact)
+    parity.announce(f"  -> {res}")
+    return res
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+@pytest.mark.parametrize("mode,n_chunks,opts", [
+    ("random", 4, {}), ("even", 2, dict(window=1, n_clusters=1)), ("random", 7, dict(window=5, n_clusters=3)),
+], ids=["random4", "halves_w1", "random7_w5c3"])
+def test_small_models_in_chunks(oracle_lib, gpu, cfg, mode, n_chunks, opts):
+    check_chunks(oracle_lib, gpu, cfg, mode, n_chunks, **opts)
+
+
+@pytest.mark.parametrize("cfg", [SMALL[1], SMALL[3], SMALL[6]], ids=lambda c: c.name)
+def test_frame_by_frame(oracle_lib, gpu, cfg):
+    """One frame a chunk: every TDT duration above 1 reaches into later chunks."""
+    check_chunks(oracle_lib, gpu, cfg, "single", 0)
+
+
+def test_fig2_in_two_chunks(gpu):
+    ex = fig2_model.build()
+    cfg, w, enc, ln = fig2_model.real_model(ex)
+    bounds = np.array([[0, 2, 4]] * ex["B"])
+    got, state, parts = decode_in_chunks(gpu, cfg, w, enc, ln, bounds, 16)
+    for b, em in enumerate(ex["expected"]):
+        n = got["len"][b]
+        assert list(zip(got["labels"][b, :n], got["frames"][b, :n])) == em
+        first = [(k, t) for k, t in em if t < 2]
+        assert parts[0]["len"][b] == len(first)
+    assert (state["started"] == 1).all() and (state["time"] == 0).all()
+
+
+@pytest.mark.parametrize("name,n_chunks", [("cfg2_rnnt_lstm", 5), ("cfg3_tdt_lstm", 4),
+                                           ("cfg4_rnnt_stateless", 3)])
+def test_paper_sized_models_in_chunks(oracle_lib, gpu, name, n_chunks):
+    cfg = synth.CONFIGS[name]
+    res = check_chunks(oracle_lib, gpu, cfg, "even", n_chunks, max_replayed_frac=0.15)
+    assert res["max_score_err"] <= parity.TOL_SCORE
+
+
+def test_slots_change_hands(oracle_lib, gpu):
+    """A batch slot whose state is cleared starts a new utterance while its neighbours go on;
+    empty chunks and slots that never get a frame leave their state alone."""
+    cfg = SMALL[3]                       # TDT, two LSTM layers
+    w = synth.generate_model(cfg)
+    encA, lnA = synth.generate_inputs(cfg)
+    encB, lnB = synth.generate_inputs(dataclasses.replace(cfg, seed=cfg.seed + 100))
+    lnA = np.maximum(lnA, 8)
+    lnB = np.maximum(lnB, 1)
+    B, S = cfg.B, cfg.max_symbols
+    u_cap = cfg.T * S
+    cut = lnA // 2
+    om = oracle_lib.OracleModel(cfg, w)
+    st = Stream(gpu, cfg, w, B, cfg.T, u_cap)
+    ref_state = oracle_lib.stream_state(om, B)
+    fresh = np.arange(B) % 3 == 0        # these slots are handed to a new utterance
+    idle = np.arange(B) % 3 == 1         # these get an empty chunk in between
+
+    def both(enc, ln):
+        g = st.feed(enc, ln)
+        r = oracle_lib.decode_batch_chunk(om, enc, ln, S, u_cap, ref_state)
+        rows = []
+        for b in range(B):
+            n = r["len"][b]
+            if g["len"][b] == n and (g["labels"][b, :n] == r["labels"][b, :n]).all() \
+                    and (g["frames"][b, :n] == r["frames"][b, :n]).all():
+                rows.append(b)
+                assert abs(g["score"][b] - r["score"][b]) <= parity.TOL_SCORE
+        return rows
+
+    first = np.zeros_like(encA)
+    for b in range(B):
+        first[b, :cut[b]] = encA[b, :cut[b]]
+    ok1 = both(first, cut.astype(np.int32))
+    # hand over the slots: clear their state on both sides
+    import torch
+    raw = st.state.download()
+    ints = (B * 4 + 255) // 256 * 256
+    off = st.state.ptr - st.state.buf.data_ptr()
+    view = st.state.buf[off:off + 4 * B].view(torch.int32)      # started[]
+    view[torch.from_numpy(fresh).to(view.device)] = 0
+    t2 = st.state.buf[off + ints:off + ints + 4 * B].view(torch.int32)   # time[]
+    t2[torch.from_numpy(fresh).to(view.device)] = 0
+    ref_state["started"][fresh] = 0
+    ref_state["time"][fresh] = 0
+    second = np.zeros_like(encA)
+    ln2 = np.zeros(B, np.int32)
+    for b in range(B):
+        if fresh[b]:
+            second[b, :lnB[b]] = encB[b, :lnB[b]]
+            ln2[b] = lnB[b]
+        elif not idle[b]:
+            n = lnA[b] - cut[b]
+            second[b, :n] = encA[b, cut[b]:lnA[b]]
+            ln2[b] = n
+    ok2 = both(second, ln2)
+    third = np.zeros_like(encA)
+    ln3 = np.zeros(B, np.int32)
+    for b in range(B):
+        if idle[b]:
+            n = lnA[b] - cut[b]
+            third[b, :n] = encA[b, cut[b]:lnA[b]]
+            ln3[b] = n
+    ok3 = both(third, ln3)
+    agree = sorted(set(ok1) & set(ok2) & set(ok3))
+    assert len(agree) >= B - 2, (ok1, ok2, ok3)
+    check_state(cfg, st.state.download(), ref_state, agree)
+    assert raw["started"].all()
+
+
+def test_chunk_capacity(oracle_lib, gpu):
+    """A hypothesis that fills its capacity inside a chunk gives up the rest of that chunk."""
+    cfg = SMALL[2]
+    w = synth.generate_model(cfg, -3.0)
+    enc, ln = synth.generate_inputs(cfg)
+    om = oracle_lib.OracleModel(cfg, w)
+    st = Stream(gpu, cfg, w, cfg.B, cfg.T, 3)
+    g = st.feed(enc, ln)
+    ref_state = oracle_lib.stream_state(om, cfg.B)
+    r = oracle_lib.decode_batch_chunk(om, enc, ln, cfg.max_symbols, 3, ref_state)
+    assert (g["len"] == r["len"]).all() and ((g["status"] & 1) == r["status"]).all()
+    same = [b for b in range(cfg.B) if (g["labels"][b, :g["len"][b]] == r["labels"][b, :r["len"][b]]).all()]
+    assert len(same) >= cfg.B - 1
+    check_state(cfg, st.state.download(), ref_state, same)
