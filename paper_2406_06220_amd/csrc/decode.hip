@@ -645,7 +645,9 @@ __device__ inline float cpart_sum(const HypShared &S, int t, int ksplit, int i, 
     return v;
 }
 
-template <typename WT>
+// CHUNKED: the call decodes the next chunk of longer utterances (tdt_greedy_decode_chunk);
+// compiled apart so that whole-utterance decoding carries none of its bookkeeping.
+template <typename WT, bool CHUNKED>
 __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_lds[];
@@ -726,7 +728,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     unsigned long long *const rd_base = p.row_dur + (size_t)cl * kRowBufs * rows_cap;
     const int max_cg = min(kMaxColGroups, kPartialEntries / ncl / kMaxRowsPerPass);
 
-    const bool chunked = p.st_started != nullptr;
+    constexpr bool chunked = CHUNKED;
     // ---- Alg. 3 lines 3-4: empty hypotheses, time 0, everyone with frames is active
     for (int g = tid; g < G; g += kThreads) {
         int len = p.enc_len[S.gid[g]];
@@ -861,11 +863,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         // only those at their start of sequence step.
         const int *plist = S.act_list;
         int n_p = n_act;
-        if (first) {
+        if (chunked && first) {
             build_list(S, S.need, G, S.need_list, &S.n_need);
             plist = S.need_list;
             n_p = S.n_need;
-            if (chunked && lstm) {
+            if (lstm) {
                 // the state brought along goes where this iteration's step would have put it
                 const int per = L * Hp;
                 for (int idx = rank * kThreads + tid; idx < n_act * per; idx += C * kThreads) {
@@ -881,7 +883,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             }
             first = false;
         }
-        for (int i = tid; i < n_act; i += kThreads) S.hpar[S.act_list[i]] = (unsigned char)(pp ^ 1);
+        if (chunked)
+            for (int i = tid; i < n_act; i += kThreads) S.hpar[S.act_list[i]] = (unsigned char)(pp ^ 1);
         const int n_tiles_p = (n_p + RT - 1) / RT;
 
         // ---- P: predictor step (Alg. 3 line 6)
@@ -1504,10 +1507,17 @@ hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats
     return hipGetLastError();
 }
 
-int decode_max_grid(const tdt_weights_t *w)
+static const void *kernel_for(const tdt_weights_t *w, bool chunked)
+{
+    if (w->dtype == 1)
+        return chunked ? (const void *)decode_kernel<uint16_t, true> : (const void *)decode_kernel<uint16_t, false>;
+    return chunked ? (const void *)decode_kernel<float, true> : (const void *)decode_kernel<float, false>;
+}
+
+int decode_max_grid(const tdt_weights_t *w, bool chunked)
 {
     const size_t lds = lds_bytes_for(w);
-    const void *fn = w->dtype == 1 ? (const void *)decode_kernel<uint16_t> : (const void *)decode_kernel<float>;
+    const void *fn = kernel_for(w, chunked);
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return 0;
@@ -1515,9 +1525,7 @@ int decode_max_grid(const tdt_weights_t *w)
     int dev = 0, n_cu = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    hipError_t e = w->dtype == 1
-        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<uint16_t>, kThreads, lds)
-        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_kernel<float>, kThreads, lds);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, lds);
     if (e != hipSuccess || per_cu < 1) {
         (void)hipGetLastError();
         return 0;
@@ -1533,7 +1541,7 @@ hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid
     DecodeParams pc = p;
     pc.kseg_max = kseg_max_for(w);
     void *args[] = {&pc};
-    const void *fn = w->dtype == 1 ? (const void *)decode_kernel<uint16_t> : (const void *)decode_kernel<float>;
+    const void *fn = kernel_for(w, p.st_started != nullptr);
     // cooperative launch: the runtime refuses a grid whose workgroups cannot all be
     // resident at once, which is what the cluster barriers rely on
     return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(kThreads), args, (unsigned)lds, stream);

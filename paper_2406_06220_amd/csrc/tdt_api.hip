@@ -176,7 +176,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < L.total)
         return TDT_ERR_WORKSPACE;
 
-    const int max_grid = decode_max_grid(weights);
+    const int max_grid = decode_max_grid(weights, state != nullptr);
     if (max_grid < 1) return TDT_ERR_LAUNCH;
     const int min_clusters = (B + kMaxHypsPerCluster - 1) / kMaxHypsPerCluster;
     if (n_clusters == 0) {

@@ -98,6 +98,6 @@ hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats
                        hipStream_t stream);
 hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid, hipStream_t stream);
 // largest grid the decode kernel can run with all workgroups resident, 0 on error
-int decode_max_grid(const tdt_weights_t *w);
+int decode_max_grid(const tdt_weights_t *w, bool chunked);
 
 }  // namespace tdt
