@@ -24,6 +24,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 _f32p = C.POINTER(C.c_float)
 _i32p = C.POINTER(C.c_int32)
 _i64p = C.POINTER(C.c_int64)
+MAX_LAYERS = 4   # ORC_MAX_LAYERS of the C source
 
 
 class _Model(C.Structure):
@@ -32,7 +33,7 @@ class _Model(C.Structure):
         ("pred_kind", C.c_int32), ("pred_layers", C.c_int32), ("h_pred", C.c_int32),
         ("emb_dim", C.c_int32),
         ("w_enc", _f32p), ("b_enc", _f32p), ("emb", _f32p),
-        ("w_ih", _f32p * 2), ("w_hh", _f32p * 2), ("b_lstm", _f32p * 2),
+        ("w_ih", _f32p * MAX_LAYERS), ("w_hh", _f32p * MAX_LAYERS), ("b_lstm", _f32p * MAX_LAYERS),
         ("w_pred", _f32p), ("b_pred", _f32p), ("w_out", _f32p), ("b_out", _f32p),
     ]
 

@@ -53,7 +53,7 @@
 #include <omp.h>
 #endif
 
-#define ORC_MAX_LAYERS 2
+#define ORC_MAX_LAYERS 4
 #define ORC_MAX_CTX 2
 
 typedef struct {

@@ -44,6 +44,10 @@ SMALL = [
                        seed=16, B=5, T=20, len_lo=0, len_hi=20, default_blank_bias=0.2),
     synth.small_config("s_tdt_no01", pred_kind="lstm", durations=(2, 3), seed=17,
                        default_blank_bias=0.0),
+    synth.small_config("s_rnnt_lstm3", pred_kind="lstm", pred_layers=3, seed=19,
+                       default_blank_bias=0.5),
+    synth.small_config("s_tdt_lstm4", pred_kind="lstm", pred_layers=4, durations=(0, 1, 2), seed=20,
+                       h_pred=16, emb_dim=8, default_blank_bias=0.3),
     synth.small_config("s_bf16_lstm", dtype="bf16", pred_kind="lstm", seed=18, d_enc=16,
                        h_pred=16, emb_dim=16, h_joint=24, vocab=11, default_blank_bias=0.6),
 ]
