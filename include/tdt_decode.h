@@ -31,7 +31,7 @@
 extern "C" {
 #endif
 
-#define TDT_MAX_LSTM_LAYERS 2
+#define TDT_MAX_LSTM_LAYERS 4
 #define TDT_MAX_CONTEXT 2
 #define TDT_MAX_DURATIONS 16
 /* widest vector a kernel stages per row: d_enc, h_joint, h_pred and
@@ -70,7 +70,7 @@ enum tdt_pred_kind {
  *
  * LSTM gate order in w_ih / w_hh / b_lstm rows is i, f, g, o (four blocks of
  * h_pred rows); one bias vector per layer.  Layer 0 reads the embedding
- * (emb_dim), layer 1 reads layer 0's hidden state (h_pred).
+ * (emb_dim), every further layer the hidden state of the layer below (h_pred).
  * Stateless predictor: `pred_layers` is the context size c (1 or 2); emb holds c
  * tables [c][V+1][emb_dim]; table c-1 embeds the newest label; h_pred must equal
  * c * emb_dim.  All pointers DEVICE; unused entries may be NULL.
@@ -82,7 +82,7 @@ typedef struct {
     int32_t vocab;       /* V, number of real labels */
     int32_t n_dur;       /* D, number of duration classes; 0 = plain Transducer */
     int32_t pred_kind;   /* enum tdt_pred_kind */
-    int32_t pred_layers; /* LSTM layers (1..2) or stateless context size (1..2) */
+    int32_t pred_layers; /* LSTM layers (1..4) or stateless context size (1..2) */
     int32_t h_pred;      /* predictor output width */
     int32_t emb_dim;     /* embedding width (per table) */
     const void *w_enc;   /* [h_joint][d_enc] */

@@ -18,7 +18,7 @@ from . import synth
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtdt_decode.so")
 
-TDT_MAX_LSTM_LAYERS = 2
+TDT_MAX_LSTM_LAYERS = 4
 TDT_STAT_NAMES = {"pred_passes": 0, "pred_rows": 1, "joint_passes": 2, "joint_rows": 3,
                   "outer_max": 4, "abort": 5, "ticks_pred": 8, "ticks_proj": 9, "ticks_joint": 10,
                   "ticks_decide": 11, "ticks_barrier": 12, "ticks_total": 13,

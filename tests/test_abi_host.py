@@ -46,7 +46,7 @@ def _weights(cfg, fake_ptr=4096):
     w.pred_layers, w.h_pred, w.emb_dim = cfg.pred_layers, cfg.h_pred, cfg.emb_dim
     for f in ("w_enc", "b_enc", "emb", "w_pred", "b_pred", "w_out", "b_out"):
         setattr(w, f, fake_ptr)
-    for l in range(2):
+    for l in range(binding.TDT_MAX_LSTM_LAYERS):
         w.w_ih[l] = w.w_hh[l] = w.b_lstm[l] = fake_ptr
     return w
 
@@ -100,7 +100,7 @@ def test_rejects_bad_arguments_before_device_work(lib):
         w2 = _weights(cfg); setattr(w2, field, val)
         assert _decode(lib, w2, durations=dur) == -2
     # unsupported model kinds
-    for field, val in (("dtype", 2), ("pred_kind", 3), ("pred_layers", 3), ("pred_layers", 0)):
+    for field, val in (("dtype", 2), ("pred_kind", 3), ("pred_layers", 5), ("pred_layers", 0)):
         w2 = _weights(cfg); setattr(w2, field, val)
         assert _decode(lib, w2, durations=dur) == -3
     ws = _weights(synth.CFG4); ws.h_pred = 320       # stateless: h_pred must be ctx * emb_dim

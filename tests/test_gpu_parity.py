@@ -125,6 +125,13 @@ SMALL = [
     synth.small_config("g_rnnt_lstm_bf16_long", dtype="bf16", pred_kind="lstm", d_enc=64,
                        h_pred=1096, emb_dim=32, h_joint=1288, vocab=37, B=3, T=24, len_lo=10,
                        len_hi=24, seed=58, default_blank_bias=1.0, max_symbols=3),
+    # deeper predictors: three layers in float32, four on the matrix cores
+    synth.small_config("g_rnnt_lstm3", pred_kind="lstm", pred_layers=3, d_enc=16, h_pred=24,
+                       emb_dim=8, h_joint=32, vocab=21, B=11, T=48, len_lo=0, len_hi=48, seed=59,
+                       default_blank_bias=0.7),
+    synth.small_config("g_tdt_lstm4_bf16", dtype="bf16", pred_kind="lstm", pred_layers=4,
+                       durations=(0, 1, 2, 4), d_enc=32, h_pred=40, emb_dim=16, h_joint=56, vocab=33,
+                       B=17, T=56, len_lo=4, len_hi=56, seed=60, default_blank_bias=0.5, max_symbols=4),
 ]
 
 
