@@ -80,10 +80,35 @@ def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0):
         b.record(stream)
     torch.cuda.synchronize(dev)
     dec.options.reuse_enc_proj = 0
-    k_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    k_all = [a.elapsed_time(b) for a, b in ev]
+    k_ms = float(np.mean(k_all))
+    # ---- the encoder projection on its own (the dense contraction of the path)
+    proj = torch.empty((cfg.B * cfg.T, cfg.h_joint), dtype=torch.float32, device=dev)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(steps)]
+    for a, b in ev:
+        a.record(stream)
+        binding.tdt_encoder_projection(enc_d.data_ptr(), cfg.B * cfg.T, model.c, proj.data_ptr(),
+                                       stream.cuda_stream)
+        b.record(stream)
+    torch.cuda.synchronize(dev)
+    e_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
     frames = int(np.clip(ln, 0, cfg.T).sum())
     return dict(cfg=cfg, weights=w, enc=enc, len=ln, out=out, sec_per_step=dt, decode_kernel_ms=k_ms,
-                frames=frames, u_cap=u_cap)
+                decode_kernel_ms_min=float(np.min(k_all)), enc_proj_ms=e_ms, frames=frames, u_cap=u_cap)
+
+
+def enc_proj_figures(cfg, ms):
+    """Rates of the encoder-projection GEMM over all B*T rows (padding included, as launched)."""
+    rows = cfg.B * cfg.T
+    wb = 2 if cfg.dtype == "bf16" else 4
+    flops = 2.0 * rows * cfg.d_enc * cfg.h_joint
+    nbytes = rows * cfg.d_enc * wb + cfg.d_enc * cfg.h_joint * wb + rows * cfg.h_joint * 4
+    peak = 2500.0 if cfg.dtype == "bf16" else 157.3
+    return {"kernel": "enc_proj", "ms": ms, "achieved_tflops": flops / (ms * 1e-3) / 1e12,
+            "peak_tflops": peak, "frac_of_mfma_peak": flops / (ms * 1e-3) / 1e12 / peak,
+            "achieved_gbs": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "note": "an event pair around one launch; at this size launch overhead is part of it"}
 
 
 def time_chunked(cfg, chunk_frames, steps, warmup):
@@ -233,7 +258,9 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": alg,
                      "kernel_ms": res["decode_kernel_ms"],
+                     "kernel_ms_min": res["decode_kernel_ms_min"],
                      "traffic": traffic_from_profiles(cfg.name)},
+        "enc_proj": enc_proj_figures(cfg, res["enc_proj_ms"]),
     }
     if not args.no_extra and args.workload == "cfg2_rnnt_lstm":
         cfg_b = synth.CONFIGS["cfg2_rnnt_lstm_b128"]
