@@ -1,0 +1,174 @@
+// How the workgroups of a cluster exchange data and wait for each other: agent-scope relaxed
+// atomics that are served at the device's coherence point, packed (value, index) cells for
+// atomic maxima, the split barrier, and the small list / split helpers of the label loop.
+// Included by decode.hip only.
+#ifndef TDT_EXCHANGE_H
+#define TDT_EXCHANGE_H
+
+#include "tdt_internal.h"
+#include "decode_state.h"
+
+namespace tdt {
+namespace {
+
+// ---- number formats
+// two consecutive matrix entries: the load as it comes from memory, and its conversion
+template <typename WT> struct W2;
+template <> struct W2<float> {
+    typedef float2 Raw;
+    __device__ static Raw load(const float *p) { return *reinterpret_cast<const float2 *>(p); }
+    __device__ static float2 cvt(Raw r) { return r; }
+};
+template <> struct W2<uint16_t> {
+    typedef uint32_t Raw;
+    __device__ static Raw load(const uint16_t *p) { return *reinterpret_cast<const uint32_t *>(p); }
+    __device__ static float2 cvt(Raw u) { return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u)); }
+};
+
+// hardware exponential and reciprocal: about 1e-7 absolute error on a value in (0, 1)
+__device__ inline float fast_sigmoid(float x) { return __frcp_rn(1.0f + __expf(-x)); }
+
+// ---- coherent exchange primitives (see the header comment)
+#define TDT_AGENT __HIP_MEMORY_SCOPE_AGENT
+__device__ inline float ld_co(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, TDT_AGENT); }
+__device__ inline void st_co(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, TDT_AGENT); }
+__device__ inline float2 ld_co2(const float *p)   // p 8-byte aligned
+{
+    const unsigned long long u =
+        __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, TDT_AGENT);
+    return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
+}
+__device__ inline unsigned long long ld_co64(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, TDT_AGENT);
+}
+__device__ inline void st_co64(unsigned long long *p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, TDT_AGENT);
+}
+
+// (logit, index) packed so that an unsigned 64-bit maximum is "largest logit,
+// lowest index on ties"; zero is below every packed value
+__device__ inline unsigned long long pack_best(float v, int idx)
+{
+    unsigned u = __float_as_uint(v + 0.0f);   // -0 and +0 compare equal: make them one pattern
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((unsigned long long)u << 32) | (unsigned long long)(0xffffffffu - (unsigned)idx);
+}
+__device__ inline int unpack_index(unsigned long long p) { return (int)(0xffffffffu - (unsigned)p); }
+__device__ inline float unpack_value(unsigned long long p)
+{
+    unsigned u = (unsigned)(p >> 32);
+    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+    return __uint_as_float(u);
+}
+
+// Barrier over the C workgroups of one cluster, in two halves.  Every workgroup owns one
+// flag word, a cache line apart from the next.  To arrive it stores the barrier's sequence
+// number there, after all its earlier coherent stores have completed.  To wait, its first
+// wavefront polls the flags of all C members (lane l reads member l, l + 64, ...) until they
+// have reached that number, while the other wavefronts rest at the workgroup barrier: little
+// polling traffic, no read-modify-write and no tree.  Work that does not depend on what the
+// other workgroups wrote (setting up the next work item, fetching weights) goes between the
+// two halves and hides the flags' way through memory.  Every wait is bounded: on a timeout,
+// or when another workgroup has flagged an abort, the wait returns false and the caller
+// leaves the kernel.
+struct BarrierInfo {
+    unsigned *flags;   // the cluster's flags; this workgroup's is flags[rank * kBarrierStride]
+    int rank;
+    unsigned epoch;    // barriers arrived at so far (the same in every thread of the cluster)
+};
+
+__device__ inline void barrier_arrive(BarrierInfo &bi, int C)
+{
+    // every coherent store / atomic of this wavefront has completed ...
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();   // ... and so have those of the whole workgroup
+    const unsigned epoch = ++bi.epoch;
+    if (C > 1 && threadIdx.x == 0)
+        __hip_atomic_store(bi.flags + (size_t)bi.rank * kBarrierStride, epoch, __ATOMIC_RELAXED, TDT_AGENT);
+}
+
+// ends with a workgroup barrier
+__device__ inline bool barrier_wait(HypShared &S, const BarrierInfo &bi, int *abort_flag, int C,
+                                    long long timeout_ticks)
+{
+    const unsigned epoch = bi.epoch;
+    if (C > 1 && threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        const long long t0 = wall_clock64();
+        unsigned spins = 0;
+        for (;;) {
+            bool all = true;
+            for (int base = 0; base < C; base += 64) {   // uniform
+                const int idx = base + lane;
+                const unsigned f = __hip_atomic_load(bi.flags + (size_t)(idx < C ? idx : 0) * kBarrierStride,
+                                                     __ATOMIC_RELAXED, TDT_AGENT);
+                all = all && (idx >= C || (int)(f - epoch) >= 0);
+            }
+            if (__ballot(!all) == 0ull) break;
+            if ((++spins & 31u) == 0u) {
+                int stop = 0;
+                if (lane == 0) {
+                    if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, TDT_AGENT)) {
+                        stop = 1;
+                    } else if (wall_clock64() - t0 > timeout_ticks) {
+                        __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, TDT_AGENT);
+                        stop = 1;
+                    }
+                }
+                if (__shfl(stop, 0, 64)) {
+                    if (lane == 0) S.aborted = 1;
+                    break;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    return S.aborted == 0;
+}
+
+__device__ inline bool cluster_barrier(HypShared &S, BarrierInfo &bi, int *abort_flag, int C,
+                                       long long timeout_ticks)
+{
+    barrier_arrive(bi, C);
+    return barrier_wait(S, bi, abort_flag, C, timeout_ticks);
+}
+
+// list[0..n) = indices g < G with flag[g] set, ascending.  All threads call it.
+__device__ inline void build_list(HypShared &S, const unsigned char *flag, int G, int *list,
+                                  int *n_out)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool f = tid < G && flag[tid] != 0;
+    const unsigned long long m = __ballot(f);
+    if (lane == 0) S.wave_cnt[wave] = __popcll(m);
+    __syncthreads();
+    int off = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const int c = S.wave_cnt[w];
+        if (w < wave) off += c;
+        total += c;
+    }
+    if (f) list[off + __popcll(m & ((1ull << lane) - 1ull))] = tid;
+    if (tid == 0) *n_out = total;
+    __syncthreads();
+}
+
+// deal `n_units` column tiles to the workgroups left after `n_row_tiles` took theirs
+__device__ inline void split_tiles(int C, int n_row_tiles, int n_units, int max_groups, int &n_groups,
+                                   int &per_group)
+{
+    int g = C / (n_row_tiles > 0 ? n_row_tiles : 1);
+    if (g < 1) g = 1;
+    if (g > max_groups) g = max_groups;
+    if (g > n_units) g = n_units;
+    per_group = (n_units + g - 1) / g;
+    n_groups = (n_units + per_group - 1) / per_group;
+}
+
+}  // namespace
+}  // namespace tdt
+
+#endif

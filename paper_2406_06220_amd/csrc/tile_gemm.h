@@ -1,0 +1,350 @@
+// The small-M GEMM every heavy phase of the decode kernel is made of: 16 activation rows staged
+// in LDS (split exactly into three bfloat16 planes for the matrix cores) against 16-column
+// tiles of a weight matrix; run_item drives one work item through staging, products and
+// epilogue.  Included by decode.hip only.
+#ifndef TDT_TILE_GEMM_H
+#define TDT_TILE_GEMM_H
+
+#include "tdt_internal.h"
+#include "decode_state.h"
+#include "exchange.h"
+
+namespace tdt {
+namespace {
+
+// ---------------------------------------------------------------------------
+// Activation tile in LDS and the two tile-GEMM back ends
+// ---------------------------------------------------------------------------
+// bfloat16 weights: three bfloat16 planes [3][RT][ldb] with hi + lo + lo2 == x.
+// float32 weights:  one float plane [RT][ldb].
+template <typename WT> struct ActTile;
+
+template <> struct ActTile<uint16_t> {
+    uint16_t *planes;
+    int ldb;   // elements per row (multiple of 8, padded)
+    __host__ __device__ static int row_elems(int kseg_max) { return ((kseg_max + 31) / 32) * 32 + 8; }
+    // x == hi + lo + lo2 exactly, each term a bfloat16: hi and lo are x and the first
+    // remainder truncated to their top 16 bits (a truncated term keeps the sign, so each
+    // remainder is exact and shorter by at least 8 significant bits); the second
+    // remainder has at most 8 significant bits left and is a bfloat16 as it stands
+    __device__ static void split3(float x, unsigned &hi, unsigned &lo, unsigned &lo2)
+    {
+        hi = __float_as_uint(x) & 0xffff0000u;
+        const float r1 = x - __uint_as_float(hi);
+        lo = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(lo);
+        lo2 = __float_as_uint(r2);
+    }
+    __device__ void store2(int i, int k, float2 v) const
+    {
+        unsigned a[3], b[3];
+        split3(v.x, a[0], a[1], a[2]);
+        split3(v.y, b[0], b[1], b[2]);
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)   // element k in the low half, k + 1 in the high half
+            *reinterpret_cast<unsigned *>(planes + ((size_t)pl * RT + i) * ldb + k) =
+                (a[pl] >> 16) | (b[pl] & 0xffff0000u);
+    }
+};
+
+template <> struct ActTile<float> {
+    float *planes;
+    int ldb;
+    __host__ __device__ static int row_elems(int kseg_max) { return ((kseg_max + 31) / 32) * 32; }
+    __device__ void store2(int i, int k, float2 v) const
+    {
+        *reinterpret_cast<float2 *>(planes + (size_t)i * ldb + k) = v;
+    }
+};
+
+// stage one K segment: with c = ctx(i) computed once per row, mix(c, k, load(c, k)) gives the
+// two inputs (k, k+1) of row i; the tail up to a multiple of 32 is zero-filled.  load only
+// loads and mix only computes: all loads of a wavefront are issued before the first loaded
+// value is used, so that their latencies overlap (a use between two loads makes the
+// compiler wait for the first load before it issues the second, and so does a load inside
+// a conditional block).  For the same reason load is called for every slot -- rows beyond
+// nrows re-read row 0, steps beyond K re-read the last step -- and what it returned there
+// is dropped afterwards.
+template <typename WT, int KIT, typename CtxF, typename LoadF, typename MixF>
+__device__ inline void stage_segment_impl(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int Kpad = ((K + 31) / 32) * 32;
+    constexpr int RPW = RT / kWaves;    // rows per wavefront
+    decltype(ctx(0)) c[RPW];
+#pragma unroll
+    for (int ii = 0; ii < RPW; ++ii) {
+        const int i = wave + ii * kWaves;
+        c[ii] = ctx(i < nrows ? i : 0);
+    }
+    decltype(load(c[0], 0)) v[RPW][KIT];
+#pragma unroll
+    for (int ii = 0; ii < RPW; ++ii)
+#pragma unroll
+        for (int kk = 0; kk < KIT; ++kk) {
+            const int k = lane * 2 + kk * 128;
+            v[ii][kk] = load(c[ii], k < K ? k : K - 2);
+        }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ii = 0; ii < RPW; ++ii)
+#pragma unroll
+        for (int kk = 0; kk < KIT; ++kk) {
+            const int i = wave + ii * kWaves, k = lane * 2 + kk * 128;
+            const bool ok = i < nrows && k < K;
+            const float2 x = mix(c[ii], k < K ? k : K - 2, v[ii][kk]);
+            if (k < Kpad) A.store2(i, k, make_float2(ok ? x.x : 0.0f, ok ? x.y : 0.0f));
+        }
+}
+
+template <typename WT, typename CtxF, typename LoadF, typename MixF>
+__device__ inline void stage_segment(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
+{
+    // 64 lanes x 2 inputs per step: pick the unrolling that covers K without spare loads
+    if (K <= 640) stage_segment_impl<WT, 5>(A, K, nrows, ctx, load, mix);
+    else stage_segment_impl<WT, KSEG / 128>(A, K, nrows, ctx, load, mix);
+}
+
+// accumulators of one wavefront for one 16x16 tile
+template <typename WT> struct Accum;
+template <> struct Accum<uint16_t> {
+    f32x4 c;   // lane l: column l % 16, rows (l / 16) * 4 + e
+    __device__ void clear() { c = f32x4{0.0f, 0.0f, 0.0f, 0.0f}; }
+};
+template <> struct Accum<float> {
+    float c[CT];   // lane l < 16: row l, column j
+    __device__ void clear()
+    {
+#pragma unroll
+        for (int j = 0; j < CT; ++j) c[j] = 0.0f;
+    }
+};
+
+// matrix-core back end: this wavefront adds its share (k-steps kpart, kpart + ksplit, ...)
+// of one segment to the 16x16 tile whose 16 weight rows are given per lane (l % 16).
+// The first chunk of weight fragments can be fetched ahead (before the activations are
+// staged) with weight_prefetch.
+constexpr int CH = 5;   // weight fragments in flight per wavefront
+
+struct WeightCursor {
+    const uint16_t *wr;   // this lane's weight row at its k-quarter (row 0 if the column is padding)
+    bool live;            // false: the column is padding and its fragments are zero
+    int kq, n_my;
+};
+
+__device__ inline WeightCursor weight_cursor(const Seg &sg, long long wrow, int kpart, int ksplit, int lane)
+{
+    WeightCursor wc;
+    wc.kq = (lane >> 4) * 8;
+    wc.live = wrow >= 0;
+    wc.wr = static_cast<const uint16_t *>(sg.w) + (wc.live ? wrow : 0) * sg.wld + sg.k0;
+    const int nsteps = (sg.K + 31) / 32;
+    // ksplit is a power of two
+    wc.n_my = nsteps > kpart ? (nsteps - kpart + ksplit - 1) >> __builtin_ctz(ksplit) : 0;
+    return wc;
+}
+
+// Loads are unconditional (address clamped into the row) and nothing uses a fragment before
+// all CH loads have been issued; what a clamped load fetched is masked where it is used.
+__device__ inline void weight_prefetch(const WeightCursor &wc, const Seg &sg, int kpart, int ksplit, int c0,
+                                       uint4 (&b)[CH])
+{
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int k = (kpart + (c0 + j) * ksplit) * 32 + wc.kq;
+        b[j] = *reinterpret_cast<const uint4 *>(wc.wr + (k < sg.K ? k : sg.K - 8));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ inline void tile_accumulate(const ActTile<uint16_t> &A, const Seg &sg, const WeightCursor &wc,
+                                       int kpart, int ksplit, uint4 (&b)[CH], bool have_first, f32x4 &acc,
+                                       int lane)
+{
+    const uint16_t *a0 = A.planes + (size_t)(lane & 15) * A.ldb + wc.kq;
+    const size_t plane = (size_t)RT * A.ldb;
+    for (int c0 = 0; c0 < wc.n_my; c0 += CH) {
+        if (c0 > 0 || !have_first) weight_prefetch(wc, sg, kpart, ksplit, c0, b);
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            if (c0 + j < wc.n_my) {
+                const int s = kpart + (c0 + j) * ksplit;
+                const bool ok = wc.live && s * 32 + wc.kq < sg.K;
+                const uint4 m = make_uint4(ok ? b[j].x : 0u, ok ? b[j].y : 0u, ok ? b[j].z : 0u, ok ? b[j].w : 0u);
+                const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&m);
+                const bf16x8 x0 = *reinterpret_cast<const bf16x8 *>(a0 + s * 32);
+                const bf16x8 x1 = *reinterpret_cast<const bf16x8 *>(a0 + plane + s * 32);
+                const bf16x8 x2 = *reinterpret_cast<const bf16x8 *>(a0 + 2 * plane + s * 32);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, bv, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, bv, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x2, bv, acc, 0, 0, 0);
+            }
+        }
+    }
+}
+
+// vector-ALU back end: the wavefront's 64 lanes split K, all 16 rows at once, one column
+__device__ inline float column_dot(const ActTile<float> &A, const Seg &sg, long long wrow, int lane)
+{
+    float acc[RT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i) acc[i] = 0.0f;
+    if (wrow >= 0) {
+        const float *w = static_cast<const float *>(sg.w) + wrow * sg.wld + sg.k0;
+        for (int k = lane * 2; k < sg.K; k += 128) {
+            const float2 wv = *reinterpret_cast<const float2 *>(w + k);
+#pragma unroll
+            for (int i = 0; i < RT; ++i) {
+                const float2 a = *reinterpret_cast<const float2 *>(A.planes + (size_t)i * A.ldb + k);
+                acc[i] = fmaf(a.x, wv.x, acc[i]);
+                acc[i] = fmaf(a.y, wv.y, acc[i]);
+            }
+        }
+    }
+    float mine = 0.0f;
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+        float v = acc[i];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        if (lane == i) mine = v;
+    }
+    return mine;   // lane i < 16: row i
+}
+
+template <typename WT> struct Backend;
+template <> struct Backend<uint16_t> {
+    struct Pre {   // weight fragments fetched while the activations are being staged
+        WeightCursor wc;
+        uint4 b[CH];
+    };
+    template <typename RowF>
+    __device__ static void prefetch(Pre &pre, const Seg &sg, RowF rowidx, int ct, int kpart, int ksplit, int lane)
+    {
+        pre.wc = weight_cursor(sg, rowidx(ct, lane & 15), kpart, ksplit, lane);
+        weight_prefetch(pre.wc, sg, kpart, ksplit, 0, pre.b);
+    }
+    template <typename RowF>
+    __device__ static void accumulate(const ActTile<uint16_t> &A, const Seg &sg, RowF, int, int kpart, int ksplit,
+                                      Accum<uint16_t> &acc, int lane, Pre &pre)
+    {
+        tile_accumulate(A, sg, pre.wc, kpart, ksplit, pre.b, true, acc.c, lane);
+    }
+    __device__ static void spill(HypShared &S, const Accum<uint16_t> &acc, int wave, int lane)
+    {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) S.cpart[wave][(lane >> 4) * 4 + e][lane & 15] = acc.c[e];
+    }
+    __device__ static int ksplit_for(int n_ct) { return n_ct <= 1 ? 8 : n_ct <= 2 ? 4 : n_ct <= 4 ? 2 : 1; }
+};
+template <> struct Backend<float> {
+    struct Pre {};
+    template <typename RowF>
+    __device__ static void prefetch(Pre &, const Seg &, RowF, int, int, int, int) {}
+    template <typename RowF>
+    __device__ static void accumulate(const ActTile<float> &A, const Seg &sg, RowF rowidx, int ct, int, int,
+                                      Accum<float> &acc, int lane, Pre &)
+    {
+        for (int j = 0; j < CT; ++j) {
+            const float v = column_dot(A, sg, rowidx(ct, j), lane);
+#pragma unroll
+            for (int jj = 0; jj < CT; ++jj)
+                if (jj == j) acc.c[jj] += v;
+        }
+    }
+    __device__ static void spill(HypShared &S, const Accum<float> &acc, int wave, int lane)
+    {
+        if (lane < RT) {
+#pragma unroll
+            for (int j = 0; j < CT; ++j) S.cpart[wave][lane][j] = acc.c[j];
+        }
+    }
+    __device__ static int ksplit_for(int) { return 1; }
+};
+
+// One work item: all K segments of the staged rows against n_ct column tiles, a round of
+// (8 / ksplit) column tiles at a time.
+//   stage(seg)                     stages Seg seg of the item's rows (stage_segment)
+//   rowidx(ct, j)    -> long long  weight row of column j of column tile ct, -1 if none
+//   pre(ct0, n)                    called by all threads at the start of a round, before the
+//                                  rows are staged: issues loads whose latency should hide there
+//   park(ct0, n)                   called by all threads after the round's products, before the
+//                                  barrier that precedes epi: may put what pre loaded into LDS
+//   wait()                         called by all threads once, before the first rows are staged
+//                                  (after the first weights have been requested); must contain
+//                                  a workgroup barrier
+//   epi(ct0, n, ksplit)            called by all threads once S.cpart holds round results:
+//                                  tile slot t (< n) is the sum over kp < ksplit of
+//                                  S.cpart[t * ksplit + kp]; S.bias[t * 16 + j] is
+//                                  bias[rowidx(ct0 + t, j)]
+// With one segment the rows are staged once; with several they are staged again for
+// every round.
+template <typename WT, typename StageF, typename RowF, typename PreF, typename ParkF, typename EpiF, typename WaitF>
+__device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseInputs &in, int n_ct,
+                                const float *__restrict__ bias, const float *any_floats, StageF stage,
+                                RowF rowidx, PreF pre_round, ParkF park, EpiF epi, WaitF wait)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nseg = in.count();
+    // always a readable float array with at least as many entries as there are weight rows
+    const float *bias_or_any = bias ? bias : static_cast<const float *>(any_floats);
+    const int ksplit = Backend<WT>::ksplit_for(n_ct);
+    const int ksh = __builtin_ctz(ksplit);    // ksplit is 1, 2, 4 or 8
+    const int tpr = kWaves >> ksh;            // column tiles per round
+    const int tslot = wave >> ksh, kpart = wave & (ksplit - 1);
+    for (int base = 0; base < n_ct; base += tpr) {
+        const int ct = base + tslot;
+        const bool mine = ct < n_ct;
+        Accum<WT> acc;
+        acc.clear();
+        // bias of column (threadIdx.x % 16) of tile slot (threadIdx.x / 16): the load is issued
+        // here, unconditionally, and parked in LDS only after the rows have been staged
+        float bias_v;
+        {
+            const int bt = (int)(threadIdx.x % (kWaves * CT)) / CT, bj = (int)threadIdx.x % CT;
+            const long long r = base + bt < n_ct ? rowidx(base + bt, bj) : -1;
+            bias_v = bias_or_any[r >= 0 ? r : 0];
+            if (r < 0 || !bias) bias_v = 0.0f;
+        }
+        pre_round(base, min(tpr, n_ct - base));
+        for (int sgi = 0; sgi < nseg; ++sgi) {
+            const Seg sg = in.get(sgi);
+            long long tq = 0;
+            if (TDT_FINE_TIMERS && threadIdx.x == 0) tq = wall_clock64();
+            typename Backend<WT>::Pre pre;
+            // the weights do not depend on the activations: fetch the first of them now
+            if (mine) Backend<WT>::prefetch(pre, sg, rowidx, ct, kpart, ksplit, lane);
+            if (nseg > 1 || base == 0) {
+                // previous readers of the tile are done
+                if (base == 0 && sgi == 0) wait();
+                else __syncthreads();
+                stage(sg);
+                __syncthreads();
+            }
+            if (TDT_FINE_TIMERS && threadIdx.x == 0) { const long long n = wall_clock64(); S.tk_fine[S.fine_phase][0] += n - tq; tq = n; }
+            if (mine) Backend<WT>::accumulate(A, sg, rowidx, ct, kpart, ksplit, acc, lane, pre);
+            if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_fine[S.fine_phase][1] += wall_clock64() - tq;
+        }
+        long long tq = 0;
+        if (TDT_FINE_TIMERS && threadIdx.x == 0) tq = wall_clock64();
+        if (mine) Backend<WT>::spill(S, acc, wave, lane);
+        if (threadIdx.x < kWaves * CT) S.bias[threadIdx.x] = bias_v;
+        park(base, min(tpr, n_ct - base));
+        __syncthreads();
+        epi(base, min(tpr, n_ct - base), ksplit);
+        __syncthreads();
+        if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_fine[S.fine_phase][2] += wall_clock64() - tq;
+    }
+}
+
+__device__ inline float cpart_sum(const HypShared &S, int t, int ksplit, int i, int j)
+{
+    float v = S.cpart[t * ksplit][i][j];
+    for (int kp = 1; kp < ksplit; ++kp) v += S.cpart[t * ksplit + kp][i][j];
+    return v;
+}
+
+}  // namespace
+}  // namespace tdt
+
+#endif
