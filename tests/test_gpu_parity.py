@@ -141,6 +141,29 @@ def test_small_models(oracle_lib, gpu, cfg, window, n_clusters):
     check(oracle_lib, gpu, cfg, window=window, n_clusters=n_clusters)
 
 
+@pytest.mark.parametrize("B,n_clusters,kind", [
+    (1500, 0, "lstm_fp32"),      # more than the batch size up to which hypotheses are dealt by length
+    (2100, 0, "stateless_fp32"), # needs nine groups: a group count that does not divide the dies evenly
+    (700, 3, "lstm_fp32"),       # 234 hypotheses a group: many row tiles per pass, windows cut to fit
+    (300, 2, "tdt_bf16"),        # the same on the matrix cores, with durations
+    (256, 1, "tdt_bf16"),        # the most hypotheses one group can hold
+])
+def test_many_hypotheses(oracle_lib, gpu, B, n_clusters, kind):
+    base = dict(B=B, T=14, len_lo=0, len_hi=14, seed=70 + B % 7, max_symbols=3)
+    if kind == "lstm_fp32":
+        cfg = synth.small_config("g_many_lstm", pred_kind="lstm", d_enc=16, h_pred=16, emb_dim=8,
+                                 h_joint=24, vocab=19, default_blank_bias=0.8, **base)
+    elif kind == "stateless_fp32":
+        cfg = synth.small_config("g_many_stateless", d_enc=16, h_pred=16, emb_dim=8, pred_layers=2,
+                                 h_joint=24, vocab=19, default_blank_bias=0.8, **base)
+    else:
+        cfg = synth.small_config("g_many_tdt_bf16", dtype="bf16", pred_kind="lstm", durations=(0, 1, 2, 3),
+                                 d_enc=32, h_pred=40, emb_dim=16, h_joint=56, vocab=37,
+                                 default_blank_bias=0.5, **base)
+    out, res = check(oracle_lib, gpu, cfg, n_clusters=n_clusters, max_replayed_frac=0.02)
+    assert res["rows"] == B
+
+
 def test_config1_tiny_rnnt(oracle_lib, gpu):
     out, res = check(oracle_lib, gpu, synth.CFG1)
     assert res["exact"] == synth.CFG1.B
