@@ -164,6 +164,20 @@ def test_many_hypotheses(oracle_lib, gpu, B, n_clusters, kind):
     assert res["rows"] == B
 
 
+def test_largest_dimensions(oracle_lib, gpu):
+    """Every width at the library's limit (2048; an LSTM input plus state 2048), sixteen
+    duration classes, two LSTM layers: two staged stretches in every product."""
+    cfg = synth.small_config("g_max_dims", dtype="bf16", pred_kind="lstm", pred_layers=2,
+                             durations=tuple(range(16)), d_enc=2048, h_pred=1024, emb_dim=1024,
+                             h_joint=2048, vocab=21, B=5, T=12, len_lo=3, len_hi=12, seed=61,
+                             default_blank_bias=0.5, max_symbols=2)
+    check(oracle_lib, gpu, cfg)
+    cfg = synth.small_config("g_max_dims_stateless", dtype="bf16", pred_layers=2, d_enc=2048,
+                             h_pred=2048, emb_dim=1024, h_joint=2048, vocab=21, B=4, T=12,
+                             len_lo=3, len_hi=12, seed=62, default_blank_bias=0.5, max_symbols=2)
+    check(oracle_lib, gpu, cfg)
+
+
 def test_config1_tiny_rnnt(oracle_lib, gpu):
     out, res = check(oracle_lib, gpu, synth.CFG1)
     assert res["exact"] == synth.CFG1.B
