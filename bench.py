@@ -45,7 +45,7 @@ def algorithmic_bytes(cfg, stats) -> float:
             + stats["joint_rows"] * H * 4 + stats["pred_rows"] * Hp * 4)
 
 
-def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0):
+def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0, algorithm=0):
     import torch
     from paper_2406_06220_amd import binding, synth
     dev = "cuda:0"
@@ -54,7 +54,7 @@ def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0):
     u_cap = cfg.T * cfg.max_symbols
     model = binding.DeviceModel(cfg, w, dev)
     dec = binding.Decoder(model, cfg.B, cfg.T, u_cap, window=window, n_clusters=n_clusters,
-                          joint_tiles=joint_tiles)
+                          joint_tiles=joint_tiles, algorithm=algorithm)
     enc_d = model.upload_enc(enc)
     len_d = torch.from_numpy(ln).to(dev)
     stream = torch.cuda.current_stream(dev)
@@ -279,6 +279,18 @@ def main():
         # the same batch fed piece by piece (50 frames = 2 s of audio at config 2's frame rate)
         line["chunked"] = time_chunked(cfg, 50, max(args.steps // 2, 3), max(args.warmup, 1))
         line["chunked"]["labels_match_whole"] = bool(line["chunked"]["labels"] == int(res["out"]["len"].sum()))
+        # the conventional loop order (Algorithm 2) on the same kernels: one lock step as
+        # printed, and with the batch split into independent groups like the default path
+        fl = {}
+        for key, ncl in (("as_printed", 1), ("independent_groups", 0)):
+            rf = time_workload(cfg, max(args.steps // 4, 2), 1, n_clusters=ncl, algorithm=1)
+            same = bool((rf["out"]["len"] == res["out"]["len"]).all()
+                        and (rf["out"]["labels"] == res["out"]["labels"]).all())
+            fl[key] = {"ms_per_batch": rf["sec_per_step"] * 1e3, "value": rf["frames"] / rf["sec_per_step"],
+                       "unit": "frames/s", "steps_of_the_slowest_group": rf["out"]["stats"]["outer_max"],
+                       "label_looping_speedup": rf["sec_per_step"] / res["sec_per_step"],
+                       "labels_match_label_looping": same}
+        line["frame_looping"] = fl
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(res)
     print(json.dumps(line))

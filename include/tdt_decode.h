@@ -118,13 +118,23 @@ typedef struct {
  *               workgroup at most one work item of this many 16-column tiles of the
  *               output layer.  0 = automatic (4, more for many hypotheses per group).
  *               Ignored when window > 0.
+ *   algorithm   TDT_ALG_LABEL_LOOPING (0, default): Algorithm 3.  TDT_ALG_FRAME_LOOPING:
+ *               the conventional batched order the paper compares against (Algorithm 2)
+ *               on the same kernels -- every step runs the predictor for every active
+ *               hypothesis, scores one frame each, and keeps the new predictor state only
+ *               where the step emitted a label.  Same hypotheses as label-looping; kept
+ *               to measure what the re-ordering of the loops is worth.  `window` and
+ *               `joint_tiles` are ignored; not available for tdt_greedy_decode_chunk.
  */
+enum tdt_algorithm { TDT_ALG_LABEL_LOOPING = 0, TDT_ALG_FRAME_LOOPING = 1 };
+
 typedef struct {
     int32_t window;
     int32_t n_clusters;
     int32_t reuse_enc_proj;
     int32_t joint_tiles;
-    int32_t reserved[4]; /* must be zero */
+    int32_t algorithm;   /* enum tdt_algorithm */
+    int32_t reserved[3]; /* must be zero */
 } tdt_options_t;
 
 /* counters written to out_stats (int64 each); sums over all hypothesis groups */

@@ -26,6 +26,8 @@ TDT_STAT_NAMES = {"pred_passes": 0, "pred_rows": 1, "joint_passes": 2, "joint_ro
                      for a, ph in enumerate(("pred", "proj", "joint"))
                      for b, part in enumerate(("stage", "mma", "epilogue"))}}
 TDT_STAT_COUNT = 24
+TDT_ALG_LABEL_LOOPING = 0
+TDT_ALG_FRAME_LOOPING = 1
 TDT_HYP_TRUNCATED = 1
 TDT_HYP_LEN_CLAMPED = 2
 
@@ -47,7 +49,7 @@ class tdt_weights_t(C.Structure):
 
 class tdt_options_t(C.Structure):
     _fields_ = [("window", C.c_int32), ("n_clusters", C.c_int32), ("reuse_enc_proj", C.c_int32),
-                ("joint_tiles", C.c_int32), ("reserved", C.c_int32 * 4)]
+                ("joint_tiles", C.c_int32), ("algorithm", C.c_int32), ("reserved", C.c_int32 * 3)]
 
 
 _lib = None
@@ -196,7 +198,7 @@ class Decoder:
     """Owns the output tensors and the workspace for one (model, B, T, u_cap)."""
 
     def __init__(self, model: DeviceModel, B: int, T: int, u_cap: int,
-                 window: int = 0, n_clusters: int = 0, joint_tiles: int = 0):
+                 window: int = 0, n_clusters: int = 0, joint_tiles: int = 0, algorithm: int = 0):
         import torch
         self.model, self.B, self.T, self.u_cap = model, B, T, u_cap
         dev = model.device
@@ -213,6 +215,7 @@ class Decoder:
         self.options.window = window
         self.options.n_clusters = n_clusters
         self.options.joint_tiles = joint_tiles
+        self.options.algorithm = algorithm
 
     def __call__(self, enc_dev, enc_len_dev, max_symbols: Optional[int] = None, stream=None):
         import torch

@@ -62,7 +62,11 @@ namespace {
 
 // CHUNKED: the call decodes the next chunk of longer utterances (tdt_greedy_decode_chunk);
 // compiled apart so that whole-utterance decoding carries none of its bookkeeping.
-template <typename WT, bool CHUNKED>
+// FRAMELOOP: the conventional order of the loops the paper compares against (Algorithm 2,
+// batched frame-looping), on the same phases: every step runs the predictor for every active
+// hypothesis, scores one frame each, and keeps the new predictor state only where the step
+// emitted a label.  Same hypotheses; there to measure what the re-ordering is worth.
+template <typename WT, bool CHUNKED, bool FRAMELOOP>
 __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_lds[];
@@ -177,6 +181,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         S.started[g] = started || active;
         S.took_part[g] = active;
         S.hpar[g] = 1;
+        S.commit[g] = 1;   // the start-of-sequence step is kept
     }
     if (tid < TDT_MAX_DURATIONS) S.durations[tid] = p.durations[tid];
     if (tid == 0) {
@@ -329,8 +334,14 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     const float gg = 2.0f * fast_sigmoid(2.0f * (r23.x + t4.z)) - 1.0f;
                     const float og = fast_sigmoid(r23.y + t4.w);
                     const float cn = fg * c_old + ig * gg;
-                    st_co(cst + o, cn);
-                    st_co(h_next + o, og * (2.0f * fast_sigmoid(2.0f * cn) - 1.0f));
+                    if (FRAMELOOP && !S.commit[g]) {
+                        // Alg. 2: the step was computed, but the last decision was a blank, so
+                        // the old state stays (it moves to the other half of the buffer)
+                        st_co(h_next + o, ld_co(p.hbuf + (size_t)pp * L * Bw * Hp + o));
+                    } else {
+                        st_co(cst + o, cn);
+                        st_co(h_next + o, og * (2.0f * fast_sigmoid(2.0f * cn) - 1.0f));
+                    }
                 }
                 if (bar_pending) finish_barrier();
                 if (!ok) break;
@@ -403,8 +414,12 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                         const float cn = fg * c_old[e] + act * gg;
                                         const int g = plist[ti * RT + i];
                                         const size_t o = (size_t)(b0 + g) * Hp + unit;
-                                        st_co(cst + o, cn);
-                                        st_co(h_next + o, og * (2.0f * fast_sigmoid(2.0f * cn) - 1.0f));
+                                        if (FRAMELOOP && !S.commit[g]) {
+                                            st_co(h_next + o, ld_co(h_cur + o));
+                                        } else {
+                                            st_co(cst + o, cn);
+                                            st_co(h_next + o, og * (2.0f * fast_sigmoid(2.0f * cn) - 1.0f));
+                                        }
                                     }
                                 }
                             }
@@ -509,12 +524,25 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 2;
         phase_bucket = kTkJ;
+        if (FRAMELOOP) {
+            // Alg. 2 is frame-synchronous: the batch looks at one frame index at a time, and a
+            // hypothesis that has already moved past it waits for the others
+            if (tid == 0) S.t_sync = 0x7fffffff;
+            __syncthreads();
+            for (int g = tid; g < G; g += kThreads)
+                if (S.active[g]) atomicMin(&S.t_sync, S.time[g]);
+            __syncthreads();
+        }
         // every active hypothesis now searches for its next non-blank label
         for (int g = tid; g < G; g += kThreads) {
             bool a = S.active[g];
             if (a && chunked && (S.time[g] >= S.len[g] || (S.status[g] & TDT_HYP_TRUNCATED))) {
                 a = false;   // had only stayed for the predictor step of its last label
                 S.active[g] = 0;
+            }
+            if (FRAMELOOP) {
+                a = a && S.time[g] == S.t_sync;
+                S.commit[g] = 0;   // this step's predictor pass has used it; a new label sets it again
             }
             S.need[g] = a;
         }
@@ -525,7 +553,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         while (S.n_need > 0) {
             const int n_need = S.n_need;
             const int NT = (O + CT - 1) / CT;
-            int Kw = p.window;
+            int Kw = FRAMELOOP ? 1 : p.window;   // Alg. 2 looks at one frame per step
             if (Kw <= 0) {
                 Kw = auto_rows / n_need;
                 if (Kw < 3) Kw = 3;
@@ -748,7 +776,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     // last label, so that the state it carries on has seen it.
                     S.active[g] = act_now || chunked;
                     S.need[g] = 0;
+                    if (FRAMELOOP) S.commit[g] = 1;
                 } else {
+                    if (FRAMELOOP) S.commit[g] = 0;
                     const int t1 = t0 + w;
                     S.time[g] = t1;
                     S.active[g] = t1 < len;
@@ -817,6 +847,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             __syncthreads();
             build_list(S, S.need, G, S.need_list, &S.n_need);
             lap(kTkD);
+            if (FRAMELOOP) break;   // Alg. 2: the next step starts with the predictor again
         }
         if (!ok) break;
         pp ^= 1;
@@ -922,17 +953,21 @@ hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats
     return hipGetLastError();
 }
 
-static const void *kernel_for(const tdt_weights_t *w, bool chunked)
+static const void *kernel_for(const tdt_weights_t *w, bool chunked, bool frame_loop)
 {
+    if (frame_loop)
+        return w->dtype == 1 ? (const void *)decode_kernel<uint16_t, false, true>
+                             : (const void *)decode_kernel<float, false, true>;
     if (w->dtype == 1)
-        return chunked ? (const void *)decode_kernel<uint16_t, true> : (const void *)decode_kernel<uint16_t, false>;
-    return chunked ? (const void *)decode_kernel<float, true> : (const void *)decode_kernel<float, false>;
+        return chunked ? (const void *)decode_kernel<uint16_t, true, false>
+                       : (const void *)decode_kernel<uint16_t, false, false>;
+    return chunked ? (const void *)decode_kernel<float, true, false> : (const void *)decode_kernel<float, false, false>;
 }
 
-int decode_max_grid(const tdt_weights_t *w, bool chunked)
+int decode_max_grid(const tdt_weights_t *w, bool chunked, bool frame_loop)
 {
     const size_t lds = lds_bytes_for(w);
-    const void *fn = kernel_for(w, chunked);
+    const void *fn = kernel_for(w, chunked, frame_loop);
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return 0;
@@ -956,7 +991,7 @@ hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid
     DecodeParams pc = p;
     pc.kseg_max = kseg_max_for(w);
     void *args[] = {&pc};
-    const void *fn = kernel_for(w, p.st_started != nullptr);
+    const void *fn = kernel_for(w, p.st_started != nullptr, p.frame_loop != 0);
     // cooperative launch: the runtime refuses a grid whose workgroups cannot all be
     // resident at once, which is what the cluster barriers rely on
     return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(kThreads), args, (unsigned)lds, stream);

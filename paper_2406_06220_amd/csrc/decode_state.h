@@ -42,9 +42,11 @@ struct HypShared {
     unsigned char started[kMaxHypsPerCluster];   // the start-of-sequence predictor step is done (chunked decoding)
     unsigned char took_part[kMaxHypsPerCluster]; // was active in this call
     unsigned char hpar[kMaxHypsPerCluster];      // which half of hbuf holds the hypothesis's newest state
+    unsigned char commit[kMaxHypsPerCluster];    // frame-looping: the last step emitted a label, so its predictor state is kept
     int act_list[kMaxHypsPerCluster];
     int need_list[kMaxHypsPerCluster];
     int n_act, n_need;
+    int t_sync;                      // frame-looping: the frame index the batch is looking at
     int wave_cnt[kWaves];
     int durations[TDT_MAX_DURATIONS];
     float cpart[kWaves][RT][CP_LD];  // per-wavefront 16x16 partial results of one round

@@ -160,7 +160,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         any_pos |= durations[j] > 0;
     }
     if (!any_pos) return TDT_ERR_DURATIONS;
-    int window = 0, n_clusters = 0, joint_tiles = 0;
+    int window = 0, n_clusters = 0, joint_tiles = 0, algorithm = TDT_ALG_LABEL_LOOPING;
     bool reuse_enc_proj = false;
     if (options) {
         for (int r : options->reserved)
@@ -169,6 +169,9 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         n_clusters = options->n_clusters;
         reuse_enc_proj = options->reuse_enc_proj != 0;
         joint_tiles = options->joint_tiles;
+        algorithm = options->algorithm;
+        if (algorithm != TDT_ALG_LABEL_LOOPING && algorithm != TDT_ALG_FRAME_LOOPING) return TDT_ERR_UNSUPPORTED;
+        if (algorithm == TDT_ALG_FRAME_LOOPING && state) return TDT_ERR_UNSUPPORTED;
         if (window < 0 || window > kMaxWindow || n_clusters < 0 || joint_tiles < 0 || joint_tiles > 64)
             return TDT_ERR_UNSUPPORTED;
     }
@@ -176,7 +179,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < L.total)
         return TDT_ERR_WORKSPACE;
 
-    const int max_grid = decode_max_grid(weights, state != nullptr);
+    const int max_grid = decode_max_grid(weights, state != nullptr, algorithm == TDT_ALG_FRAME_LOOPING);
     if (max_grid < 1) return TDT_ERR_LAUNCH;
     const int min_clusters = (B + kMaxHypsPerCluster - 1) / kMaxHypsPerCluster;
     if (n_clusters == 0) {
@@ -226,6 +229,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     p.window = window;
     p.joint_tiles = joint_tiles;
     p.n_clusters = n_clusters;
+    p.frame_loop = algorithm == TDT_ALG_FRAME_LOOPING;
     p.hyps_per_cluster = (B + n_clusters - 1) / n_clusters;
     for (int j = 0; j < TDT_MAX_DURATIONS; ++j) p.durations[j] = j < weights->n_dur ? durations[j] : 0;
     p.emb = weights->emb;

@@ -38,6 +38,7 @@ struct DecodeParams {
     int joint_tiles;       // column tiles per joint work item the automatic window aims at (0 = 4)
     int kseg_max;          // longest K segment staged at once (set by launch_decode)
     int n_clusters, hyps_per_cluster;
+    int frame_loop;        // non-zero: batched frame-looping (Algorithm 2) instead of label-looping
     int durations[TDT_MAX_DURATIONS];
     // weights
     const void *emb;
@@ -98,6 +99,6 @@ hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats
                        hipStream_t stream);
 hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid, hipStream_t stream);
 // largest grid the decode kernel can run with all workgroups resident, 0 on error
-int decode_max_grid(const tdt_weights_t *w, bool chunked);
+int decode_max_grid(const tdt_weights_t *w, bool chunked, bool frame_loop);
 
 }  // namespace tdt

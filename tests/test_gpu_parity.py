@@ -24,14 +24,14 @@ def gpu():
 
 
 def run_gpu(binding, cfg, w, enc, ln, u_cap, window=0, n_clusters=0, joint_tiles=0, max_symbols=None,
-            repeat=1):
+            repeat=1, algorithm=0):
     import torch
     parity.announce(f"tdt_greedy_decode cfg={cfg.name} B={len(ln)} T={enc.shape[1]} u_cap={u_cap} "
                     f"window={window} n_clusters={n_clusters} joint_tiles={joint_tiles} "
-                    f"S={max_symbols or cfg.max_symbols}")
+                    f"S={max_symbols or cfg.max_symbols} algorithm={algorithm}")
     model = binding.DeviceModel(cfg, w)
     dec = binding.Decoder(model, len(ln), enc.shape[1], u_cap, window=window, n_clusters=n_clusters,
-                          joint_tiles=joint_tiles)
+                          joint_tiles=joint_tiles, algorithm=algorithm)
     enc_d = model.upload_enc(enc)
     len_d = torch.from_numpy(np.ascontiguousarray(ln, np.int32)).to(model.device)
     out = None
@@ -176,6 +176,42 @@ def test_largest_dimensions(oracle_lib, gpu):
                              h_pred=2048, emb_dim=1024, h_joint=2048, vocab=21, B=4, T=12,
                              len_lo=3, len_hi=12, seed=62, default_blank_bias=0.5, max_symbols=2)
     check(oracle_lib, gpu, cfg)
+
+
+# ------------------------------------------------------------------ the conventional loop order
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+@pytest.mark.parametrize("n_clusters", [1, 0])
+def test_frame_looping_small_models(oracle_lib, gpu, cfg, n_clusters):
+    """Algorithm 2 on the same kernels: the oracle's hypotheses, one joint pass and one
+    predictor pass per step."""
+    out, res = check(oracle_lib, gpu, cfg, n_clusters=n_clusters, algorithm=1)
+    assert out["stats"]["joint_passes"] == out["stats"]["pred_passes"]
+    if n_clusters == 1 and not cfg.durations and res["exact"] == res["rows"]:
+        # the whole batch looks at one frame at a time: the step count of Algorithm 2 run on the
+        # oracle's primitives, and one scored row per decision of the oracle
+        import loops
+        w = synth.generate_model(cfg)
+        enc, ln = synth.generate_inputs(cfg)
+        om = oracle_lib.OracleModel(cfg, w)
+        fl = loops.frame_looping_batched(loops.oracle_fns(om, enc), ln, cfg.max_symbols,
+                                         cfg.T * cfg.max_symbols)
+        ref = oracle_lib.decode_batch(om, enc, ln, cfg.max_symbols, cfg.T * cfg.max_symbols)
+        assert out["stats"]["joint_passes"] == fl["n_joint"]
+        assert out["stats"]["joint_rows"] == ref["n_joint"].sum()
+
+
+def test_frame_looping_fig2_and_config2(oracle_lib, gpu):
+    ex = fig2_model.build()
+    cfg, w, enc, ln = fig2_model.real_model(ex)
+    out = run_gpu(gpu, cfg, w, enc, ln, 16, n_clusters=1, algorithm=1)
+    for b, em in enumerate(ex["expected"]):
+        n = out["len"][b]
+        assert list(zip(out["labels"][b, :n], out["frames"][b, :n])) == em
+    # the hand-traced call counts of Algorithm 2 for the figure's example
+    assert out["stats"]["pred_passes"] == ex["vals"]["frame_looping_predictor_calls"]
+    assert out["stats"]["joint_passes"] == ex["vals"]["frame_looping_joiner_calls"]
+    check(oracle_lib, gpu, synth.CONFIGS["cfg2_rnnt_lstm"], algorithm=1)
+    check(oracle_lib, gpu, synth.CONFIGS["cfg3_tdt_lstm"], algorithm=1, n_clusters=1)
 
 
 def test_config1_tiny_rnnt(oracle_lib, gpu):
