@@ -38,7 +38,7 @@
 // cores (v_mfma_f32_16x16x32_bf16) with every activation split exactly into
 // three bfloat16 terms (hi + lo + lo2 == x), so products are exact and only the
 // float32 summation order differs from a scalar reference.  float32 weights
-// (small models) use the vector ALUs.
+// (small models) run on the float32 matrix-core product (v_mfma_f32_16x16x4_f32).
 //
 // Exchange between workgroups.  Data one workgroup writes for another (hidden and
 // cell state, projected predictor output, per-row argmax cells, softmax partials,

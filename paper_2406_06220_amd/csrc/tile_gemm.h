@@ -13,7 +13,7 @@ namespace tdt {
 namespace {
 
 // ---------------------------------------------------------------------------
-// Activation tile in LDS and the two tile-GEMM back ends
+// Activation tile in LDS and the two tile-GEMM back ends (both on the matrix cores)
 // ---------------------------------------------------------------------------
 // bfloat16 weights: three bfloat16 planes [3][RT][ldb] with hi + lo + lo2 == x.
 // float32 weights:  one float plane [RT][ldb].
@@ -49,8 +49,8 @@ template <> struct ActTile<uint16_t> {
 
 template <> struct ActTile<float> {
     float *planes;
-    int ldb;
-    __host__ __device__ static int row_elems(int kseg_max) { return ((kseg_max + 31) / 32) * 32; }
+    int ldb;   // floats per row: padded by 16 bytes so that 16-byte reads of 16 rows meet different banks
+    __host__ __device__ static int row_elems(int kseg_max) { return ((kseg_max + 31) / 32) * 32 + 4; }
     __device__ void store2(int i, int k, float2 v) const
     {
         *reinterpret_cast<float2 *>(planes + (size_t)i * ldb + k) = v;
@@ -112,12 +112,8 @@ template <> struct Accum<uint16_t> {
     __device__ void clear() { c = f32x4{0.0f, 0.0f, 0.0f, 0.0f}; }
 };
 template <> struct Accum<float> {
-    float c[CT];   // lane l < 16: row l, column j
-    __device__ void clear()
-    {
-#pragma unroll
-        for (int j = 0; j < CT; ++j) c[j] = 0.0f;
-    }
+    f32x4 c;   // same layout
+    __device__ void clear() { c = f32x4{0.0f, 0.0f, 0.0f, 0.0f}; }
 };
 
 // matrix-core back end: this wavefront adds its share (k-steps kpart, kpart + ksplit, ...)
@@ -183,35 +179,6 @@ __device__ inline void tile_accumulate(const ActTile<uint16_t> &A, const Seg &sg
     }
 }
 
-// vector-ALU back end: the wavefront's 64 lanes split K, all 16 rows at once, one column
-__device__ inline float column_dot(const ActTile<float> &A, const Seg &sg, long long wrow, int lane)
-{
-    float acc[RT];
-#pragma unroll
-    for (int i = 0; i < RT; ++i) acc[i] = 0.0f;
-    if (wrow >= 0) {
-        const float *w = static_cast<const float *>(sg.w) + wrow * sg.wld + sg.k0;
-        for (int k = lane * 2; k < sg.K; k += 128) {
-            const float2 wv = *reinterpret_cast<const float2 *>(w + k);
-#pragma unroll
-            for (int i = 0; i < RT; ++i) {
-                const float2 a = *reinterpret_cast<const float2 *>(A.planes + (size_t)i * A.ldb + k);
-                acc[i] = fmaf(a.x, wv.x, acc[i]);
-                acc[i] = fmaf(a.y, wv.y, acc[i]);
-            }
-        }
-    }
-    float mine = 0.0f;
-#pragma unroll
-    for (int i = 0; i < RT; ++i) {
-        float v = acc[i];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-        if (lane == i) mine = v;
-    }
-    return mine;   // lane i < 16: row i
-}
-
 template <typename WT> struct Backend;
 template <> struct Backend<uint16_t> {
     struct Pre {   // weight fragments fetched while the activations are being staged
@@ -237,29 +204,64 @@ template <> struct Backend<uint16_t> {
     }
     __device__ static int ksplit_for(int n_ct) { return n_ct <= 1 ? 8 : n_ct <= 2 ? 4 : n_ct <= 4 ? 2 : 1; }
 };
+// float32 weights: the float32 matrix-core product (v_mfma_f32_16x16x4_f32: exact products,
+// float32 accumulation).  A lane holds four consecutive inputs of its weight row / activation
+// row (one 16-byte load each) and feeds them to four MFMAs; a step covers 16 inputs.
 template <> struct Backend<float> {
-    struct Pre {};
-    template <typename RowF>
-    __device__ static void prefetch(Pre &, const Seg &, RowF, int, int, int, int) {}
-    template <typename RowF>
-    __device__ static void accumulate(const ActTile<float> &A, const Seg &sg, RowF rowidx, int ct, int, int,
-                                      Accum<float> &acc, int lane, Pre &)
+    struct Pre {
+        const float *wr;   // this lane's weight row at its quarter of a step (row 0 if the column is padding)
+        bool live;
+        int kq, n_my;
+        float4 b[CH];
+    };
+    __device__ static void fetch(Pre &pre, const Seg &sg, int kpart, int ksplit, int c0)
     {
-        for (int j = 0; j < CT; ++j) {
-            const float v = column_dot(A, sg, rowidx(ct, j), lane);
 #pragma unroll
-            for (int jj = 0; jj < CT; ++jj)
-                if (jj == j) acc.c[jj] += v;
+        for (int j = 0; j < CH; ++j) {   // unconditional, clamped into the row; masked where used
+            const int k = (kpart + (c0 + j) * ksplit) * 16 + pre.kq;
+            pre.b[j] = *reinterpret_cast<const float4 *>(pre.wr + (k < sg.K ? k : sg.K - 4));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    template <typename RowF>
+    __device__ static void prefetch(Pre &pre, const Seg &sg, RowF rowidx, int ct, int kpart, int ksplit, int lane)
+    {
+        const long long wrow = rowidx(ct, lane & 15);
+        pre.kq = (lane >> 4) * 4;
+        pre.live = wrow >= 0;
+        pre.wr = static_cast<const float *>(sg.w) + (pre.live ? wrow : 0) * sg.wld + sg.k0;
+        const int nsteps = (sg.K + 15) / 16;
+        pre.n_my = nsteps > kpart ? (nsteps - kpart + ksplit - 1) >> __builtin_ctz(ksplit) : 0;
+        fetch(pre, sg, kpart, ksplit, 0);
+    }
+    template <typename RowF>
+    __device__ static void accumulate(const ActTile<float> &A, const Seg &sg, RowF, int, int kpart, int ksplit,
+                                      Accum<float> &acc, int lane, Pre &pre)
+    {
+        const float *a0 = A.planes + (size_t)(lane & 15) * A.ldb + pre.kq;
+        for (int c0 = 0; c0 < pre.n_my; c0 += CH) {
+            if (c0 > 0) fetch(pre, sg, kpart, ksplit, c0);
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                if (c0 + j < pre.n_my) {
+                    const int s = kpart + (c0 + j) * ksplit;
+                    // the tile is zero beyond K up to a multiple of 32, so only the weights need the mask
+                    const bool ok = pre.live && s * 16 + pre.kq < sg.K;
+                    const float4 x = *reinterpret_cast<const float4 *>(a0 + s * 16);
+                    acc.c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x, ok ? pre.b[j].x : 0.0f, acc.c, 0, 0, 0);
+                    acc.c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.y, ok ? pre.b[j].y : 0.0f, acc.c, 0, 0, 0);
+                    acc.c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.z, ok ? pre.b[j].z : 0.0f, acc.c, 0, 0, 0);
+                    acc.c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.w, ok ? pre.b[j].w : 0.0f, acc.c, 0, 0, 0);
+                }
+            }
         }
     }
     __device__ static void spill(HypShared &S, const Accum<float> &acc, int wave, int lane)
     {
-        if (lane < RT) {
 #pragma unroll
-            for (int j = 0; j < CT; ++j) S.cpart[wave][lane][j] = acc.c[j];
-        }
+        for (int e = 0; e < 4; ++e) S.cpart[wave][(lane >> 4) * 4 + e][lane & 15] = acc.c[e];
     }
-    __device__ static int ksplit_for(int) { return 1; }
+    __device__ static int ksplit_for(int n_ct) { return n_ct <= 1 ? 8 : n_ct <= 2 ? 4 : n_ct <= 4 ? 2 : 1; }
 };
 
 // One work item: all K segments of the staged rows against n_ct column tiles, a round of
