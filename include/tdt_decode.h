@@ -195,6 +195,10 @@ int tdt_workspace_bytes(const tdt_weights_t *weights, int B, int T, int u_cap, s
  *
  * Calls that share a workspace must not overlap.  Returns TDT_OK once
  * everything is enqueued; outputs are valid after the stream is synchronised.
+ *
+ * The call allocates nothing and enqueues only kernels (no memset or copy nodes), so it
+ * may be recorded into a HIP graph by stream capture and replayed; `durations` and
+ * `options` are read when the call is made, i.e. at capture time.
  */
 int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
                       const tdt_weights_t *weights, const int32_t *durations, int max_symbols,

@@ -227,3 +227,48 @@ def test_chunk_capacity(oracle_lib, gpu):
     same = [b for b in range(cfg.B) if (g["labels"][b, :g["len"][b]] == r["labels"][b, :r["len"][b]]).all()]
     assert len(same) >= cfg.B - 1
     check_state(cfg, st.state.download(), ref_state, same)
+
+
+def test_chunk_call_replayed_from_a_graph(oracle_lib, gpu):
+    """A serving loop: the chunk call is captured once into a HIP graph (it allocates nothing and
+    enqueues only kernels); for every chunk the caller copies the new frames and lengths into the
+    captured buffers and replays.  Every replay must equal the eager call on the same chunk."""
+    import torch
+    cfg = synth.CONFIGS["cfg3_tdt_lstm"]
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    F, u_cap = 64, 64 * cfg.max_symbols
+    n_chunks = (int(ln.max()) + F - 1) // F
+    bounds = np.stack([np.minimum(np.arange(n_chunks + 1) * F, int(l)) for l in ln]).astype(np.int64)
+    eager, eager_state, eager_parts = decode_in_chunks(gpu, cfg, w, enc, ln, bounds, u_cap)
+
+    st = Stream(gpu, cfg, w, cfg.B, F, u_cap)
+    enc_buf = st.model.upload_enc(np.zeros((cfg.B, F, cfg.d_enc), np.float32))
+    len_buf = torch.zeros(cfg.B, dtype=torch.int32, device=st.model.device)
+    st.dec(enc_buf, len_buf, T=F)            # warm-up outside the capture
+    torch.cuda.synchronize()
+    st.state.reset()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    parity.announce(f"graph capture of tdt_greedy_decode_chunk cfg={cfg.name} B={cfg.B} T={F}")
+    with torch.cuda.graph(graph, stream=side, capture_error_mode="relaxed"):
+        st.dec(enc_buf, len_buf, T=F)
+    rng = np.random.default_rng(0)
+    for c in range(n_chunks):
+        ec, lc = chunks.make_chunk(enc, bounds, c, rng)
+        pad = np.zeros((cfg.B, F, cfg.d_enc), np.float32)
+        pad[:, :ec.shape[1]] = ec
+        enc_buf.copy_(st.model.upload_enc(pad))
+        len_buf.copy_(torch.from_numpy(lc).to(len_buf.device))
+        torch.cuda.synchronize()
+        parity.announce(f"  replay for chunk {c}")
+        graph.replay()
+        out = st.dec.results()
+        assert out["stats"]["abort"] == 0
+        ref = eager_parts[c]
+        assert (out["len"] == ref["len"]).all() and (out["status"] == ref["status"]).all()
+        assert (out["labels"] == ref["labels"]).all() and (out["frames"] == ref["frames"]).all()
+        assert (out["score"] == ref["score"]).all()
+    got_state = st.state.download()
+    for k in ("started", "time", "last", "last2", "h", "c"):
+        assert (got_state[k] == eager_state[k]).all(), k

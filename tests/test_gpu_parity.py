@@ -360,6 +360,47 @@ def test_side_stream_and_back_to_back_calls(oracle_lib, gpu):
         assert res["replayed"] <= 2, res
 
 
+def test_call_replayed_from_a_graph(oracle_lib, gpu):
+    """The whole call (clear, encoder projection, table, cooperative decode kernel) captured into
+    a HIP graph: every replay, with eager calls and synchronisations in between, gives the eager
+    result bit for bit."""
+    import torch
+    cfg = synth.CONFIGS["cfg2_rnnt_lstm"]
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    u_cap = cfg.T * cfg.max_symbols
+    model = gpu.DeviceModel(cfg, w)
+    dec = gpu.Decoder(model, cfg.B, cfg.T, u_cap)
+    enc_d = model.upload_enc(enc)
+    len_d = torch.from_numpy(ln).to(model.device)
+    parity.announce(f"graph capture of tdt_greedy_decode cfg={cfg.name}")
+    dec(enc_d, len_d)
+    ref = dec.results()
+    assert ref["stats"]["abort"] == 0
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side, capture_error_mode="relaxed"):
+        dec(enc_d, len_d)
+    for i in range(4):
+        for t in (dec.labels, dec.frames, dec.lens, dec.score, dec.status):
+            t.fill_(-1)
+        torch.cuda.synchronize()
+        parity.announce(f"  replay {i}")
+        graph.replay()
+        out = dec.results()
+        assert out["stats"]["abort"] == 0
+        for key in ("len", "score", "status"):
+            assert (out[key] == ref[key]).all(), (i, key)
+        for b in range(cfg.B):
+            n = ref["len"][b]
+            assert (out["labels"][b, :n] == ref["labels"][b, :n]).all()
+            assert (out["frames"][b, :n] == ref["frames"][b, :n]).all()
+        if i % 2 == 0:   # the program's own eager work between replays
+            dec(enc_d, len_d)
+            torch.cuda.synchronize()
+    parity.compare(oracle_lib, oracle_lib.OracleModel(cfg, w), cfg, enc, ln, out, u_cap)
+
+
 def test_pass_counters_match_the_loop_structure(oracle_lib, gpu):
     """With one group and a window of one frame the kernel is Algorithm 3 step for step: the number
     of predictor passes is the length of the longest hypothesis (plus the start-of-sequence step
