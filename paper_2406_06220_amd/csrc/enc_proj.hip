@@ -23,10 +23,25 @@ constexpr int GEMM_THREADS = 256;            // 4 wavefronts, each a 64x64 sub-t
 // 32 rows a wavefront reads for one k-slice spread over all LDS banks.
 __device__ inline int lds_off(int row, int chunk) { return row * BK + ((chunk ^ (row & 7)) << 3); }
 
-__global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(
-    const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
-    float *__restrict__ C, long long M, int N, int K, int group)
+// One product C = A * W^T + bias and the workgroups it takes.
+struct LinearProblem {
+    const uint16_t *A, *W;
+    const float *bias;
+    float *C;
+    long long M;
+    int N, K, group;
+    unsigned blocks;
+};
+
+// the 128 x 128 output tile of workgroup `block` (of q.blocks) of one product
+__device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
 {
+    const uint16_t *__restrict__ A = q.A;
+    const uint16_t *__restrict__ W = q.W;
+    const float *__restrict__ bias = q.bias;
+    float *__restrict__ C = q.C;
+    const long long M = q.M;
+    const int N = q.N, K = q.K, group = q.group;
     __shared__ __align__(16) uint16_t As[BM * BK];
     __shared__ __align__(16) uint16_t Bs[BN * BK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -37,8 +52,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(
     // column tile j % nt_n of that XCD's (j / nt_n)-th row tile.  `A` then comes from HBM once
     // instead of once per XCD; `W` is small and stays in every L2.
     const int nt_n = (N + BN - 1) / BN;
-    const long long j = blockIdx.x / kXcds;
-    const long long mt = (j / nt_n) * kXcds + blockIdx.x % kXcds;
+    const long long j = block / kXcds;
+    const long long mt = (j / nt_n) * kXcds + block % kXcds;
     const long long m0 = mt * BM;
     const int n0 = (int)(j % nt_n) * BN;
     if (m0 >= M) return;   // the last round of row tiles may be partial (uniform over the workgroup)
@@ -119,6 +134,32 @@ __global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(
         }
 }
 
+__global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(LinearProblem q)
+{
+    gemm_tile_bf16(q, blockIdx.x);
+}
+
+// Everything a decode call needs before its decode kernel, in one launch: the encoder
+// projection, the per-label input table of the first LSTM layer (q1.blocks == 0: none), and
+// the clearing of the workspace's zero region and of the statistics.  The three are
+// independent; a workgroup takes its task from its index.  Both products' workgroup counts
+// are multiples of the number of dies, so each keeps its die-aware order of tiles.
+__global__ __launch_bounds__(GEMM_THREADS) void prepare_bf16_kernel(LinearProblem q0, LinearProblem q1, uint4 *zero,
+                                                                   size_t n16, long long *out_stats)
+{
+    const unsigned b = blockIdx.x;
+    if (b < q0.blocks) {
+        gemm_tile_bf16(q0, b);
+    } else if (b < q0.blocks + q1.blocks) {
+        gemm_tile_bf16(q1, b - q0.blocks);
+    } else {
+        const unsigned zb = b - q0.blocks - q1.blocks, nzb = gridDim.x - q0.blocks - q1.blocks;
+        for (size_t i = (size_t)zb * GEMM_THREADS + threadIdx.x; i < n16; i += (size_t)nzb * GEMM_THREADS)
+            zero[i] = make_uint4(0, 0, 0, 0);
+        if (out_stats && zb == 0 && threadIdx.x < TDT_STAT_COUNT) out_stats[threadIdx.x] = 0;
+    }
+}
+
 // float32 models (small): classic 64x64 tile, 4x4 outputs per thread.
 __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
     const float *__restrict__ A, const float *__restrict__ W, const float *__restrict__ bias,
@@ -171,16 +212,48 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
 
 }  // namespace
 
+static LinearProblem linear_problem(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
+                                    int group, float *out)
+{
+    LinearProblem q{};
+    q.A = static_cast<const uint16_t *>(a);
+    q.W = static_cast<const uint16_t *>(w);
+    q.bias = bias;
+    q.C = out;
+    q.M = rows;
+    q.N = N;
+    q.K = K;
+    q.group = group;
+    const long long row_tiles = (rows + BM - 1) / BM, rounds = (row_tiles + kXcds - 1) / kXcds;
+    q.blocks = (unsigned)(rounds * kXcds * ((N + BN - 1) / BN));
+    return q;
+}
+
+hipError_t launch_prepare_bf16(const void *enc, int64_t rows, const tdt_weights_t *w, float *enc_proj,
+                               float *emb_gates, void *zero_begin, size_t zero_bytes, long long *out_stats,
+                               hipStream_t stream)
+{
+    const LinearProblem q0 = linear_problem(enc, rows, w->d_enc, w->w_enc, w->h_joint, w->b_enc, 0, enc_proj);
+    LinearProblem q1{};
+    if (w->pred_kind == TDT_PRED_LSTM)   // stored [label][unit][gate]
+        q1 = linear_problem(w->emb, w->vocab + 1, w->emb_dim, w->w_ih[0], 4 * w->h_pred, w->b_lstm[0], w->h_pred,
+                            emb_gates);
+    const size_t n16 = zero_bytes / 16;
+    size_t zb = (n16 + GEMM_THREADS - 1) / GEMM_THREADS;
+    if (zb > 256) zb = 256;
+    if (zb < 1) zb = 1;
+    hipLaunchKernelGGL(prepare_bf16_kernel, dim3(q0.blocks + q1.blocks + (unsigned)zb), dim3(GEMM_THREADS), 0, stream,
+                       q0, q1, static_cast<uint4 *>(zero_begin), n16, out_stats);
+    return hipGetLastError();
+}
+
 hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
                          int dtype, int group, float *out, hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;
     if (dtype == 1) {
-        const long long row_tiles = (rows + BM - 1) / BM, rounds = (row_tiles + kXcds - 1) / kXcds;
-        dim3 grid((unsigned)(rounds * kXcds * ((N + BN - 1) / BN)));
-        hipLaunchKernelGGL(enc_proj_bf16_kernel, grid, dim3(GEMM_THREADS), 0, stream,
-                           static_cast<const uint16_t *>(a), static_cast<const uint16_t *>(w), bias, out,
-                           (long long)rows, N, K, group);
+        const LinearProblem q = linear_problem(a, rows, K, w, N, bias, group, out);
+        hipLaunchKernelGGL(enc_proj_bf16_kernel, dim3(q.blocks), dim3(GEMM_THREADS), 0, stream, q);
     } else {
         dim3 grid((unsigned)(((N + 63) / 64) * ((rows + 63) / 64)));
         hipLaunchKernelGGL(enc_proj_f32_kernel, grid, dim3(256), 0, stream, static_cast<const float *>(a),

@@ -196,11 +196,18 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     char *ws = static_cast<char *>(workspace);
     float *enc_proj = reinterpret_cast<float *>(ws + L.enc_proj);
 
-    if (launch_init(ws + L.zero_begin, L.zero_end - L.zero_begin,
-                    reinterpret_cast<long long *>(out_stats), s) != hipSuccess)
-        return TDT_ERR_LAUNCH;
     float *emb_gates = reinterpret_cast<float *>(ws + L.emb_gates);
-    if (!reuse_enc_proj) {
+    if (!reuse_enc_proj && weights->dtype == 1) {
+        // one launch: the projection, the first LSTM layer's per-label table, the clearing
+        if (launch_prepare_bf16(enc, (int64_t)B * T, weights, enc_proj, emb_gates, ws + L.zero_begin,
+                                L.zero_end - L.zero_begin, reinterpret_cast<long long *>(out_stats),
+                                s) != hipSuccess)
+            return TDT_ERR_LAUNCH;
+    } else if (launch_init(ws + L.zero_begin, L.zero_end - L.zero_begin,
+                           reinterpret_cast<long long *>(out_stats), s) != hipSuccess) {
+        return TDT_ERR_LAUNCH;
+    }
+    if (!reuse_enc_proj && weights->dtype != 1) {
         if (launch_encoder_projection(enc, (int64_t)B * T, weights, enc_proj, s) != hipSuccess)
             return TDT_ERR_LAUNCH;
         // first LSTM layer: its input product depends on the label only, so it is a table,

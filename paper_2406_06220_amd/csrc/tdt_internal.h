@@ -95,6 +95,11 @@ hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_we
 // which puts the N / group outputs n, n + group, n + 2 group, ... side by side.
 hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
                          int dtype, int group, float *out, hipStream_t stream);
+// bf16 models: encoder projection, the first LSTM layer's per-label table and the clearing of the
+// zero region in one launch
+hipError_t launch_prepare_bf16(const void *enc, int64_t rows, const tdt_weights_t *w, float *enc_proj,
+                               float *emb_gates, void *zero_begin, size_t zero_bytes, long long *out_stats,
+                               hipStream_t stream);
 hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats,
                        hipStream_t stream);
 hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid, hipStream_t stream);
