@@ -200,6 +200,20 @@ def test_frame_looping_small_models(oracle_lib, gpu, cfg, n_clusters):
         assert out["stats"]["joint_rows"] == ref["n_joint"].sum()
 
 
+def test_frame_looping_edges(oracle_lib, gpu):
+    cfg = SMALL[3]                       # TDT, two LSTM layers, lengths from 0
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    check(oracle_lib, gpu, cfg, w, enc, ln, u_cap=3, algorithm=1)            # capacity reached
+    check(oracle_lib, gpu, cfg, w, enc, ln, max_symbols=1, algorithm=1)      # one label a frame
+    check(oracle_lib, gpu, cfg, w, enc[:1], ln[:1] * 0 + cfg.T, algorithm=1) # B = 1
+    out = run_gpu(gpu, cfg, w, enc, np.zeros_like(ln), 10, algorithm=1)
+    assert (out["len"] == 0).all() and (out["status"] == 0).all()
+    cfg = SMALL[2]                       # RNN-T: a burst of labels on every frame
+    out, _ = check(oracle_lib, gpu, cfg, synth.generate_model(cfg, -1e4), algorithm=1, n_clusters=1)
+    assert (out["len"] == synth.generate_inputs(cfg)[1] * cfg.max_symbols).all()
+
+
 def test_frame_looping_fig2_and_config2(oracle_lib, gpu):
     ex = fig2_model.build()
     cfg, w, enc, ln = fig2_model.real_model(ex)
