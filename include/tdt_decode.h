@@ -11,7 +11,8 @@
  * Conventions
  *   - every pointer marked DEVICE is device memory owned by the caller; the
  *     library allocates nothing, keeps no state between calls, reads inputs and
- *     weights, and writes only outputs and the workspace;
+ *     weights, and writes only outputs, the workspace and -- in the chunk-by-chunk
+ *     call -- the state buffer the caller passes;
  *   - every matrix is [out_features][in_features], row-major;
  *   - dtype 0: enc, embeddings and weight matrices are float32;
  *     dtype 1: they are bfloat16 (raw 16-bit patterns); biases are float32 in
@@ -43,7 +44,7 @@ enum tdt_status {
     TDT_ERR_NULL = -1,        /* a required pointer is NULL */
     TDT_ERR_SHAPE = -2,       /* B, T, u_cap or max_symbols < 1, or a model dim out of range */
     TDT_ERR_UNSUPPORTED = -3, /* dtype, predictor kind, layer count or option not supported */
-    TDT_ERR_DURATIONS = -4,   /* n_dur / durations mismatch, negative entry, or no positive entry */
+    TDT_ERR_DURATIONS = -4,   /* n_dur / durations mismatch, entry outside [0, 2^20], or no positive entry */
     TDT_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or smaller than tdt_workspace_bytes */
     TDT_ERR_LAUNCH = -6       /* the HIP runtime refused a launch or a query */
 };
