@@ -93,7 +93,9 @@ def check_chunks(oracle, binding, cfg, mode, n_chunks, w=None, enc=None, ln=None
     w = synth.generate_model(cfg) if w is None else w
     if enc is None:
         enc, ln = synth.generate_inputs(cfg)
-    u_cap = cfg.T * cfg.max_symbols
+    # one more than any utterance can emit: capacity is counted per chunk, so a flag raised for
+    # the whole utterance has no counterpart in its pieces
+    u_cap = cfg.T * cfg.max_symbols + 1
     bounds = chunks.split_plan(ln, n_chunks, np.random.default_rng(7 + n_chunks), mode)
     got, state, _ = decode_in_chunks(binding, cfg, w, enc, ln, bounds, u_cap, **opts)
     om = oracle.OracleModel(cfg, w)
