@@ -228,6 +228,19 @@ def test_frame_looping_fig2_and_config2(oracle_lib, gpu):
     check(oracle_lib, gpu, synth.CONFIGS["cfg3_tdt_lstm"], algorithm=1, n_clusters=1)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes(oracle_lib, gpu, seed):
+    """Seeded random widths, depths, batch sizes, lengths and options: whole utterances, and the
+    same utterances in chunks where the draw is label-looping."""
+    import random_shapes
+    from test_gpu_chunks import check_chunks
+    cfg, opts, n_chunks = random_shapes.draw(seed)
+    check(oracle_lib, gpu, cfg, max_replayed_frac=0.2, **opts)
+    if opts["algorithm"] == 0 and cfg.T >= 2:
+        check_chunks(oracle_lib, gpu, cfg, "random", n_chunks, max_replayed_frac=0.2,
+                     window=opts["window"], n_clusters=opts["n_clusters"])
+
+
 def test_config1_tiny_rnnt(oracle_lib, gpu):
     out, res = check(oracle_lib, gpu, synth.CFG1)
     assert res["exact"] == synth.CFG1.B
