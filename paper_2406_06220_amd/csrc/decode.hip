@@ -462,7 +462,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 in.w1 = nullptr;
                 in.K1 = 0;
                 run_item<WT>(
-                    S, A, in, n_ct, sec_b ? nullptr : p.b_pred, p.b_pred,
+                    // the recurrent section has no bias of its own; its placeholder must still
+                    // cover the section's 4 * h_pred weight rows (run_item reads it unconditionally)
+                    S, A, in, n_ct, sec_b ? nullptr : p.b_pred, sec_b ? p.b_lstm[0] : p.b_pred,
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
                         if (lstm) {

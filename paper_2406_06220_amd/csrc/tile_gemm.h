@@ -288,7 +288,9 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nseg = in.count();
-    // always a readable float array with at least as many entries as there are weight rows
+    // The bias load below is unconditional, so that it is issued with the other loads of the
+    // item: where there is no bias, any_floats must be a readable float array that covers every
+    // index rowidx can return.
     const float *bias_or_any = bias ? bias : static_cast<const float *>(any_floats);
     const int ksplit = Backend<WT>::ksplit_for(n_ct);
     const int ksh = __builtin_ctz(ksplit);    // ksplit is 1, 2, 4 or 8

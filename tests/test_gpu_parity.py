@@ -132,12 +132,19 @@ SMALL = [
     synth.small_config("g_tdt_lstm4_bf16", dtype="bf16", pred_kind="lstm", pred_layers=4,
                        durations=(0, 1, 2, 4), d_enc=32, h_pred=40, emb_dim=16, h_joint=56, vocab=33,
                        B=17, T=56, len_lo=4, len_hi=56, seed=60, default_blank_bias=0.5, max_symbols=4),
+    # a joint space much narrower than the predictor (its bias vector is far shorter than the
+    # recurrent matrix has rows), few workgroups per group: several rounds per work item
+    synth.small_config("g_tdt_lstm2_bf16_narrow", dtype="bf16", pred_kind="lstm", pred_layers=2,
+                       durations=(0, 1, 3, 5), d_enc=400, h_pred=360, emb_dim=312, h_joint=16, vocab=449,
+                       B=114, T=29, len_lo=28, len_hi=29, seed=1023, default_blank_bias=0.87, max_symbols=3),
 ]
 
 
 @pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
-@pytest.mark.parametrize("window,n_clusters", [(0, 0), (1, 1), (5, 3), (64, 8)])
+@pytest.mark.parametrize("window,n_clusters", [(0, 0), (1, 1), (5, 3), (64, 8), (0, 32)])
 def test_small_models(oracle_lib, gpu, cfg, window, n_clusters):
+    if n_clusters > cfg.B:
+        pytest.skip("more groups than hypotheses")
     check(oracle_lib, gpu, cfg, window=window, n_clusters=n_clusters)
 
 
