@@ -19,17 +19,18 @@ TOL_MARGIN = 1e-3
 TOL_SCORE = 1e-3
 
 
-_CASE_LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out",
-                         "gpu_cases.log")
+_CASE_LOG = os.environ.get("TDT_CASE_LOG", "")   # optional file that also receives the case names
 
 
 def announce(msg: str) -> None:
-    """Name the case before a GPU step: on the real stderr, and appended (flushed to disk) to
-    the case log, so that its last line names the case if the process dies."""
+    """Name the case before a GPU step: on the real stderr, and -- if TDT_CASE_LOG names a file --
+    appended there and flushed to disk, so that its last line names the case if the process dies."""
     sys.__stderr__.write("[gpu-case] " + msg + "\n")
     sys.__stderr__.flush()
+    if not _CASE_LOG:
+        return
     try:
-        os.makedirs(os.path.dirname(_CASE_LOG), exist_ok=True)
+        os.makedirs(os.path.dirname(os.path.abspath(_CASE_LOG)), exist_ok=True)
         with open(_CASE_LOG, "a") as f:
             f.write(msg + "\n")
             f.flush()
