@@ -126,6 +126,15 @@ typedef struct {
  *               where the step emitted a label.  Same hypotheses as label-looping; kept
  *               to measure what the re-ordering of the loops is worth.  `window` and
  *               `joint_tiles` are ignored; not available for tdt_greedy_decode_chunk.
+ *   wait_timeout_us  bound on a single device-side wait of one workgroup for the others
+ *               of its group, in microseconds; 0 = 4 seconds.  A wait that runs out sets
+ *               TDT_STAT_ABORT, every workgroup leaves the kernel, and the outputs of the
+ *               call are invalid.  (A wait only runs out if workgroups of the kernel are
+ *               not making progress, e.g. on a device shared with a debugger.)
+ *   selftest_stall  non-zero: one workgroup of the first group never announces that it
+ *               has arrived, so that the waits of its group run out -- a self-test of
+ *               the path above (use a small wait_timeout_us); every workgroup still
+ *               leaves the kernel normally.
  */
 enum tdt_algorithm { TDT_ALG_LABEL_LOOPING = 0, TDT_ALG_FRAME_LOOPING = 1 };
 
@@ -135,7 +144,9 @@ typedef struct {
     int32_t reuse_enc_proj;
     int32_t joint_tiles;
     int32_t algorithm;   /* enum tdt_algorithm */
-    int32_t reserved[3]; /* must be zero */
+    int32_t wait_timeout_us;
+    int32_t selftest_stall;
+    int32_t reserved[1]; /* must be zero */
 } tdt_options_t;
 
 /* counters written to out_stats (int64 each); sums over all hypothesis groups */

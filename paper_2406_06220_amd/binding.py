@@ -49,7 +49,8 @@ class tdt_weights_t(C.Structure):
 
 class tdt_options_t(C.Structure):
     _fields_ = [("window", C.c_int32), ("n_clusters", C.c_int32), ("reuse_enc_proj", C.c_int32),
-                ("joint_tiles", C.c_int32), ("algorithm", C.c_int32), ("reserved", C.c_int32 * 3)]
+                ("joint_tiles", C.c_int32), ("algorithm", C.c_int32), ("wait_timeout_us", C.c_int32),
+                ("selftest_stall", C.c_int32), ("reserved", C.c_int32 * 1)]
 
 
 _lib = None

@@ -141,6 +141,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     bi.flags = p.barrier + (size_t)cl * C * kBarrierStride;
     bi.rank = rank;
     bi.epoch = 0;
+    bi.stall = p.selftest_stall && cl == 0 && rank == 0;
     LsePartial *const pbase = p.partials + (size_t)cl * (kPartialEntries / ncl);
     const int rows_cap = p.rows_per_cluster;
     unsigned long long *const rl_base = p.row_lab + (size_t)cl * kRowBufs * rows_cap;

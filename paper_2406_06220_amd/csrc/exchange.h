@@ -77,6 +77,7 @@ struct BarrierInfo {
     unsigned *flags;   // the cluster's flags; this workgroup's is flags[rank * kBarrierStride]
     int rank;
     unsigned epoch;    // barriers arrived at so far (the same in every thread of the cluster)
+    bool stall;        // self-test: this workgroup never publishes its arrivals, so the others' waits run out
 };
 
 __device__ inline void barrier_arrive(BarrierInfo &bi, int C)
@@ -85,7 +86,7 @@ __device__ inline void barrier_arrive(BarrierInfo &bi, int C)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();   // ... and so have those of the whole workgroup
     const unsigned epoch = ++bi.epoch;
-    if (C > 1 && threadIdx.x == 0)
+    if (C > 1 && threadIdx.x == 0 && !bi.stall)
         __hip_atomic_store(bi.flags + (size_t)bi.rank * kBarrierStride, epoch, __ATOMIC_RELAXED, TDT_AGENT);
 }
 

@@ -161,6 +161,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     }
     if (!any_pos) return TDT_ERR_DURATIONS;
     int window = 0, n_clusters = 0, joint_tiles = 0, algorithm = TDT_ALG_LABEL_LOOPING;
+    int wait_timeout_us = 0, selftest_stall = 0;
     bool reuse_enc_proj = false;
     if (options) {
         for (int r : options->reserved)
@@ -170,6 +171,9 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         reuse_enc_proj = options->reuse_enc_proj != 0;
         joint_tiles = options->joint_tiles;
         algorithm = options->algorithm;
+        wait_timeout_us = options->wait_timeout_us;
+        selftest_stall = options->selftest_stall;
+        if (wait_timeout_us < 0) return TDT_ERR_UNSUPPORTED;
         if (algorithm != TDT_ALG_LABEL_LOOPING && algorithm != TDT_ALG_FRAME_LOOPING) return TDT_ERR_UNSUPPORTED;
         if (algorithm == TDT_ALG_FRAME_LOOPING && state) return TDT_ERR_UNSUPPORTED;
         if (window < 0 || window > kMaxWindow || n_clusters < 0 || joint_tiles < 0 || joint_tiles > 64)
@@ -237,6 +241,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     p.joint_tiles = joint_tiles;
     p.n_clusters = n_clusters;
     p.frame_loop = algorithm == TDT_ALG_FRAME_LOOPING;
+    p.selftest_stall = selftest_stall != 0;
     p.hyps_per_cluster = (B + n_clusters - 1) / n_clusters;
     for (int j = 0; j < TDT_MAX_DURATIONS; ++j) p.durations[j] = j < weights->n_dur ? durations[j] : 0;
     p.emb = weights->emb;
@@ -285,7 +290,8 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
             khz = 100000;
-        p.timeout_ticks = 4000LL * khz;
+        p.timeout_ticks = wait_timeout_us > 0 ? (long long)wait_timeout_us * khz / 1000 : 4000LL * khz;
+        if (p.timeout_ticks < 1) p.timeout_ticks = 1;
     }
     if (launch_decode(p, weights, grid, s) != hipSuccess) return TDT_ERR_LAUNCH;
     return TDT_OK;

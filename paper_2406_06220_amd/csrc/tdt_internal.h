@@ -39,6 +39,7 @@ struct DecodeParams {
     int kseg_max;          // longest K segment staged at once (set by launch_decode)
     int n_clusters, hyps_per_cluster;
     int frame_loop;        // non-zero: batched frame-looping (Algorithm 2) instead of label-looping
+    int selftest_stall;    // non-zero: rank 0 of cluster 0 withholds its first barrier arrival
     int durations[TDT_MAX_DURATIONS];
     // weights
     const void *emb;

@@ -113,11 +113,13 @@ def test_rejects_bad_arguments_before_device_work(lib):
     # options
     o = binding.tdt_options_t(); o.window = 65
     assert _decode(lib, w, durations=dur, options=o) == -3
-    o = binding.tdt_options_t(); o.reserved[2] = 1
+    o = binding.tdt_options_t(); o.reserved[0] = 1
     assert _decode(lib, w, durations=dur, options=o) == -3
     o = binding.tdt_options_t(); o.joint_tiles = 65
     assert _decode(lib, w, durations=dur, options=o) == -3
     o = binding.tdt_options_t(); o.algorithm = 2
+    assert _decode(lib, w, durations=dur, options=o) == -3
+    o = binding.tdt_options_t(); o.wait_timeout_us = -1
     assert _decode(lib, w, durations=dur, options=o) == -3
     # workspace
     assert _decode(lib, w, durations=dur, ws=None) == -5

@@ -435,6 +435,34 @@ def test_call_replayed_from_a_graph(oracle_lib, gpu):
     parity.compare(oracle_lib, oracle_lib.OracleModel(cfg, w), cfg, enc, ln, out, u_cap)
 
 
+def test_a_wait_that_runs_out_ends_the_call(oracle_lib, gpu):
+    """Failure handling, forced from the host: one workgroup never announces its arrivals, the
+    bounded waits of its group run out after 300 us, every workgroup leaves the kernel, the call
+    reports it -- and the next call on the same workspace is sound again."""
+    import torch
+    cfg = SMALL[5]
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    u_cap = cfg.T * cfg.max_symbols
+    model = gpu.DeviceModel(cfg, w)
+    dec = gpu.Decoder(model, cfg.B, cfg.T, u_cap)
+    enc_d = model.upload_enc(enc)
+    len_d = torch.from_numpy(ln).to(model.device)
+    dec.options.wait_timeout_us = 300
+    dec.options.selftest_stall = 1
+    parity.announce(f"self-test: stalled arrival, waits bounded to 300 us, cfg={cfg.name}")
+    dec(enc_d, len_d)
+    out = dec.results()
+    assert out["stats"]["abort"] >= 1
+    dec.options.wait_timeout_us = 0
+    dec.options.selftest_stall = 0
+    parity.announce("  the next call on the same workspace")
+    dec(enc_d, len_d)
+    out = dec.results()
+    assert out["stats"]["abort"] == 0
+    parity.compare(oracle_lib, oracle_lib.OracleModel(cfg, w), cfg, enc, ln, out, u_cap)
+
+
 def test_pass_counters_match_the_loop_structure(oracle_lib, gpu):
     """With one group and a window of one frame the kernel is Algorithm 3 step for step: the number
     of predictor passes is the length of the longest hypothesis (plus the start-of-sequence step
