@@ -134,7 +134,8 @@ typedef struct {
  *   selftest_stall  non-zero: one workgroup of the first group never announces that it
  *               has arrived, so that the waits of its group run out -- a self-test of
  *               the path above (use a small wait_timeout_us); every workgroup still
- *               leaves the kernel normally.
+ *               leaves the kernel normally.  Honoured with TDT_ALG_FRAME_LOOPING only
+ *               (TDT_ERR_UNSUPPORTED otherwise), which keeps the hook out of the default kernels.
  */
 enum tdt_algorithm { TDT_ALG_LABEL_LOOPING = 0, TDT_ALG_FRAME_LOOPING = 1 };
 

@@ -74,10 +74,10 @@ __device__ inline float unpack_value(unsigned long long p)
 // or when another workgroup has flagged an abort, the wait returns false and the caller
 // leaves the kernel.
 struct BarrierInfo {
-    unsigned *flags;   // the cluster's flags; this workgroup's is flags[rank * kBarrierStride]
-    int rank;
+    unsigned *flags;   // the cluster's flags, kBarrierStride words apart
+    unsigned *mine;    // where this workgroup announces its arrivals: its flag -- or, in the self-test
+                       // of the time-out path, a spare word nobody reads
     unsigned epoch;    // barriers arrived at so far (the same in every thread of the cluster)
-    bool stall;        // self-test: this workgroup never publishes its arrivals, so the others' waits run out
 };
 
 __device__ inline void barrier_arrive(BarrierInfo &bi, int C)
@@ -86,8 +86,7 @@ __device__ inline void barrier_arrive(BarrierInfo &bi, int C)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();   // ... and so have those of the whole workgroup
     const unsigned epoch = ++bi.epoch;
-    if (C > 1 && threadIdx.x == 0 && !bi.stall)
-        __hip_atomic_store(bi.flags + (size_t)bi.rank * kBarrierStride, epoch, __ATOMIC_RELAXED, TDT_AGENT);
+    if (C > 1 && threadIdx.x == 0) __hip_atomic_store(bi.mine, epoch, __ATOMIC_RELAXED, TDT_AGENT);
 }
 
 // ends with a workgroup barrier

@@ -39,7 +39,7 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T)
     L.rgate = off;
     if (lstm_layers > 0) off = align_up(off + rows * 4 * w->h_pred * sizeof(float), 256);
     L.barrier = off;
-    off = align_up(off + (size_t)kMaxGrid * kBarrierStride * sizeof(unsigned), 256);
+    off = align_up(off + (size_t)(kMaxGrid + 1) * kBarrierStride * sizeof(unsigned), 256);   // + one spare word
     L.abort_flag = off;
     off = align_up(off + 256, 256);
     L.zero_end = off;
@@ -174,6 +174,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         wait_timeout_us = options->wait_timeout_us;
         selftest_stall = options->selftest_stall;
         if (wait_timeout_us < 0) return TDT_ERR_UNSUPPORTED;
+        if (selftest_stall && algorithm != TDT_ALG_FRAME_LOOPING) return TDT_ERR_UNSUPPORTED;
         if (algorithm != TDT_ALG_LABEL_LOOPING && algorithm != TDT_ALG_FRAME_LOOPING) return TDT_ERR_UNSUPPORTED;
         if (algorithm == TDT_ALG_FRAME_LOOPING && state) return TDT_ERR_UNSUPPORTED;
         if (window < 0 || window > kMaxWindow || n_clusters < 0 || joint_tiles < 0 || joint_tiles > 64)

@@ -450,12 +450,14 @@ def test_a_wait_that_runs_out_ends_the_call(oracle_lib, gpu):
     len_d = torch.from_numpy(ln).to(model.device)
     dec.options.wait_timeout_us = 300
     dec.options.selftest_stall = 1
+    dec.options.algorithm = 1          # the hook lives in the frame-looping kernels only
     parity.announce(f"self-test: stalled arrival, waits bounded to 300 us, cfg={cfg.name}")
     dec(enc_d, len_d)
     out = dec.results()
     assert out["stats"]["abort"] >= 1
     dec.options.wait_timeout_us = 0
     dec.options.selftest_stall = 0
+    dec.options.algorithm = 0
     parity.announce("  the next call on the same workspace")
     dec(enc_d, len_d)
     out = dec.results()
