@@ -188,10 +188,11 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     if (max_grid < 1) return TDT_ERR_LAUNCH;
     const int min_clusters = (B + kMaxHypsPerCluster - 1) / kMaxHypsPerCluster;
     if (n_clusters == 0) {
-        // Measured on the paper-sized models (B = 1 ... 512): two clusters beat one from a
-        // handful of hypotheses on (shorter joint passes outweigh the thinner spread of the
-        // matrices), four from about fifty, eight from about a hundred; more never paid.
-        n_clusters = B >= 128 ? 8 : B >= 48 ? 4 : B >= 4 ? 2 : 1;
+        // Measured on the paper-sized models (B = 1 ... 512): two clusters beat one from two
+        // hypotheses on (a cluster runs as long as its longest hypothesis, and shorter joint
+        // passes outweigh the thinner spread of the matrices), four from sixteen, eight from
+        // about eighty; more never paid.
+        n_clusters = B >= 80 ? 8 : B >= 16 ? 4 : B >= 2 ? 2 : 1;
         if (n_clusters < min_clusters) n_clusters = min_clusters;
     }
     if (n_clusters < min_clusters || n_clusters > max_grid) return TDT_ERR_UNSUPPORTED;
