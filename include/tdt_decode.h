@@ -109,7 +109,7 @@ typedef struct {
  *               and the first non-blank taken).  0 = automatic.
  *   n_clusters  the batch is split into this many groups of hypotheses that are
  *               decoded by disjoint sets of workgroups without waiting for each
- *               other.  0 = automatic (1, 2, 4 or 8 by batch size; more when B needs it).
+ *               other.  0 = automatic (by batch size and model shape; see the design notes).
  *   reuse_enc_proj  non-zero: the workspace still holds the encoder projection (and the
  *               first LSTM layer's per-label input table) that an earlier call with the
  *               same enc, B, T and weights left there, and these steps are skipped

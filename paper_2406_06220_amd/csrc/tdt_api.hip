@@ -188,11 +188,30 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     if (max_grid < 1) return TDT_ERR_LAUNCH;
     const int min_clusters = (B + kMaxHypsPerCluster - 1) / kMaxHypsPerCluster;
     if (n_clusters == 0) {
-        // Measured on the paper-sized models (B = 1 ... 512): two clusters beat one from two
-        // hypotheses on (a cluster runs as long as its longest hypothesis, and shorter joint
-        // passes outweigh the thinner spread of the matrices), four from sixteen, eight from
-        // about eighty; more never paid.
-        n_clusters = B >= 80 ? 8 : B >= 16 ? 4 : B >= 2 ? 2 : 1;
+        // Measured on the paper-sized models (B = 1 ... 512, 2 ... 16 clusters).  A cluster runs
+        // as long as its longest hypothesis and the fewer hypotheses it holds the shorter its
+        // joint passes, so more clusters pay -- until a cluster has too few workgroups to give
+        // each at most four column tiles of the predictor-side products (two weight batches per
+        // wavefront); `fit` is the cluster count at which that holds.  Small batches: two
+        // clusters.  An LSTM predictor: `fit`, except that eight are taken where eight make a
+        // cluster's hypotheses fit one 16-row tile and `fit` would not.  A stateless predictor
+        // streams no matrices per step and likes about ten hypotheses per cluster.
+        const bool lstm = weights->pred_kind == TDT_PRED_LSTM;
+        const int nt_a = (weights->h_joint + 15) / 16, nt_b = lstm ? (weights->h_pred + 3) / 4 : 0;
+        const int q4 = (nt_a + 3) / 4 + (nt_b + 3) / 4;
+        int fit = (2 * max_grid + q4) / (2 * q4);   // max_grid / q4, rounded
+        if (fit < 1) fit = 1;
+        if (B < 16) {
+            n_clusters = B >= 2 ? 2 : 1;
+        } else if (lstm) {
+            n_clusters = fit;
+            if (fit < 8 && (B + 7) / 8 <= 16 && (B + fit - 1) / fit > 16) n_clusters = 8;
+        } else {
+            n_clusters = B / 10;
+            if (n_clusters < 2) n_clusters = 2;
+            if (n_clusters > fit) n_clusters = fit;
+        }
+        if (n_clusters > B) n_clusters = B;
         if (n_clusters < min_clusters) n_clusters = min_clusters;
     }
     if (n_clusters < min_clusters || n_clusters > max_grid) return TDT_ERR_UNSUPPORTED;
