@@ -76,15 +76,26 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     const int ncl = p.n_clusters;
     const int C = gridDim.x / ncl;
     // Workgroups go to the chip's kXcds dies round-robin by blockIdx, and each die has its own
-    // L2.  A workgroup's rank decides which weight columns it multiplies, so each die gets a
-    // contiguous eighth of the ranks of every cluster: then its L2 holds an eighth of the
-    // matrices whatever the number of clusters (with one cluster per die each L2 would have
-    // to hold all of them, which it cannot, and every pass would fetch them again).
+    // L2.  A workgroup's rank decides which weight columns it multiplies, so a die should host
+    // the SAME ranks of every cluster: then its L2 holds an eighth of the matrices whatever the
+    // number of clusters (with one cluster per die each L2 would have to hold all of them, which
+    // it cannot, and every pass would fetch them again).  A die has gridDim / 8 slots; `per`
+    // ranks of every cluster are aligned that way (ranks die * per .. die * per + per - 1), the
+    // few ranks left over when the cluster size is no multiple of 8 take the remaining slots,
+    // and a slot beyond those stays empty (the grid is rounded up to a multiple of 8).
     int cl, rank;
-    if (C % kXcds == 0) {
+    if (gridDim.x % kXcds == 0) {
         const int die = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
-        cl = j % ncl;
-        rank = die * (C / kXcds) + j / ncl;
+        const int per = (int)(gridDim.x / kXcds) / ncl;
+        if (j < per * ncl) {
+            cl = j % ncl;
+            rank = die * per + j / ncl;
+        } else {
+            const int e = (j - per * ncl) * kXcds + die;
+            if (e >= ncl * (C - kXcds * per)) return;   // an empty slot: not part of any cluster
+            cl = e % ncl;
+            rank = kXcds * per + e / ncl;
+        }
     } else {
         cl = blockIdx.x % ncl;
         rank = blockIdx.x / ncl;

@@ -215,7 +215,10 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         if (n_clusters < min_clusters) n_clusters = min_clusters;
     }
     if (n_clusters < min_clusters || n_clusters > max_grid) return TDT_ERR_UNSUPPORTED;
-    const int grid = max_grid / n_clusters * n_clusters;
+    // every cluster gets max_grid / n_clusters workgroups; the launch is rounded up to whole
+    // rounds of the dies (the kernel leaves the spare slots empty)
+    int grid = max_grid / n_clusters * n_clusters;
+    if ((grid + kXcds - 1) / kXcds * kXcds <= max_grid) grid = (grid + kXcds - 1) / kXcds * kXcds;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
