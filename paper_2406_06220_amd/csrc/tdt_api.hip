@@ -193,9 +193,9 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         // joint passes, so more clusters pay -- until a cluster has too few workgroups to give
         // each at most four column tiles of the predictor-side products (two weight batches per
         // wavefront); `fit` is the cluster count at which that holds.  Small batches: two
-        // clusters.  An LSTM predictor: `fit`, except that eight are taken where eight make a
-        // cluster's hypotheses fit one 16-row tile and `fit` would not.  A stateless predictor
-        // streams no matrices per step and likes about ten hypotheses per cluster.
+        // clusters.  An LSTM predictor: `fit`; from about 14 hypotheses per cluster of eight on,
+        // where the row tiles are full either way, eight.  A stateless predictor streams no
+        // matrices per step and likes about ten hypotheses per cluster.
         const bool lstm = weights->pred_kind == TDT_PRED_LSTM;
         const int nt_a = (weights->h_joint + 15) / 16, nt_b = lstm ? (weights->h_pred + 3) / 4 : 0;
         const int q4 = (nt_a + 3) / 4 + (nt_b + 3) / 4;
@@ -205,7 +205,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
             n_clusters = B >= 2 ? 2 : 1;
         } else if (lstm) {
             n_clusters = fit;
-            if (fit < 8 && (B + 7) / 8 <= 16 && (B + fit - 1) / fit > 16) n_clusters = 8;
+            if (fit < 8 && B >= 14 * 8) n_clusters = 8;
         } else {
             n_clusters = B / 10;
             if (n_clusters < 2) n_clusters = 2;
