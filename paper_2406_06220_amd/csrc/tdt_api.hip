@@ -202,7 +202,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         int fit = (2 * max_grid + q4) / (2 * q4);   // max_grid / q4, rounded
         if (fit < 1) fit = 1;
         if (B < 16) {
-            n_clusters = B >= 2 ? 2 : 1;
+            n_clusters = 2;   // also for a single hypothesis: half the workgroups synchronise faster
         } else if (lstm) {
             n_clusters = fit;
             if (fit < 8 && B >= 14 * 8) n_clusters = 8;
@@ -211,7 +211,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
             if (n_clusters < 2) n_clusters = 2;
             if (n_clusters > fit) n_clusters = fit;
         }
-        if (n_clusters > B) n_clusters = B;
+        if (n_clusters > B && B > 1) n_clusters = B;
         if (n_clusters < min_clusters) n_clusters = min_clusters;
     }
     if (n_clusters < min_clusters || n_clusters > max_grid) return TDT_ERR_UNSUPPORTED;
