@@ -136,8 +136,17 @@ typedef struct {
  *               the path above (use a small wait_timeout_us); every workgroup still
  *               leaves the kernel normally.  Honoured with TDT_ALG_FRAME_LOOPING only
  *               (TDT_ERR_UNSUPPORTED otherwise), which keeps the hook out of the default kernels.
+ *   projections TDT_PROJ_PRECOMPUTED (0, default): the encoder frames are projected into the
+ *               joint space once, before the loops, and a predictor output once per label
+ *               (Sec. 3.4).  TDT_PROJ_ON_THE_FLY: the arrangement that section compares
+ *               against -- every joint pass first projects the encoder frames and the
+ *               predictor outputs of exactly the rows it is about to score.  Same
+ *               hypotheses; kept to measure what the precomputation is worth.  Needs
+ *               TDT_ALG_LABEL_LOOPING and no reuse_enc_proj; not available for
+ *               tdt_greedy_decode_chunk (TDT_ERR_UNSUPPORTED).
  */
 enum tdt_algorithm { TDT_ALG_LABEL_LOOPING = 0, TDT_ALG_FRAME_LOOPING = 1 };
+enum tdt_projections { TDT_PROJ_PRECOMPUTED = 0, TDT_PROJ_ON_THE_FLY = 1 };
 
 typedef struct {
     int32_t window;
@@ -147,7 +156,7 @@ typedef struct {
     int32_t algorithm;   /* enum tdt_algorithm */
     int32_t wait_timeout_us;
     int32_t selftest_stall;
-    int32_t reserved[1]; /* must be zero */
+    int32_t projections; /* enum tdt_projections */
 } tdt_options_t;
 
 /* counters written to out_stats (int64 each); sums over all hypothesis groups */

@@ -66,7 +66,9 @@ namespace {
 // batched frame-looping), on the same phases: every step runs the predictor for every active
 // hypothesis, scores one frame each, and keeps the new predictor state only where the step
 // emitted a label.  Same hypotheses; there to measure what the re-ordering is worth.
-template <typename WT, bool CHUNKED, bool FRAMELOOP>
+// ONTHEFLY: no projections ahead of the loops (the arrangement Sec. 3.4 compares against): every
+// joint pass first projects the encoder frames and the predictor outputs of its own rows.
+template <typename WT, bool CHUNKED, bool FRAMELOOP, bool ONTHEFLY>
 __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_lds[];
@@ -459,9 +461,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         {
             const float *src_a = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * Bw * Hp : nullptr;
             const float *src_b = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L) * Bw * Hp : nullptr;
-            const int NT_A = (H + CT - 1) / CT, NT_B = lstm ? (Hp + 3) / 4 : 0;
+            // (projections on the fly: only the recurrent product is left here)
+            const int NT_A = ONTHEFLY ? 0 : (H + CT - 1) / CT, NT_B = lstm ? (Hp + 3) / 4 : 0;
             // fewest tiles per work item that give every workgroup at most one item
-            int tpg = ((NT_A + NT_B) * n_tiles_a + C - 1) / C;
+            int tpg = max(1, ((NT_A + NT_B) * n_tiles_a + C - 1) / C);
             while (((NT_A + tpg - 1) / tpg + (NT_B + tpg - 1) / tpg) * n_tiles_a > C && tpg < NT_A + NT_B) ++tpg;
             const int g_a = (NT_A + tpg - 1) / tpg, g_b = (NT_B + tpg - 1) / tpg;
             const int n_grp = g_a + g_b;
@@ -600,6 +603,107 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 S.st[3] += M;
             }
 
+            if constexpr (ONTHEFLY) {
+                // ---- the projections of this pass's rows into the joint space, as Sec. 3.4 has
+                // them without precomputation: the M (hypothesis, frame) rows of the encoder output
+                // and the predictor outputs of the n_need searching hypotheses
+                const int NT_H = (H + CT - 1) / CT;
+                const int n_tiles_n = (n_need + RT - 1) / RT, rt_all = n_tiles + n_tiles_n;
+                int tpe = max(1, (NT_H * rt_all + C - 1) / C);
+                while (((NT_H + tpe - 1) / tpe) * rt_all > C && tpe < NT_H) ++tpe;
+                const int g_e = (NT_H + tpe - 1) / tpe;
+                const float *src_h = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * Bw * Hp : nullptr;
+                for (int it = rank; it < rt_all * g_e; it += C) {
+                    const int ti_all = it / g_e, grp = it % g_e;
+                    const bool sec_p = ti_all >= n_tiles;   // a tile of predictor outputs
+                    const int ti = sec_p ? ti_all - n_tiles : ti_all;
+                    const int nrows = min(RT, (sec_p ? n_need : M) - ti * RT);
+                    const int tile0 = grp * tpe, n_ct = min(tpe, NT_H - tile0);
+                    PhaseInputs ein;
+                    ein.w0 = sec_p ? p.w_pred : p.w_enc;
+                    ein.K0 = sec_p ? Hp : p.d_enc;
+                    ein.w1 = nullptr;
+                    ein.K1 = 0;
+                    // frame of joint row r, or -1 if it lies beyond its hypothesis' last frame
+                    auto row_frame = [&](int r, int &g) {
+                        const int q = r / Kw;
+                        g = S.need_list[q];
+                        const int f = S.time[g] + (r - q * Kw);
+                        return f < S.len[g] ? f : -1;
+                    };
+                    run_item<WT>(
+                        S, A, ein, n_ct, sec_p ? p.b_pred : p.b_enc, p.b_pred,
+                        [&](const Seg &sg) {
+                            const int k0 = sg.k0;
+                            if (!sec_p) {
+                                stage_segment<WT>(
+                                    A, sg.K, nrows,
+                                    [&](int i) {
+                                        int g;
+                                        const int f = row_frame(ti * RT + i, g);
+                                        EncRow c;
+                                        c.valid = f >= 0;
+                                        c.row = static_cast<const WT *>(p.enc) +
+                                                ((size_t)S.gid[g] * T + (c.valid ? f : 0)) * p.d_enc + k0;
+                                        return c;
+                                    },
+                                    [](const EncRow &c, int k) { return W2<WT>::load(static_cast<const WT *>(c.row) + k); },
+                                    [](const EncRow &c, int, typename W2<WT>::Raw v) {
+                                        const float2 x = W2<WT>::cvt(v);
+                                        return make_float2(c.valid ? x.x : 0.0f, c.valid ? x.y : 0.0f);
+                                    });
+                            } else if (lstm) {
+                                stage_segment<WT>(
+                                    A, sg.K, nrows,
+                                    [&](int i) { return src_h + (size_t)(b0 + S.need_list[ti * RT + i]) * Hp + k0; },
+                                    [](const float *row, int k) { return ld_co2(row + k); },
+                                    [](const float *, int, float2 v) { return v; });
+                            } else {
+                                stage_segment<WT>(
+                                    A, sg.K, nrows,
+                                    [&](int i) {
+                                        const int g = S.need_list[ti * RT + i];
+                                        return make_int2(S.last[g], S.last2[g]);
+                                    },
+                                    [&](int2 lab, int k) {
+                                        const int kk = k0 + k, c = kk / E;
+                                        const int tok = (c == L - 1) ? lab.x : lab.y;
+                                        return W2<WT>::load(static_cast<const WT *>(p.emb) +
+                                                            ((size_t)c * (V + 1) + tok) * E + (kk - c * E));
+                                    },
+                                    [](int2, int, typename W2<WT>::Raw v) { return W2<WT>::cvt(v); });
+                            }
+                        },
+                        [&](int ct, int j) -> long long {
+                            const int n = (tile0 + ct) * CT + j;
+                            return n < H ? n : -1;
+                        },
+                        [&](int, int) {},
+                        [&](int, int) {},
+                        [&](int base, int n, int ksplit) {
+                            for (int idx = tid; idx < n * RT * CT; idx += kThreads) {
+                                const int t = idx >> 8, i = (idx >> 4) & 15, j = idx & 15;
+                                const int col = (tile0 + base + t) * CT + j;
+                                if (i >= nrows || col >= H) continue;
+                                const float v = cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j];
+                                if (sec_p) {
+                                    st_co(p.pred_proj + (size_t)(b0 + S.need_list[ti * RT + i]) * H + col, v);
+                                } else {
+                                    int g;
+                                    const int f = row_frame(ti * RT + i, g);
+                                    if (f >= 0) st_co(p.enc_proj + ((size_t)S.gid[g] * T + f) * H + col, v);
+                                }
+                            }
+                        },
+                        wait_hook);
+                }
+                if (bar_pending) finish_barrier();
+                if (!ok) break;
+                lap(kTkQ);
+                barrier_arrive(bi, C);
+                bar_pending = true;
+            }
+
             // ---- J: joint network on M rows
             PhaseInputs in;
             in.w0 = p.w_out;
@@ -631,7 +735,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             },
                             [](const JointRow &c, int k) {
                                 EncPred v;
-                                v.e = *reinterpret_cast<const float2 *>(c.enc + k);
+                                if constexpr (ONTHEFLY) v.e = ld_co2(c.enc + k);   // written a phase ago
+                                else v.e = *reinterpret_cast<const float2 *>(c.enc + k);
                                 v.p = ld_co2(c.pred + k);
                                 return v;
                             },
@@ -941,16 +1046,17 @@ __global__ void init_kernel(uint4 *zero, size_t n16, long long *out_stats)
     if (out_stats && blockIdx.x == 0 && threadIdx.x < TDT_STAT_COUNT) out_stats[threadIdx.x] = 0;
 }
 
-int kseg_max_for(const tdt_weights_t *w)
+int kseg_max_for(const tdt_weights_t *w, bool on_the_fly)
 {
     int kmax = w->h_joint;
     if (w->h_pred > kmax) kmax = w->h_pred;
+    if (on_the_fly && w->d_enc > kmax) kmax = w->d_enc;   // the encoder output is staged too
     return kmax < KSEG ? kmax : KSEG;
 }
 
-size_t lds_bytes_for(const tdt_weights_t *w)
+size_t lds_bytes_for(const tdt_weights_t *w, bool on_the_fly)
 {
-    const int k = kseg_max_for(w);
+    const int k = kseg_max_for(w, on_the_fly);
     const size_t tile = w->dtype == 1 ? (size_t)3 * RT * ActTile<uint16_t>::row_elems(k) * sizeof(uint16_t)
                                       : (size_t)RT * ActTile<float>::row_elems(k) * sizeof(float);
     // before the first tile is staged the same memory holds the batch's lengths while they are ranked
@@ -971,21 +1077,26 @@ hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats
     return hipGetLastError();
 }
 
-static const void *kernel_for(const tdt_weights_t *w, bool chunked, bool frame_loop)
+static const void *kernel_for(const tdt_weights_t *w, DecodeVariant v)
 {
-    if (frame_loop)
-        return w->dtype == 1 ? (const void *)decode_kernel<uint16_t, false, true>
-                             : (const void *)decode_kernel<float, false, true>;
-    if (w->dtype == 1)
-        return chunked ? (const void *)decode_kernel<uint16_t, true, false>
-                       : (const void *)decode_kernel<uint16_t, false, false>;
-    return chunked ? (const void *)decode_kernel<float, true, false> : (const void *)decode_kernel<float, false, false>;
+    const bool bf16 = w->dtype == 1;
+    if (v.on_the_fly)
+        return bf16 ? (const void *)decode_kernel<uint16_t, false, false, true>
+                    : (const void *)decode_kernel<float, false, false, true>;
+    if (v.frame_loop)
+        return bf16 ? (const void *)decode_kernel<uint16_t, false, true, false>
+                    : (const void *)decode_kernel<float, false, true, false>;
+    if (bf16)
+        return v.chunked ? (const void *)decode_kernel<uint16_t, true, false, false>
+                         : (const void *)decode_kernel<uint16_t, false, false, false>;
+    return v.chunked ? (const void *)decode_kernel<float, true, false, false>
+                     : (const void *)decode_kernel<float, false, false, false>;
 }
 
-int decode_max_grid(const tdt_weights_t *w, bool chunked, bool frame_loop)
+int decode_max_grid(const tdt_weights_t *w, DecodeVariant v)
 {
-    const size_t lds = lds_bytes_for(w);
-    const void *fn = kernel_for(w, chunked, frame_loop);
+    const size_t lds = lds_bytes_for(w, v.on_the_fly);
+    const void *fn = kernel_for(w, v);
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return 0;
@@ -1003,13 +1114,14 @@ int decode_max_grid(const tdt_weights_t *w, bool chunked, bool frame_loop)
     return grid;
 }
 
-hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid, hipStream_t stream)
+hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, DecodeVariant v, int grid,
+                         hipStream_t stream)
 {
-    const size_t lds = lds_bytes_for(w);
+    const size_t lds = lds_bytes_for(w, v.on_the_fly);
     DecodeParams pc = p;
-    pc.kseg_max = kseg_max_for(w);
+    pc.kseg_max = kseg_max_for(w, v.on_the_fly);
     void *args[] = {&pc};
-    const void *fn = kernel_for(w, p.st_started != nullptr, p.frame_loop != 0);
+    const void *fn = kernel_for(w, v);
     // cooperative launch: the runtime refuses a grid whose workgroups cannot all be
     // resident at once, which is what the cluster barriers rely on
     return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(kThreads), args, (unsigned)lds, stream);

@@ -90,6 +90,12 @@ struct JointRow {
     bool valid;
 };
 
+// one row of encoder output that a pass projects on the fly
+struct EncRow {
+    const void *row;
+    bool valid;
+};
+
 struct PhaseInputs {
     const void *w0, *w1;   // weight matrices of the two inputs (w1 null: one input)
     int K0, K1;

@@ -162,10 +162,8 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     if (!any_pos) return TDT_ERR_DURATIONS;
     int window = 0, n_clusters = 0, joint_tiles = 0, algorithm = TDT_ALG_LABEL_LOOPING;
     int wait_timeout_us = 0, selftest_stall = 0;
-    bool reuse_enc_proj = false;
+    bool reuse_enc_proj = false, on_the_fly = false;
     if (options) {
-        for (int r : options->reserved)
-            if (r != 0) return TDT_ERR_UNSUPPORTED;
         window = options->window;
         n_clusters = options->n_clusters;
         reuse_enc_proj = options->reuse_enc_proj != 0;
@@ -177,6 +175,10 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         if (selftest_stall && algorithm != TDT_ALG_FRAME_LOOPING) return TDT_ERR_UNSUPPORTED;
         if (algorithm != TDT_ALG_LABEL_LOOPING && algorithm != TDT_ALG_FRAME_LOOPING) return TDT_ERR_UNSUPPORTED;
         if (algorithm == TDT_ALG_FRAME_LOOPING && state) return TDT_ERR_UNSUPPORTED;
+        if (options->projections != TDT_PROJ_PRECOMPUTED && options->projections != TDT_PROJ_ON_THE_FLY)
+            return TDT_ERR_UNSUPPORTED;
+        on_the_fly = options->projections == TDT_PROJ_ON_THE_FLY;
+        if (on_the_fly && (state || reuse_enc_proj || algorithm != TDT_ALG_LABEL_LOOPING)) return TDT_ERR_UNSUPPORTED;
         if (window < 0 || window > kMaxWindow || n_clusters < 0 || joint_tiles < 0 || joint_tiles > 64)
             return TDT_ERR_UNSUPPORTED;
     }
@@ -184,7 +186,8 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < L.total)
         return TDT_ERR_WORKSPACE;
 
-    const int max_grid = decode_max_grid(weights, state != nullptr, algorithm == TDT_ALG_FRAME_LOOPING);
+    const DecodeVariant variant{state != nullptr, algorithm == TDT_ALG_FRAME_LOOPING, on_the_fly};
+    const int max_grid = decode_max_grid(weights, variant);
     if (max_grid < 1) return TDT_ERR_LAUNCH;
     const int min_clusters = (B + kMaxHypsPerCluster - 1) / kMaxHypsPerCluster;
     if (n_clusters == 0) {
@@ -227,7 +230,8 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     float *emb_gates = reinterpret_cast<float *>(ws + L.emb_gates);
     if (!reuse_enc_proj && weights->dtype == 1) {
         // one launch: the projection, the first LSTM layer's per-label table, the clearing
-        if (launch_prepare_bf16(enc, (int64_t)B * T, weights, enc_proj, emb_gates, ws + L.zero_begin,
+        // (projections on the fly: no rows for the projection here)
+        if (launch_prepare_bf16(enc, on_the_fly ? 0 : (int64_t)B * T, weights, enc_proj, emb_gates, ws + L.zero_begin,
                                 L.zero_end - L.zero_begin, reinterpret_cast<long long *>(out_stats),
                                 s) != hipSuccess)
             return TDT_ERR_LAUNCH;
@@ -236,7 +240,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         return TDT_ERR_LAUNCH;
     }
     if (!reuse_enc_proj && weights->dtype != 1) {
-        if (launch_encoder_projection(enc, (int64_t)B * T, weights, enc_proj, s) != hipSuccess)
+        if (!on_the_fly && launch_encoder_projection(enc, (int64_t)B * T, weights, enc_proj, s) != hipSuccess)
             return TDT_ERR_LAUNCH;
         // first LSTM layer: its input product depends on the label only, so it is a table,
         // stored [label][unit][gate]
@@ -274,6 +278,9 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         p.w_hh[l] = weights->w_hh[l];
         p.b_lstm[l] = weights->b_lstm[l];
     }
+    p.enc = enc;
+    p.w_enc = weights->w_enc;
+    p.b_enc = weights->b_enc;
     p.w_pred = weights->w_pred;
     p.b_pred = weights->b_pred;
     p.w_out = weights->w_out;
@@ -317,7 +324,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         p.timeout_ticks = wait_timeout_us > 0 ? (long long)wait_timeout_us * khz / 1000 : 4000LL * khz;
         if (p.timeout_ticks < 1) p.timeout_ticks = 1;
     }
-    if (launch_decode(p, weights, grid, s) != hipSuccess) return TDT_ERR_LAUNCH;
+    if (launch_decode(p, weights, variant, grid, s) != hipSuccess) return TDT_ERR_LAUNCH;
     return TDT_OK;
 }
 

@@ -42,6 +42,8 @@ struct DecodeParams {
     int selftest_stall;    // non-zero: rank 0 of cluster 0 withholds its first barrier arrival
     int durations[TDT_MAX_DURATIONS];
     // weights
+    const void *w_enc;       // [H][d_enc]   (read by the kernel only when it projects on the fly)
+    const float *b_enc;
     const void *emb;
     const void *w_ih[TDT_MAX_LSTM_LAYERS], *w_hh[TDT_MAX_LSTM_LAYERS];
     const float *b_lstm[TDT_MAX_LSTM_LAYERS];
@@ -50,7 +52,8 @@ struct DecodeParams {
     const void *w_out;
     const float *b_out;
     // inputs
-    const float *enc_proj;   // [B][T][H]
+    const void *enc;         // [B][T][d_enc]   (read by the kernel only when it projects on the fly)
+    float *enc_proj;         // [B][T][H]; on the fly: written row by row as joint passes need them
     const float *emb_gates;  // [V+1][h_pred][4 gates]: w_ih[0] * emb[label] + b_lstm[0] (LSTM only)
     const int32_t *enc_len;  // [B]
     // outputs
@@ -103,8 +106,15 @@ hipError_t launch_prepare_bf16(const void *enc, int64_t rows, const tdt_weights_
                                hipStream_t stream);
 hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats,
                        hipStream_t stream);
-hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, int grid, hipStream_t stream);
+// which compiled form of the decode kernel a call runs
+struct DecodeVariant {
+    bool chunked;      // tdt_greedy_decode_chunk
+    bool frame_loop;   // TDT_ALG_FRAME_LOOPING
+    bool on_the_fly;   // TDT_PROJ_ON_THE_FLY
+};
+hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, DecodeVariant v, int grid,
+                         hipStream_t stream);
 // largest grid the decode kernel can run with all workgroups resident, 0 on error
-int decode_max_grid(const tdt_weights_t *w, bool chunked, bool frame_loop);
+int decode_max_grid(const tdt_weights_t *w, DecodeVariant v);
 
 }  // namespace tdt

@@ -113,7 +113,11 @@ def test_rejects_bad_arguments_before_device_work(lib):
     # options
     o = binding.tdt_options_t(); o.window = 65
     assert _decode(lib, w, durations=dur, options=o) == -3
-    o = binding.tdt_options_t(); o.reserved[0] = 1
+    o = binding.tdt_options_t(); o.projections = 2
+    assert _decode(lib, w, durations=dur, options=o) == -3
+    o = binding.tdt_options_t(); o.projections = 1; o.reuse_enc_proj = 1   # nothing to reuse on the fly
+    assert _decode(lib, w, durations=dur, options=o) == -3
+    o = binding.tdt_options_t(); o.projections = 1; o.algorithm = 1        # label-looping only
     assert _decode(lib, w, durations=dur, options=o) == -3
     o = binding.tdt_options_t(); o.joint_tiles = 65
     assert _decode(lib, w, durations=dur, options=o) == -3

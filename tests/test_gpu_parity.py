@@ -24,14 +24,14 @@ def gpu():
 
 
 def run_gpu(binding, cfg, w, enc, ln, u_cap, window=0, n_clusters=0, joint_tiles=0, max_symbols=None,
-            repeat=1, algorithm=0):
+            repeat=1, algorithm=0, projections=0):
     import torch
     parity.announce(f"tdt_greedy_decode cfg={cfg.name} B={len(ln)} T={enc.shape[1]} u_cap={u_cap} "
                     f"window={window} n_clusters={n_clusters} joint_tiles={joint_tiles} "
-                    f"S={max_symbols or cfg.max_symbols} algorithm={algorithm}")
+                    f"S={max_symbols or cfg.max_symbols} algorithm={algorithm} projections={projections}")
     model = binding.DeviceModel(cfg, w)
     dec = binding.Decoder(model, len(ln), enc.shape[1], u_cap, window=window, n_clusters=n_clusters,
-                          joint_tiles=joint_tiles, algorithm=algorithm)
+                          joint_tiles=joint_tiles, algorithm=algorithm, projections=projections)
     enc_d = model.upload_enc(enc)
     len_d = torch.from_numpy(np.ascontiguousarray(ln, np.int32)).to(model.device)
     out = None
@@ -233,6 +233,40 @@ def test_frame_looping_fig2_and_config2(oracle_lib, gpu):
     assert out["stats"]["joint_passes"] == ex["vals"]["frame_looping_joiner_calls"]
     check(oracle_lib, gpu, synth.CONFIGS["cfg2_rnnt_lstm"], algorithm=1)
     check(oracle_lib, gpu, synth.CONFIGS["cfg3_tdt_lstm"], algorithm=1, n_clusters=1)
+
+
+# ------------------------------------------------------------------ no precomputed projections
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+@pytest.mark.parametrize("window,n_clusters", [(0, 0), (1, 1), (5, 3)])
+def test_projections_on_the_fly_small_models(oracle_lib, gpu, cfg, window, n_clusters):
+    """Sec. 3.4's arrangement without precomputation: every joint pass projects its own rows.
+    Same hypotheses, same passes as the default."""
+    if n_clusters > cfg.B:
+        pytest.skip("more groups than hypotheses")
+    out, _ = check(oracle_lib, gpu, cfg, window=window, n_clusters=n_clusters, projections=1)
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    ref = run_gpu(gpu, cfg, w, enc, ln, cfg.T * cfg.max_symbols, window=window, n_clusters=n_clusters)
+    if (out["len"] == ref["len"]).all() and (out["labels"] == ref["labels"]).all():
+        for k in ("pred_passes", "joint_passes", "joint_rows"):
+            assert out["stats"][k] == ref["stats"][k]
+
+
+@pytest.mark.timeout(600)
+def test_projections_on_the_fly_edges_and_paper_sizes(oracle_lib, gpu):
+    cfg = SMALL[3]                       # TDT, two LSTM layers, lengths from 0
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    check(oracle_lib, gpu, cfg, w, enc, ln, u_cap=3, projections=1)            # capacity reached
+    check(oracle_lib, gpu, cfg, w, enc, ln, max_symbols=1, projections=1)      # one label a frame
+    check(oracle_lib, gpu, cfg, w, enc[:1], ln[:1] * 0 + cfg.T, projections=1) # B = 1
+    out = run_gpu(gpu, cfg, w, enc, np.zeros_like(ln), 10, projections=1)
+    assert (out["len"] == 0).all() and (out["status"] == 0).all()
+    # the projected frames land in a workspace that a default call has filled before, and the other
+    # way round: neither call may depend on what the other left there
+    out = run_gpu(gpu, cfg, w, enc, ln, cfg.T * cfg.max_symbols, projections=1, repeat=2)
+    for name in ("cfg2_rnnt_lstm", "cfg3_tdt_lstm", "cfg4_rnnt_stateless"):
+        check(oracle_lib, gpu, synth.CONFIGS[name], projections=1)
 
 
 @pytest.mark.parametrize("seed", range(16))
