@@ -2,7 +2,7 @@
 
 Every width is a multiple of 8 (the library's requirement); the draws cover both dtypes and
 predictors, one to four LSTM layers, with and without durations, lengths from 0, and the option
-space (window, groups, loop order)."""
+space (window, groups, loop order, projections ahead of the loops or on the fly)."""
 from __future__ import annotations
 
 import numpy as np
@@ -35,4 +35,7 @@ def draw(seed: int, hi: int = 320, v_hi: int = 400, b_hi: int = 70, t_hi: int = 
                 algorithm=int(rng.choice([0, 0, 0, 1])))
     if opts["n_clusters"] > cfg.B:
         opts["n_clusters"] = 0
-    return cfg, opts, int(rng.integers(2, 6))
+    n_chunks = int(rng.integers(2, 6))
+    # (drawn last, so that the draws above are what they were before this option existed)
+    opts["projections"] = int(opts["algorithm"] == 0 and rng.random() < 0.35)
+    return cfg, opts, n_chunks
