@@ -179,9 +179,17 @@ def test_largest_dimensions(oracle_lib, gpu):
                              h_joint=2048, vocab=21, B=5, T=12, len_lo=3, len_hi=12, seed=61,
                              default_blank_bias=0.5, max_symbols=2)
     check(oracle_lib, gpu, cfg)
+    check(oracle_lib, gpu, cfg, projections=1)
     cfg = synth.small_config("g_max_dims_stateless", dtype="bf16", pred_layers=2, d_enc=2048,
                              h_pred=2048, emb_dim=1024, h_joint=2048, vocab=21, B=4, T=12,
                              len_lo=3, len_hi=12, seed=62, default_blank_bias=0.5, max_symbols=2)
+    check(oracle_lib, gpu, cfg)
+    check(oracle_lib, gpu, cfg, projections=1)
+    # projected on the fly, the encoder output is the widest vector a kernel stages
+    cfg = synth.small_config("g_wide_enc", dtype="bf16", pred_kind="lstm", pred_layers=1, d_enc=2048,
+                             h_pred=64, emb_dim=32, h_joint=72, vocab=30, B=9, T=14, len_lo=2,
+                             len_hi=14, seed=63, default_blank_bias=0.5, max_symbols=3)
+    check(oracle_lib, gpu, cfg, projections=1)
     check(oracle_lib, gpu, cfg)
 
 
