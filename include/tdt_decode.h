@@ -57,6 +57,9 @@ enum tdt_pred_kind {
 /* per-hypothesis bits written to out_status */
 #define TDT_HYP_TRUNCATED 1   /* stopped because it reached u_cap labels */
 #define TDT_HYP_LEN_CLAMPED 2 /* enc_len[b] was outside [0, T] and was clamped */
+#define TDT_HYP_ABORTED 4     /* a bounded device-side wait of this hypothesis' group ran out
+                                 (see wait_timeout_us): its outputs are incomplete and, in the
+                                 chunk-by-chunk call, its state was left as it was before the call */
 
 /*
  * Model description (Sec. 2 "Background": encoder output, prediction network,
@@ -128,8 +131,9 @@ typedef struct {
  *               `joint_tiles` are ignored; not available for tdt_greedy_decode_chunk.
  *   wait_timeout_us  bound on a single device-side wait of one workgroup for the others
  *               of its group, in microseconds; 0 = 4 seconds.  A wait that runs out sets
- *               TDT_STAT_ABORT, every workgroup leaves the kernel, and the outputs of the
- *               call are invalid.  (A wait only runs out if workgroups of the kernel are
+ *               TDT_STAT_ABORT and TDT_HYP_ABORTED in the out_status of every hypothesis of
+ *               that group, every workgroup leaves the kernel, and those hypotheses are
+ *               incomplete.  (A wait only runs out if workgroups of the kernel are
  *               not making progress, e.g. on a device shared with a debugger.)
  *   selftest_stall  non-zero: one workgroup of the first group never announces that it
  *               has arrived, so that the waits of its group run out -- a self-test of
@@ -166,7 +170,8 @@ enum tdt_stat {
     TDT_STAT_JOINT_PASSES = 2, /* batched joint passes executed (Alg. 3 lines 7 and 13) */
     TDT_STAT_JOINT_ROWS = 3,  /* (hypothesis, frame) rows those passes scored */
     TDT_STAT_OUTER_MAX = 4,   /* largest number of label-loop iterations of any group */
-    TDT_STAT_ABORT = 5,       /* non-zero if an internal wait timed out (results invalid) */
+    TDT_STAT_ABORT = 5,       /* non-zero if an internal wait timed out (the hypotheses of the groups
+                                 concerned carry TDT_HYP_ABORTED in out_status) */
     /* where the first hypothesis group's time went, in ticks of the device wall clock
        (hipDeviceAttributeWallClockRate): predictor, projection, joint, decision, waits, all */
     TDT_STAT_TICKS_PRED = 8,

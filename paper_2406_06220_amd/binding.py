@@ -30,6 +30,7 @@ TDT_ALG_LABEL_LOOPING = 0
 TDT_ALG_FRAME_LOOPING = 1
 TDT_HYP_TRUNCATED = 1
 TDT_HYP_LEN_CLAMPED = 2
+TDT_HYP_ABORTED = 4
 
 EXPORTS = ("tdt_workspace_bytes", "tdt_greedy_decode", "tdt_state_bytes",
            "tdt_greedy_decode_chunk", "tdt_encoder_projection", "tdt_status_string")

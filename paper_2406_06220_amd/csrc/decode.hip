@@ -52,6 +52,8 @@
 // starts and are read through the caches as usual.
 #include <math.h>
 
+#include <mutex>
+
 #include "tdt_internal.h"
 #include "decode_state.h"
 #include "exchange.h"
@@ -1012,7 +1014,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         for (int g = tid; g < G; g += kThreads) {
             p.out_len[S.gid[g]] = S.out_len[g];
             p.out_score[S.gid[g]] = S.score[g];
-            p.out_status[S.gid[g]] = S.status[g];
+            // a wait of this cluster that ran out leaves its hypotheses incomplete: say so per row
+            p.out_status[S.gid[g]] = S.status[g] | (ok ? 0 : TDT_HYP_ABORTED);
         }
         if (tid == 0 && p.out_stats) {
             auto add = [&](int slot, long long v) {
@@ -1093,16 +1096,38 @@ static const void *kernel_for(const tdt_weights_t *w, DecodeVariant v)
                      : (const void *)decode_kernel<float, false, false, false>;
 }
 
+// The answer depends on the compiled form, the LDS it is launched with and the device only.  The
+// attribute call and the occupancy query cost tens of microseconds of host time, so they are
+// made once per (compiled form, device) and again only when a call needs more LDS than any
+// before it (the attribute is only ever raised; less LDS cannot lower the occupancy).
+namespace {
+struct GridCacheEntry {
+    const void *fn;
+    size_t max_lds;
+    int dev, grid;
+};
+constexpr int kGridCacheSize = 64;
+GridCacheEntry g_grid_cache[kGridCacheSize];
+int g_grid_cache_n = 0;
+std::mutex g_grid_cache_mutex;
+}  // namespace
+
 int decode_max_grid(const tdt_weights_t *w, DecodeVariant v)
 {
     const size_t lds = lds_bytes_for(w, v.on_the_fly);
     const void *fn = kernel_for(w, v);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    std::lock_guard<std::mutex> lock(g_grid_cache_mutex);
+    GridCacheEntry *ent = nullptr;
+    for (int i = 0; i < g_grid_cache_n; ++i)
+        if (g_grid_cache[i].fn == fn && g_grid_cache[i].dev == dev) ent = &g_grid_cache[i];
+    if (ent && lds <= ent->max_lds) return ent->grid;
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return 0;
     }
-    int dev = 0, n_cu = 0, per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    int n_cu = 0, per_cu = 0;
     if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
     hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, lds);
     if (e != hipSuccess || per_cu < 1) {
@@ -1111,7 +1136,29 @@ int decode_max_grid(const tdt_weights_t *w, DecodeVariant v)
     }
     int grid = n_cu;   // one workgroup per compute unit
     if (grid > kMaxGrid) grid = kMaxGrid;
+    if (ent) {
+        ent->max_lds = lds;
+        ent->grid = grid;
+    } else if (g_grid_cache_n < kGridCacheSize) {
+        g_grid_cache[g_grid_cache_n++] = GridCacheEntry{fn, lds, dev, grid};
+    }
     return grid;
+}
+
+// ticks per millisecond of the wall clock the kernels read (cached per device)
+int wall_clock_khz()
+{
+    static int khz_of[64];
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 100000;
+    std::lock_guard<std::mutex> lock(g_grid_cache_mutex);
+    if (khz_of[dev] > 0) return khz_of[dev];
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
+        (void)hipGetLastError();
+        return 100000;
+    }
+    khz_of[dev] = khz;
+    return khz;
 }
 
 hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, DecodeVariant v, int grid,

@@ -317,10 +317,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     p.abort_flag = reinterpret_cast<int *>(ws + L.abort_flag);
     {
         // bound on a single device-side wait: 4 s of the wall clock the kernel reads
-        int dev = 0, khz = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
-            khz = 100000;
+        const int khz = wall_clock_khz();
         p.timeout_ticks = wait_timeout_us > 0 ? (long long)wait_timeout_us * khz / 1000 : 4000LL * khz;
         if (p.timeout_ticks < 1) p.timeout_ticks = 1;
     }

@@ -116,5 +116,7 @@ hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, DecodeVa
                          hipStream_t stream);
 // largest grid the decode kernel can run with all workgroups resident, 0 on error
 int decode_max_grid(const tdt_weights_t *w, DecodeVariant v);
+// ticks per millisecond of the device wall clock the kernels read (100000 if the query fails)
+int wall_clock_khz();
 
 }  // namespace tdt

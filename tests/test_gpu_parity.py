@@ -497,13 +497,24 @@ def test_a_wait_that_runs_out_ends_the_call(oracle_lib, gpu):
     dec(enc_d, len_d)
     out = dec.results()
     assert out["stats"]["abort"] >= 1
+    # every hypothesis of a group whose wait ran out says so itself ...
+    assert (out["status"] & gpu.TDT_HYP_ABORTED).any()
+    # ... also for a caller who passes no statistics array
+    dec.status.zero_()
+    parity.announce("  the same without out_stats")
+    gpu.tdt_greedy_decode(enc_d.data_ptr(), len_d.data_ptr(), cfg.B, cfg.T, model.c, None,
+                          cfg.max_symbols, u_cap, dec.labels.data_ptr(), dec.frames.data_ptr(),
+                          dec.lens.data_ptr(), dec.score.data_ptr(), dec.status.data_ptr(), 0,
+                          dec.ws_ptr, dec.ws_bytes, dec.options, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert (dec.status.cpu().numpy() & gpu.TDT_HYP_ABORTED).any()
     dec.options.wait_timeout_us = 0
     dec.options.selftest_stall = 0
     dec.options.algorithm = 0
     parity.announce("  the next call on the same workspace")
     dec(enc_d, len_d)
     out = dec.results()
-    assert out["stats"]["abort"] == 0
+    assert out["stats"]["abort"] == 0 and not (out["status"] & gpu.TDT_HYP_ABORTED).any()
     parity.compare(oracle_lib, oracle_lib.OracleModel(cfg, w), cfg, enc, ln, out, u_cap)
 
 
