@@ -46,7 +46,8 @@ enum tdt_status {
     TDT_ERR_UNSUPPORTED = -3, /* dtype, predictor kind, layer count or option not supported */
     TDT_ERR_DURATIONS = -4,   /* n_dur / durations mismatch, entry outside [0, 2^20], or no positive entry */
     TDT_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or smaller than tdt_workspace_bytes */
-    TDT_ERR_LAUNCH = -6       /* the HIP runtime refused a launch or a query */
+    TDT_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch or a query */
+    TDT_ERR_TOO_LARGE = -7    /* tdt_greedy_decode_static: the sizes need more than TDT_STATIC_SCRATCH_BYTES */
 };
 
 enum tdt_pred_kind {
@@ -233,6 +234,31 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
                       float *out_score, int32_t *out_status, int64_t *out_stats,
                       void *workspace, size_t workspace_bytes, const tdt_options_t *options,
                       void *stream);
+
+/*
+ * tdt_greedy_decode for callers that cannot allocate device memory or have none to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The workspace is an array of TDT_STATIC_SCRATCH_BYTES bytes that is part of
+ * the library's device image: every GPU the library runs on holds its own copy from the
+ * first call on that GPU until the process ends.  The call allocates nothing and frees
+ * nothing; everything else -- arguments, outputs, options, error codes, asynchrony -- is
+ * tdt_greedy_decode's.
+ *
+ * Limit: tdt_workspace_bytes(weights, B, T, u_cap) must not exceed
+ * TDT_STATIC_SCRATCH_BYTES (64 MiB: e.g. B = 32 utterances of T = 250 frames with a joint
+ * width of 640 and a 1024-label LSTM predictor need 37 MB); otherwise TDT_ERR_TOO_LARGE, and
+ * nothing is enqueued.  All calls on one GPU share that GPU's array, which still holds what
+ * the previous call left there; the call clears, with a kernel on `stream`, every part that
+ * has to start at zero.  Calls that overlap on one GPU (different streams, or host threads
+ * without ordering between them) race on the array and give undefined results; calls on
+ * different GPUs are independent.
+ */
+#define TDT_STATIC_SCRATCH_BYTES (64u << 20)
+int tdt_greedy_decode_static(const void *enc, const int32_t *enc_len, int B, int T,
+                             const tdt_weights_t *weights, const int32_t *durations,
+                             int max_symbols, int u_cap, int32_t *out_labels, int32_t *out_frames,
+                             int32_t *out_len, float *out_score, int32_t *out_status,
+                             int64_t *out_stats, const tdt_options_t *options, void *stream);
 
 /*
  * Decoding utterances chunk by chunk (an extension beyond the paper, in the spirit of

@@ -31,8 +31,10 @@ TDT_ALG_FRAME_LOOPING = 1
 TDT_HYP_TRUNCATED = 1
 TDT_HYP_LEN_CLAMPED = 2
 TDT_HYP_ABORTED = 4
+TDT_ERR_TOO_LARGE = -7
+TDT_STATIC_SCRATCH_BYTES = 64 << 20
 
-EXPORTS = ("tdt_workspace_bytes", "tdt_greedy_decode", "tdt_state_bytes",
+EXPORTS = ("tdt_workspace_bytes", "tdt_greedy_decode", "tdt_greedy_decode_static", "tdt_state_bytes",
            "tdt_greedy_decode_chunk", "tdt_encoder_projection", "tdt_status_string")
 
 
@@ -74,6 +76,11 @@ def load_library():
             C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
             C.POINTER(tdt_options_t), C.c_void_p]
+        lib.tdt_greedy_decode_static.restype = C.c_int
+        lib.tdt_greedy_decode_static.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(tdt_weights_t),
+            C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(tdt_options_t), C.c_void_p]
         lib.tdt_state_bytes.restype = C.c_int
         lib.tdt_state_bytes.argtypes = [C.POINTER(tdt_weights_t), C.c_int, C.POINTER(C.c_size_t)]
         lib.tdt_greedy_decode_chunk.restype = C.c_int
@@ -133,6 +140,20 @@ def tdt_greedy_decode(enc_ptr: int, enc_len_ptr: int, B: int, T: int, weights: t
         enc_ptr, enc_len_ptr, B, T, C.byref(weights), dur, max_symbols, u_cap, out_labels_ptr,
         out_frames_ptr, out_len_ptr, out_score_ptr, out_status_ptr, out_stats_ptr, workspace_ptr,
         workspace_bytes, C.byref(options) if options is not None else None, stream))
+
+
+def tdt_greedy_decode_static(enc_ptr: int, enc_len_ptr: int, B: int, T: int, weights: tdt_weights_t,
+                             durations: Optional[Sequence[int]], max_symbols: int, u_cap: int,
+                             out_labels_ptr: int, out_frames_ptr: int, out_len_ptr: int,
+                             out_score_ptr: int, out_status_ptr: int, out_stats_ptr: int,
+                             options: Optional[tdt_options_t] = None, stream: int = 0) -> None:
+    dur = None
+    if durations is not None and len(durations):
+        dur = (C.c_int32 * len(durations))(*[int(d) for d in durations])
+    _check(load_library().tdt_greedy_decode_static(
+        enc_ptr, enc_len_ptr, B, T, C.byref(weights), dur, max_symbols, u_cap, out_labels_ptr,
+        out_frames_ptr, out_len_ptr, out_score_ptr, out_status_ptr, out_stats_ptr,
+        C.byref(options) if options is not None else None, stream))
 
 
 def tdt_state_bytes(weights: tdt_weights_t, B: int) -> int:

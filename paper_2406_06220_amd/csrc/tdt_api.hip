@@ -1,9 +1,44 @@
 // Host side of the C ABI: argument checks, workspace layout, launches.
 #include <string.h>
 
+#include <mutex>
+
 #include "tdt_internal.h"
 
+// Workspace of tdt_greedy_decode_static: device memory the library owns from the moment it is
+// loaded until the process ends, one copy on every GPU the library runs on.  In host code this
+// name is only a handle for hipGetSymbolAddress; the device address it yields (per device) is
+// what kernels, and everything else on the host, use.
+static __device__ __align__(256) unsigned char scratch[TDT_STATIC_SCRATCH_BYTES];
+
 namespace tdt {
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, once asked for
+
+// the current device's copy of `scratch`, or null (with *err set) if it cannot be found
+static void *static_scratch(hipError_t *err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -336,6 +371,28 @@ int tdt_greedy_decode(const void *enc, const int32_t *enc_len, int B, int T,
                          workspace_bytes, options, stream);
 }
 
+int tdt_greedy_decode_static(const void *enc, const int32_t *enc_len, int B, int T,
+                             const tdt_weights_t *weights, const int32_t *durations, int max_symbols,
+                             int u_cap, int32_t *out_labels, int32_t *out_frames, int32_t *out_len,
+                             float *out_score, int32_t *out_status, int64_t *out_stats,
+                             const tdt_options_t *options, void *stream)
+{
+    if (!weights) return TDT_ERR_NULL;
+    if (B < 1 || T < 1 || u_cap < 1) return TDT_ERR_SHAPE;
+    const int st = check_model(weights);
+    if (st != TDT_OK) return st;
+    // the same layout as a caller's workspace; it has to fit the array the library holds
+    const size_t need = workspace_layout(weights, B, T).total;
+    if (need > (size_t)TDT_STATIC_SCRATCH_BYTES) return TDT_ERR_TOO_LARGE;
+    hipError_t err = hipSuccess;
+    void *ptr = static_scratch(&err);
+    if (!ptr) return TDT_ERR_LAUNCH;
+    // decode_common clears, with a kernel, every part of the workspace that has to start at zero
+    return decode_common(enc, enc_len, B, T, weights, durations, max_symbols, u_cap, out_labels,
+                         out_frames, out_len, out_score, out_status, out_stats, nullptr, ptr,
+                         (size_t)TDT_STATIC_SCRATCH_BYTES, options, stream);
+}
+
 int tdt_greedy_decode_chunk(const void *enc, const int32_t *enc_len, int B, int T,
                             const tdt_weights_t *weights, const int32_t *durations, int max_symbols,
                             int u_cap, int32_t *out_labels, int32_t *out_frames, int32_t *out_len,
@@ -360,6 +417,7 @@ const char *tdt_status_string(int status)
     case TDT_ERR_DURATIONS: return "bad duration list";
     case TDT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case TDT_ERR_LAUNCH: return "HIP launch or query failed";
+    case TDT_ERR_TOO_LARGE: return "sizes beyond the library's own scratch memory";
     default: return "unknown status";
     }
 }

@@ -171,3 +171,19 @@ def test_state_bytes(lib):
     assert lib.tdt_state_bytes(None, 1, C.byref(size)) == -1
     assert lib.tdt_state_bytes(C.byref(w), 0, C.byref(size)) == -2
     assert lib.tdt_state_bytes(C.byref(w), 1, None) == -1
+
+
+def test_static_entry_point_refuses_sizes_beyond_its_array(lib):
+    """tdt_greedy_decode_static checks the sizes against the array it holds before any device
+    work (so this is safe without a GPU)."""
+    cfg = synth.CFG2_B128                    # 82 MB of projected frames alone
+    w = _weights(cfg)
+    assert binding.tdt_workspace_bytes(w, cfg.B, cfg.T, 100) > binding.TDT_STATIC_SCRATCH_BYTES
+    rc = lib.tdt_greedy_decode_static(4096, 4096, cfg.B, cfg.T, C.byref(w), None, 3, 30, 4096, 4096,
+                                      4096, 4096, 4096, None, None, None)
+    assert rc == binding.TDT_ERR_TOO_LARGE
+    assert binding.tdt_status_string(rc) != "unknown status"
+    assert lib.tdt_greedy_decode_static(4096, 4096, 0, 10, C.byref(w), None, 3, 30, 4096, 4096, 4096,
+                                        4096, 4096, None, None, None) == -2
+    assert lib.tdt_greedy_decode_static(4096, 4096, 2, 10, None, None, 3, 30, 4096, 4096, 4096,
+                                        4096, 4096, None, None, None) == -1
