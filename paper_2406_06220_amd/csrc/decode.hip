@@ -59,6 +59,14 @@
 #include "exchange.h"
 #include "tile_gemm.h"
 
+#if TDT_TRACE
+// profiling builds only: copies the recorded time line (see TR in decode_state.h) to the host
+extern "C" int tdt_debug_trace(long long *out, int n)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), (size_t)n * sizeof(long long));
+}
+#endif
+
 namespace tdt {
 namespace {
 
@@ -205,6 +213,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     }
     if (tid < TDT_MAX_DURATIONS) S.durations[tid] = p.durations[tid];
     if (tid == 0) {
+#if TDT_TRACE
+        g_tr_n = 0;
+        g_tr_on = 0;
+#endif
         S.aborted = 0;
         S.pend_n = 0;
         S.pend_ncg = 0;
@@ -327,6 +339,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             for (int i = tid; i < n_act; i += kThreads) S.hpar[S.act_list[i]] = (unsigned char)(pp ^ 1);
         const int n_tiles_p = (n_p + RT - 1) / RT;
 
+#if TDT_TRACE
+        if (tid == 0) g_tr_on = (S.st[4] >= 20 && S.st[4] < 24);
+#endif
+        TR(1);
         // ---- P: predictor step (Alg. 3 line 6)
         if (tid == 0) S.st[1] += n_p;
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 0;
@@ -455,6 +471,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             if (!ok) break;
         }
 
+        TR(2);
         // ---- Q: everything that is a product with the new predictor state: its projection into
         // the joint space (Sec. 3.4), and for an LSTM the recurrent part W_hh * h of the first
         // layer's next step.  Two sections of column tiles, each with its matrix and its input.
@@ -706,6 +723,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 bar_pending = true;
             }
 
+            TR(3);
             // ---- J: joint network on M rows
             PhaseInputs in;
             in.w0 = p.w_out;
@@ -820,11 +838,13 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             }
             if (bar_pending) finish_barrier();
             if (!ok) break;
+            TR(22);
             lap(kTkJ);
             ok = cluster_barrier(S, bi, p.abort_flag, C, p.timeout_ticks);
             lap(kTkBar);
             if (!ok) break;
 
+            TR(4);
             // ---- D: every workgroup takes the same decisions from the same cells
             // D1: one coherent load per row, all rows in flight together
             {
@@ -851,6 +871,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 }
             }
             __syncthreads();
+            TR(40);
             // the walk through the window of one searching hypothesis (all lanes of a wavefront)
             auto walk = [&](int q, int &w) -> bool {
                 const int g = S.need_list[q];
@@ -971,6 +992,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             }
             __syncthreads();
             build_list(S, S.need, G, S.need_list, &S.n_need);
+            TR(5);
             lap(kTkD);
             if (FRAMELOOP) break;   // Alg. 2: the next step starts with the predictor again
         }

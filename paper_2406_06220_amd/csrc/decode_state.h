@@ -13,6 +13,31 @@
 #define TDT_FINE_TIMERS 0
 #endif
 
+// 1: profiling build.  Thread 0 of workgroup 0 records (event id, device wall clock) pairs of a
+// few label-loop iterations into a device array that tdt_debug_trace() copies out -- a time line
+// of one workgroup through the phases, their barriers and the steps of a work item.
+#ifndef TDT_TRACE
+#define TDT_TRACE 0
+#endif
+
+#if TDT_TRACE
+__device__ long long g_trace[8192];   // [0]: events recorded; then (id << 48) | ticks
+namespace tdt {
+namespace {
+__shared__ int g_tr_n, g_tr_on;
+}
+}
+#define TR(id)                                                                                     \
+    do {                                                                                           \
+        if (blockIdx.x == 0 && threadIdx.x == 0 && tdt::g_tr_on && tdt::g_tr_n < 8190) {           \
+            g_trace[1 + tdt::g_tr_n] = ((long long)(id) << 48) | (wall_clock64() & 0xffffffffffffll); \
+            g_trace[0] = ++tdt::g_tr_n;                                                            \
+        }                                                                                          \
+    } while (0)
+#else
+#define TR(id) do { } while (0)
+#endif
+
 namespace tdt {
 namespace {
 

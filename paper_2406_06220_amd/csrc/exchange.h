@@ -83,8 +83,11 @@ struct BarrierInfo {
 __device__ inline void barrier_arrive(BarrierInfo &bi, int C)
 {
     // every coherent store / atomic of this wavefront has completed ...
+    TR(30);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    TR(31);
     __syncthreads();   // ... and so have those of the whole workgroup
+    TR(32);
     const unsigned epoch = ++bi.epoch;
     if (C > 1 && threadIdx.x == 0) __hip_atomic_store(bi.mine, epoch, __ATOMIC_RELAXED, TDT_AGENT);
 }
@@ -93,6 +96,7 @@ __device__ inline void barrier_arrive(BarrierInfo &bi, int C)
 __device__ inline bool barrier_wait(HypShared &S, const BarrierInfo &bi, int *abort_flag, int C,
                                     long long timeout_ticks)
 {
+    TR(34);
     const unsigned epoch = bi.epoch;
     if (C > 1 && threadIdx.x < 64) {
         const int lane = threadIdx.x;
@@ -125,6 +129,7 @@ __device__ inline bool barrier_wait(HypShared &S, const BarrierInfo &bi, int *ab
         }
     }
     __syncthreads();
+    TR(33);
     return S.aborted == 0;
 }
 

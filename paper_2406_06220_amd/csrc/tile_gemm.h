@@ -120,7 +120,10 @@ template <> struct Accum<float> {
 // of one segment to the 16x16 tile whose 16 weight rows are given per lane (l % 16).
 // The first chunk of weight fragments can be fetched ahead (before the activations are
 // staged) with weight_prefetch.
-constexpr int CH = 5;   // weight fragments in flight per wavefront
+#ifndef TDT_CH
+#define TDT_CH 5
+#endif
+constexpr int CH = TDT_CH;   // weight fragments in flight per wavefront
 
 struct WeightCursor {
     const uint16_t *wr;   // this lane's weight row at its k-quarter (row 0 if the column is padding)
@@ -310,7 +313,9 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
             bias_v = bias_or_any[r >= 0 ? r : 0];
             if (r < 0 || !bias) bias_v = 0.0f;
         }
+        TR(10);
         pre_round(base, min(tpr, n_ct - base));
+        TR(11);
         for (int sgi = 0; sgi < nseg; ++sgi) {
             const Seg sg = in.get(sgi);
             long long tq = 0;
@@ -318,15 +323,20 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
             typename Backend<WT>::Pre pre;
             // the weights do not depend on the activations: fetch the first of them now
             if (mine) Backend<WT>::prefetch(pre, sg, rowidx, ct, kpart, ksplit, lane);
+            TR(12);
             if (nseg > 1 || base == 0) {
                 // previous readers of the tile are done
                 if (base == 0 && sgi == 0) wait();
                 else __syncthreads();
+                TR(13);
                 stage(sg);
+                TR(14);
                 __syncthreads();
+                TR(15);
             }
             if (TDT_FINE_TIMERS && threadIdx.x == 0) { const long long n = wall_clock64(); S.tk_fine[S.fine_phase][0] += n - tq; tq = n; }
             if (mine) Backend<WT>::accumulate(A, sg, rowidx, ct, kpart, ksplit, acc, lane, pre);
+            TR(16);
             if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_fine[S.fine_phase][1] += wall_clock64() - tq;
         }
         long long tq = 0;
@@ -334,9 +344,13 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
         if (mine) Backend<WT>::spill(S, acc, wave, lane);
         if (threadIdx.x < kWaves * CT) S.bias[threadIdx.x] = bias_v;
         park(base, min(tpr, n_ct - base));
+        TR(17);
         __syncthreads();
+        TR(18);
         epi(base, min(tpr, n_ct - base), ksplit);
+        TR(19);
         __syncthreads();
+        TR(20);
         if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_fine[S.fine_phase][2] += wall_clock64() - tq;
     }
 }
