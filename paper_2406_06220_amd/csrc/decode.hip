@@ -155,6 +155,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 
     const int Hp = p.h_pred, E = p.emb_dim, L = p.pred_layers;
     const bool lstm = p.pred_kind == TDT_PRED_LSTM;
+    // the activation tile starts out as zeros: rows a work item does not stage keep what they
+    // held, and although nothing ever looks at their products they should be numbers
+    for (int i = tid; i < p.lds_bytes / 16; i += kThreads)
+        reinterpret_cast<uint4 *>(dyn_lds)[i] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
 
     ActTile<WT> A;
     A.planes = reinterpret_cast<decltype(A.planes)>(dyn_lds);
@@ -280,6 +285,30 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         const int groups = (NT + tiles_per_item - 1) / tiles_per_item;
         auto_rows = max(1, C / groups) * RT;
     }
+    // How a joint pass is cut depends only on how many hypotheses search: tabulated here, one
+    // thread per count, so that a pass looks it up instead of dividing.
+    for (int n = tid + 1; n <= G; n += kThreads) {
+        const int NT = (O + CT - 1) / CT;
+        int Kw = FRAMELOOP ? 1 : p.window;   // Alg. 2 looks at one frame per step
+        if (Kw <= 0) {
+            Kw = auto_rows / n;
+            if (Kw < 3) Kw = 3;
+        }
+        if (Kw > kMaxWindow) Kw = kMaxWindow;
+        if (Kw * n > rows_cap) Kw = rows_cap / n;
+        const int n_tiles = (n * Kw + RT - 1) / RT;
+        int n_cg, tpg;
+        split_tiles(C, n_tiles, NT, max_cg, n_cg, tpg);
+        JointPlan jp;
+        jp.Kw = (short)Kw;
+        jp.n_tiles = (short)n_tiles;
+        jp.n_cg = (short)n_cg;
+        jp.tpg = tpg;
+        jp.ti0 = (short)(rank / n_cg);   // this workgroup's first work item (rank), if it has one
+        jp.cg0 = rank % n_cg;
+        S.jplan[n] = jp;
+    }
+    __syncthreads();
     int pp = 0;          // which half of hbuf holds the current hidden state
     bool first = true;   // the first label-loop iteration of this call
     unsigned jpass = 0;  // joint passes so far (selects the exchange buffers)
@@ -301,8 +330,15 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         else __syncthreads();
     };
 
+    // The list of active hypotheses is rebuilt by the decision step together with the list of those
+    // that still search; the loop top builds it only where that has not happened (first iteration;
+    // the chunked and frame-looping forms, which change the flags between the two).
+    constexpr bool kPlain = !CHUNKED && !FRAMELOOP;
+    bool have_act = false;
+    // the split of phase Q's column tiles, kept while the number of row tiles stays the same
+    int q_for_tiles = -1, q_tpg = 1, q_ga = 0, q_gb = 0;
     while (ok) {   // ---- Alg. 3 line 5: while any hypothesis is active
-        build_list(S, S.active, G, S.act_list, &S.n_act);
+        if (!(kPlain && have_act)) build_list(S, S.active, G, S.act_list, &S.n_act);
         const int n_act = S.n_act;
         if (n_act == 0) break;
         if (tid == 0) {
@@ -482,13 +518,23 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             const float *src_b = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L) * Bw * Hp : nullptr;
             // (projections on the fly: only the recurrent product is left here)
             const int NT_A = ONTHEFLY ? 0 : (H + CT - 1) / CT, NT_B = lstm ? (Hp + 3) / 4 : 0;
-            // fewest tiles per work item that give every workgroup at most one item
-            int tpg = max(1, ((NT_A + NT_B) * n_tiles_a + C - 1) / C);
-            while (((NT_A + tpg - 1) / tpg + (NT_B + tpg - 1) / tpg) * n_tiles_a > C && tpg < NT_A + NT_B) ++tpg;
-            const int g_a = (NT_A + tpg - 1) / tpg, g_b = (NT_B + tpg - 1) / tpg;
+            if (n_tiles_a != q_for_tiles) {
+                // fewest tiles per work item that give every workgroup at most one item
+                int t = max(1, ((NT_A + NT_B) * n_tiles_a + C - 1) / C);
+                while (((NT_A + t - 1) / t + (NT_B + t - 1) / t) * n_tiles_a > C && t < NT_A + NT_B) ++t;
+                q_tpg = t;
+                q_ga = (NT_A + t - 1) / t;
+                q_gb = (NT_B + t - 1) / t;
+                q_for_tiles = n_tiles_a;
+            }
+            const int tpg = q_tpg, g_a = q_ga, g_b = q_gb;
             const int n_grp = g_a + g_b;
             for (int it = rank; it < n_tiles_a * n_grp; it += C) {
-                const int ti = it / n_grp, grp = it % n_grp;
+                int ti = 0, grp = it;   // one row tile: the item index is the group
+                if (n_tiles_a > 1) {
+                    ti = it / n_grp;
+                    grp = it - ti * n_grp;
+                }
                 const bool sec_b = grp >= g_a;
                 const int nrows = min(RT, n_act - ti * RT);
                 const int tile0 = (sec_b ? grp - g_a : grp) * tpg;
@@ -573,49 +619,43 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 if (S.active[g]) atomicMin(&S.t_sync, S.time[g]);
             __syncthreads();
         }
-        // every active hypothesis now searches for its next non-blank label
-        for (int g = tid; g < G; g += kThreads) {
-            bool a = S.active[g];
-            if (a && chunked && (S.time[g] >= S.len[g] || (S.status[g] & TDT_HYP_TRUNCATED))) {
-                a = false;   // had only stayed for the predictor step of its last label
-                S.active[g] = 0;
+        // Every active hypothesis now searches for its next non-blank label: the first joint pass
+        // of the iteration takes the list of active hypotheses as it stands (the search flags of
+        // everybody else are clear, and the decision step sets those of the listed ones).
+        const int *jl = S.act_list;   // who searches in the coming pass
+        int n_need = n_act;
+        if constexpr (!kPlain) {
+            for (int g = tid; g < G; g += kThreads) {
+                bool a = S.active[g];
+                if (a && chunked && (S.time[g] >= S.len[g] || (S.status[g] & TDT_HYP_TRUNCATED))) {
+                    a = false;   // had only stayed for the predictor step of its last label
+                    S.active[g] = 0;
+                }
+                if (FRAMELOOP) {
+                    a = a && S.time[g] == S.t_sync;
+                    S.commit[g] = 0;   // this step's predictor pass has used it; a new label sets it again
+                }
+                S.need[g] = a;
             }
-            if (FRAMELOOP) {
-                a = a && S.time[g] == S.t_sync;
-                S.commit[g] = 0;   // this step's predictor pass has used it; a new label sets it again
-            }
-            S.need[g] = a;
+            __syncthreads();
+            build_list(S, S.need, G, S.need_list, &S.n_need);
+            jl = S.need_list;
+            n_need = S.n_need;
         }
-        __syncthreads();
-        build_list(S, S.need, G, S.need_list, &S.n_need);
 
         // ---- inner loop (Alg. 3 line 12): joint passes until nobody searches any more
-        while (S.n_need > 0) {
-            const int n_need = S.n_need;
+        while (n_need > 0) {
             const int NT = (O + CT - 1) / CT;
-            int Kw = FRAMELOOP ? 1 : p.window;   // Alg. 2 looks at one frame per step
-            if (Kw <= 0) {
-                Kw = auto_rows / n_need;
-                if (Kw < 3) Kw = 3;
-            }
-            if (Kw > kMaxWindow) Kw = kMaxWindow;
-            if (Kw * n_need > rows_cap) Kw = rows_cap / n_need;
+            const JointPlan jp = S.jplan[n_need];
+            const int Kw = jp.Kw, n_tiles = jp.n_tiles, n_cg = jp.n_cg, tpg = jp.tpg;
             const int M = n_need * Kw;
-            const int n_tiles = (M + RT - 1) / RT;
-            int n_cg, tpg;
-            split_tiles(C, n_tiles, NT, max_cg, n_cg, tpg);
             LsePartial *pbuf = pbase + (size_t)(jpass & 1u) * kPartialEntries;
             unsigned long long *row_lab = rl_base + (size_t)(jpass % kRowBufs) * rows_cap;
             unsigned long long *row_dur = rd_base + (size_t)(jpass % kRowBufs) * rows_cap;
-            {   // clear the argmax cells of the next pass; their last readers finished before
-                // the barrier that precedes this pass
-                unsigned long long *nl = rl_base + (size_t)((jpass + 1) % kRowBufs) * rows_cap;
-                unsigned long long *nd = rd_base + (size_t)((jpass + 1) % kRowBufs) * rows_cap;
-                for (int r = rank * kThreads + tid; r < rows_cap; r += C * kThreads) {
-                    st_co64(nl + r, 0ull);
-                    if (D > 0) st_co64(nd + r, 0ull);
-                }
-            }
+            // argmax cells to clear while this pass's barrier completes: those of the pass after
+            // the next (see below)
+            unsigned long long *clear_lab = rl_base + (size_t)((jpass + 2) % kRowBufs) * rows_cap;
+            unsigned long long *clear_dur = rd_base + (size_t)((jpass + 2) % kRowBufs) * rows_cap;
             ++jpass;
             if (tid == 0) {
                 S.st[2] += 1;
@@ -646,7 +686,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     // frame of joint row r, or -1 if it lies beyond its hypothesis' last frame
                     auto row_frame = [&](int r, int &g) {
                         const int q = r / Kw;
-                        g = S.need_list[q];
+                        g = jl[q];
                         const int f = S.time[g] + (r - q * Kw);
                         return f < S.len[g] ? f : -1;
                     };
@@ -674,14 +714,14 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             } else if (lstm) {
                                 stage_segment<WT>(
                                     A, sg.K, nrows,
-                                    [&](int i) { return src_h + (size_t)(b0 + S.need_list[ti * RT + i]) * Hp + k0; },
+                                    [&](int i) { return src_h + (size_t)(b0 + jl[ti * RT + i]) * Hp + k0; },
                                     [](const float *row, int k) { return ld_co2(row + k); },
                                     [](const float *, int, float2 v) { return v; });
                             } else {
                                 stage_segment<WT>(
                                     A, sg.K, nrows,
                                     [&](int i) {
-                                        const int g = S.need_list[ti * RT + i];
+                                        const int g = jl[ti * RT + i];
                                         return make_int2(S.last[g], S.last2[g]);
                                     },
                                     [&](int2 lab, int k) {
@@ -706,7 +746,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 if (i >= nrows || col >= H) continue;
                                 const float v = cpart_sum(S, t, ksplit, i, j) + S.bias[t * CT + j];
                                 if (sec_p) {
-                                    st_co(p.pred_proj + (size_t)(b0 + S.need_list[ti * RT + i]) * H + col, v);
+                                    st_co(p.pred_proj + (size_t)(b0 + jl[ti * RT + i]) * H + col, v);
                                 } else {
                                     int g;
                                     const int f = row_frame(ti * RT + i, g);
@@ -731,7 +771,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             in.w1 = nullptr;
             in.K1 = 0;
             for (int it = rank; it < n_tiles * n_cg; it += C) {
-                const int ti = it / n_cg, cg = it % n_cg;
+                int ti = jp.ti0, cg = jp.cg0;   // the first item is tabulated
+                if (it != rank) {
+                    ti = it / n_cg;
+                    cg = it - ti * n_cg;
+                }
                 const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
                 // running statistics of row tid / 32 over this item's columns (lanes 0 and 32)
                 float rm = -INFINITY, rs = 0.0f, rdm = -INFINITY;
@@ -745,7 +789,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             [&](int i) {
                                 const int r = ti * RT + i;
                                 const int q = r / Kw;
-                                const int g = S.need_list[q];
+                                const int g = jl[q];
                                 const int f = S.time[g] + (r - q * Kw);
                                 JointRow c;
                                 c.valid = f < S.len[g];
@@ -840,7 +884,20 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             if (!ok) break;
             TR(22);
             lap(kTkJ);
-            ok = cluster_barrier(S, bi, p.abort_flag, C, p.timeout_ticks);
+            barrier_arrive(bi, C);
+            // While the arrivals travel: clear the argmax cells of the pass after the next.  Of
+            // the four rotating buffers that one was last read by the decision step two passes
+            // ago, which every workgroup had left before it arrived at the previous pass's
+            // barrier; and its next writers start behind the next pass's barrier, at which this
+            // workgroup arrives only after these stores have completed.
+            for (int r = rank * kThreads + tid; r < rows_cap; r += C * kThreads) {
+                st_co64(clear_lab + r, 0ull);
+                if (D > 0) st_co64(clear_dur + r, 0ull);
+            }
+            // ... and add the score terms the previous pass left pending (their loads were
+            // complete before the arrival)
+            finish_scores();
+            ok = barrier_wait(S, bi, p.abort_flag, C, p.timeout_ticks);
             lap(kTkBar);
             if (!ok) break;
 
@@ -858,8 +915,6 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         if (D > 0) bd[e] = ld_co64(row_dur + (r < M ? r : 0));
                     }
                 }
-                // while they are in flight: the score terms the previous pass left pending
-                finish_scores();
 #pragma unroll
                 for (int e = 0; e < kMaxRowsPerPass / kThreads; ++e) {
                     const int r = tid + e * kThreads;
@@ -874,7 +929,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             TR(40);
             // the walk through the window of one searching hypothesis (all lanes of a wavefront)
             auto walk = [&](int q, int &w) -> bool {
-                const int g = S.need_list[q];
+                const int g = jl[q];
                 const int nv = min(Kw, S.len[g] - S.time[g]);   // >= 1: a searching row has frames left
                 int a = V, dstep = 0;
                 if (lane < nv) {
@@ -897,7 +952,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             };
             // the state update of one hypothesis (one thread): Alg. 3 line 20, Sec. 3.1 add_results
             auto apply = [&](int q, bool found, int w) {
-                const int g = S.need_list[q];
+                const int g = jl[q];
                 const int t0 = S.time[g], len = S.len[g];
                 int sym = (w > 0 || !found) ? 0 : S.sym[g];
                 if (found) {
@@ -946,7 +1001,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             pend_u[j] = ld_co64(reinterpret_cast<const unsigned long long *>(
                                 pbuf + (size_t)(q * Kw + w) * n_cg + lane));
                         if (lane == 0) {
-                            S.pend_g[q] = S.need_list[q];
+                            S.pend_g[q] = jl[q];
                             S.pend_found[q] = found;
                             S.pend_m[q] = found ? S.row_m[q * Kw + w] : 0.0f;
                             apply(q, found, w);
@@ -985,13 +1040,16 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     for (int off = seg >> 1; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
                     if (live && cg == 0) {
                         // log_softmax at the maximum = -log(sum exp(l - max))
-                        if (found) S.score[S.need_list[q]] -= logf(part);
+                        if (found) S.score[jl[q]] -= logf(part);
                         apply(q, found, w);
                     }
                 }
             }
             __syncthreads();
-            build_list(S, S.need, G, S.need_list, &S.n_need);
+            build_two_lists(S, G, S.need, S.need_list, &S.n_need, S.active, S.act_list, &S.n_act);
+            have_act = true;
+            jl = S.need_list;
+            n_need = S.n_need;
             TR(5);
             lap(kTkD);
             if (FRAMELOOP) break;   // Alg. 2: the next step starts with the predictor again
@@ -1189,6 +1247,7 @@ hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, DecodeVa
     const size_t lds = lds_bytes_for(w, v.on_the_fly);
     DecodeParams pc = p;
     pc.kseg_max = kseg_max_for(w, v.on_the_fly);
+    pc.lds_bytes = (int)lds;
     void *args[] = {&pc};
     const void *fn = kernel_for(w, v);
     // cooperative launch: the runtime refuses a grid whose workgroups cannot all be

@@ -52,6 +52,14 @@ constexpr int kDeferPerWave = 4;                     // hypotheses per wavefront
 constexpr int kDeferred = kDeferPerWave * kWaves;
 constexpr int kTabPerThread = kWaves * RT * CT / kThreads;
 
+// How a joint pass with n searching hypotheses is cut: frames per hypothesis, row tiles, groups
+// of column tiles and tiles per group, and the first work item of this workgroup.  A function
+// of n only (for fixed options), so it is tabulated once when the kernel starts.
+struct JointPlan {
+    short Kw, n_tiles, n_cg, ti0;
+    int tpg, cg0;
+};
+
 struct HypShared {
     int gid[kMaxHypsPerCluster];     // the caller's index of the hypothesis in each slot
     int len[kMaxHypsPerCluster];
@@ -72,13 +80,14 @@ struct HypShared {
     int need_list[kMaxHypsPerCluster];
     int n_act, n_need;
     int t_sync;                      // frame-looping: the frame index the batch is looking at
-    int wave_cnt[kWaves];
+    int wave_cnt[kWaves], wave_cnt2[kWaves];
     int durations[TDT_MAX_DURATIONS];
     float cpart[kWaves][RT][CP_LD];  // per-wavefront 16x16 partial results of one round
     float bias[kWaves * CT];         // biases of the columns of the current round
     int row_a[kMaxRowsPerPass];      // per joint row: argmax label (V = blank)
     int row_d[kMaxRowsPerPass];      //                frame step of the argmax duration class
     float row_m[kMaxRowsPerPass];    //                largest label logit
+    JointPlan jplan[kMaxHypsPerCluster + 1];   // by number of searching hypotheses
     int dec_w[kMaxHypsPerCluster];   // per searching hypothesis: window offset the walk stopped at
     unsigned char dec_found[kMaxHypsPerCluster];   // ... on a non-blank label
     int pend_n, pend_ncg;            // hypotheses whose score term is still in flight

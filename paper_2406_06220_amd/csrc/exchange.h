@@ -161,6 +161,36 @@ __device__ inline void build_list(HypShared &S, const unsigned char *flag, int G
     __syncthreads();
 }
 
+// build_list for two flag arrays at once (one pair of workgroup barriers for both)
+__device__ inline void build_two_lists(HypShared &S, int G, const unsigned char *flag_a, int *list_a, int *n_a,
+                                       const unsigned char *flag_b, int *list_b, int *n_b)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool fa = tid < G && flag_a[tid] != 0, fb = tid < G && flag_b[tid] != 0;
+    const unsigned long long ma = __ballot(fa), mb = __ballot(fb);
+    if (lane == 0) {
+        S.wave_cnt[wave] = __popcll(ma);
+        S.wave_cnt2[wave] = __popcll(mb);
+    }
+    __syncthreads();
+    int off_a = 0, tot_a = 0, off_b = 0, tot_b = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const int ca = S.wave_cnt[w], cb = S.wave_cnt2[w];
+        if (w < wave) { off_a += ca; off_b += cb; }
+        tot_a += ca;
+        tot_b += cb;
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    if (fa) list_a[off_a + __popcll(ma & below)] = tid;
+    if (fb) list_b[off_b + __popcll(mb & below)] = tid;
+    if (tid == 0) {
+        *n_a = tot_a;
+        *n_b = tot_b;
+    }
+    __syncthreads();
+}
+
 // deal `n_units` column tiles to the workgroups left after `n_row_tiles` took theirs
 __device__ inline void split_tiles(int C, int n_row_tiles, int n_units, int max_groups, int &n_groups,
                                    int &per_group)

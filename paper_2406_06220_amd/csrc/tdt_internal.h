@@ -20,7 +20,7 @@ constexpr int kXcds = 8;                      // accelerator dies of an MI355X; 
 constexpr int kBarrierStride = 32;            // uint32 slots between two workgroups' barrier flags
 constexpr int kMaxRankedBatch = 1024;          // largest batch whose hypotheses are dealt to the clusters by length
 constexpr int kMaxDuration = 1 << 20;          // largest frame increment of a duration class
-constexpr int kRowBufs = 3;                   // rotating per-row argmax buffers
+constexpr int kRowBufs = 4;                   // rotating per-row argmax buffers
 
 // Softmax-denominator share of one slice of label columns for one joint row.
 struct __align__(8) LsePartial {
@@ -37,6 +37,7 @@ struct DecodeParams {
     int window;            // 0 = automatic
     int joint_tiles;       // column tiles per joint work item the automatic window aims at (0 = 4)
     int kseg_max;          // longest K segment staged at once (set by launch_decode)
+    int lds_bytes;         // dynamic LDS of the launch, a multiple of 16 (set by launch_decode)
     int n_clusters, hyps_per_cluster;
     int frame_loop;        // non-zero: batched frame-looping (Algorithm 2) instead of label-looping
     int selftest_stall;    // non-zero: rank 0 of cluster 0 withholds its first barrier arrival

@@ -62,9 +62,11 @@ template <> struct ActTile<float> {
 // loads and mix only computes: all loads of a wavefront are issued before the first loaded
 // value is used, so that their latencies overlap (a use between two loads makes the
 // compiler wait for the first load before it issues the second, and so does a load inside
-// a conditional block).  For the same reason load is called for every slot -- rows beyond
-// nrows re-read row 0, steps beyond K re-read the last step -- and what it returned there
-// is dropped afterwards.
+// a block that depends on the lane).  For the same reason load is called for every step of a
+// row -- steps beyond K re-read the last step -- and what it returned there is dropped
+// afterwards.  Rows beyond nrows are skipped altogether (the condition is the same for all
+// lanes of a wavefront): the tile keeps whatever those rows held, their products are never
+// looked at, and a row of the product depends on no other row of the tile.
 template <typename WT, int KIT, typename CtxF, typename LoadF, typename MixF>
 __device__ inline void stage_segment_impl(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
 {
@@ -80,20 +82,23 @@ __device__ inline void stage_segment_impl(const ActTile<WT> &A, int K, int nrows
     decltype(load(c[0], 0)) v[RPW][KIT];
 #pragma unroll
     for (int ii = 0; ii < RPW; ++ii)
+        if (wave + ii * kWaves < nrows) {
 #pragma unroll
-        for (int kk = 0; kk < KIT; ++kk) {
-            const int k = lane * 2 + kk * 128;
-            v[ii][kk] = load(c[ii], k < K ? k : K - 2);
+            for (int kk = 0; kk < KIT; ++kk) {
+                const int k = lane * 2 + kk * 128;
+                v[ii][kk] = load(c[ii], k < K ? k : K - 2);
+            }
         }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ii = 0; ii < RPW; ++ii)
+        if (wave + ii * kWaves < nrows) {
 #pragma unroll
-        for (int kk = 0; kk < KIT; ++kk) {
-            const int i = wave + ii * kWaves, k = lane * 2 + kk * 128;
-            const bool ok = i < nrows && k < K;
-            const float2 x = mix(c[ii], k < K ? k : K - 2, v[ii][kk]);
-            if (k < Kpad) A.store2(i, k, make_float2(ok ? x.x : 0.0f, ok ? x.y : 0.0f));
+            for (int kk = 0; kk < KIT; ++kk) {
+                const int i = wave + ii * kWaves, k = lane * 2 + kk * 128;
+                const float2 x = mix(c[ii], k < K ? k : K - 2, v[ii][kk]);
+                if (k < Kpad) A.store2(i, k, make_float2(k < K ? x.x : 0.0f, k < K ? x.y : 0.0f));
+            }
         }
 }
 
