@@ -167,24 +167,43 @@ __device__ inline void tile_accumulate(const ActTile<uint16_t> &A, const Seg &sg
 {
     const uint16_t *a0 = A.planes + (size_t)(lane & 15) * A.ldb + wc.kq;
     const size_t plane = (size_t)RT * A.ldb;
-    for (int c0 = 0; c0 < wc.n_my; c0 += CH) {
+    const int n_my = __builtin_amdgcn_readfirstlane(wc.n_my);   // the same in every lane
+    // the last k-step this wavefront may read activations of (steps beyond its share re-read it)
+    const int s_last = kpart + (n_my > 0 ? n_my - 1 : 0) * ksplit;
+    // One accumulator per plane of the split: three independent chains of products instead of
+    // one, added up at the end.
+    f32x4 acc1 = f32x4{0.0f, 0.0f, 0.0f, 0.0f}, acc2 = acc1;
+    for (int c0 = 0; c0 < n_my; c0 += CH) {
         if (c0 > 0 || !have_first) weight_prefetch(wc, sg, kpart, ksplit, c0, b);
+        // Every chunk runs all CH steps without a branch: a step beyond this wavefront's share
+        // multiplies by zeros.  The activation fragments of step j + 1 are requested from LDS
+        // before the products of step j are issued.
+        bf16x8 x[2][3];
+        {
+            const int s = min(kpart + c0 * ksplit, s_last);
+            x[0][0] = *reinterpret_cast<const bf16x8 *>(a0 + s * 32);
+            x[0][1] = *reinterpret_cast<const bf16x8 *>(a0 + plane + s * 32);
+            x[0][2] = *reinterpret_cast<const bf16x8 *>(a0 + 2 * plane + s * 32);
+        }
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
-            if (c0 + j < wc.n_my) {
-                const int s = kpart + (c0 + j) * ksplit;
-                const bool ok = wc.live && s * 32 + wc.kq < sg.K;
-                const uint4 m = make_uint4(ok ? b[j].x : 0u, ok ? b[j].y : 0u, ok ? b[j].z : 0u, ok ? b[j].w : 0u);
-                const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&m);
-                const bf16x8 x0 = *reinterpret_cast<const bf16x8 *>(a0 + s * 32);
-                const bf16x8 x1 = *reinterpret_cast<const bf16x8 *>(a0 + plane + s * 32);
-                const bf16x8 x2 = *reinterpret_cast<const bf16x8 *>(a0 + 2 * plane + s * 32);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x0, bv, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x1, bv, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x2, bv, acc, 0, 0, 0);
+            if (j + 1 < CH) {
+                const int sn = min(kpart + (c0 + j + 1) * ksplit, s_last);
+                x[(j + 1) & 1][0] = *reinterpret_cast<const bf16x8 *>(a0 + sn * 32);
+                x[(j + 1) & 1][1] = *reinterpret_cast<const bf16x8 *>(a0 + plane + sn * 32);
+                x[(j + 1) & 1][2] = *reinterpret_cast<const bf16x8 *>(a0 + 2 * plane + sn * 32);
             }
+            const int s = kpart + (c0 + j) * ksplit;
+            const bool ok = wc.live && c0 + j < n_my && s * 32 + wc.kq < sg.K;
+            const uint4 m = make_uint4(ok ? b[j].x : 0u, ok ? b[j].y : 0u, ok ? b[j].z : 0u, ok ? b[j].w : 0u);
+            const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&m);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][0], bv, acc, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][1], bv, acc1, 0, 0, 0);
+            acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][2], bv, acc2, 0, 0, 0);
         }
     }
+    // smallest terms first
+    acc = acc + (acc1 + acc2);
 }
 
 template <typename WT> struct Backend;
