@@ -173,8 +173,10 @@ enum tdt_stat {
     TDT_STAT_OUTER_MAX = 4,   /* largest number of label-loop iterations of any group */
     TDT_STAT_ABORT = 5,       /* non-zero if an internal wait timed out (the hypotheses of the groups
                                  concerned carry TDT_HYP_ABORTED in out_status) */
-    /* where the first hypothesis group's time went, in ticks of the device wall clock
-       (hipDeviceAttributeWallClockRate): predictor, projection, joint, decision, waits, all */
+    /* library builds with phase timers only (-DTDT_PHASE_TIMERS=1; zero otherwise, because
+       keeping them costs a microsecond or two per label): where the first hypothesis group's
+       time went, in ticks of the device wall clock (hipDeviceAttributeWallClockRate):
+       predictor, projection, joint, decision, waits, all */
     TDT_STAT_TICKS_PRED = 8,
     TDT_STAT_TICKS_PROJ = 9,
     TDT_STAT_TICKS_JOINT = 10,

@@ -233,11 +233,16 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 
     enum { kTkP = 0, kTkQ, kTkJ, kTkD, kTkBar };
     if (tid == 0) {
-        for (int a = 0; a < 5; ++a) S.st[a] = S.tk[a] = 0;
+        for (int a = 0; a < 5; ++a) S.tk[a] = 0;
         S.tk_last = S.tk_start = wall_clock64();
     }
-    auto lap = [&](int bucket) {   // thread 0 books the time since the last call
-        if (tid == 0) {
+    // work counters: the same in every thread, so they live in scalar registers
+    long long st_pred_passes = 0, st_pred_rows = 0, st_joint_passes = 0, st_joint_rows = 0;
+    // Thread 0 books the time since the last call -- in profiling builds only: every call is a
+    // clock read and an LDS update that the other wavefronts wait for at the next barrier, about
+    // ten of them per label.
+    auto lap = [&](int bucket) {
+        if (TDT_PHASE_TIMERS && tid == 0) {
             const long long now = wall_clock64();
             S.tk[bucket] += now - S.tk_last;
             S.tk_last = now;
@@ -341,10 +346,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         if (!(kPlain && have_act)) build_list(S, S.active, G, S.act_list, &S.n_act);
         const int n_act = S.n_act;
         if (n_act == 0) break;
-        if (tid == 0) {
-            S.st[4] += 1;
-            S.st[0] += 1;
-        }
+        st_pred_passes += 1;
         const int n_tiles_a = (n_act + RT - 1) / RT;
         // Who takes the predictor step: every active hypothesis -- except in the first
         // iteration of a chunk, where the hypotheses that bring a state along keep it and
@@ -376,11 +378,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         const int n_tiles_p = (n_p + RT - 1) / RT;
 
 #if TDT_TRACE
-        if (tid == 0) g_tr_on = (S.st[4] >= 20 && S.st[4] < 24);
+        if (tid == 0) g_tr_on = (st_pred_passes >= 20 && st_pred_passes < 24);
 #endif
         TR(1);
         // ---- P: predictor step (Alg. 3 line 6)
-        if (tid == 0) S.st[1] += n_p;
+        st_pred_rows += n_p;
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 0;
         phase_bucket = kTkP;
         if (lstm) {
@@ -657,10 +659,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             unsigned long long *clear_lab = rl_base + (size_t)((jpass + 2) % kRowBufs) * rows_cap;
             unsigned long long *clear_dur = rd_base + (size_t)((jpass + 2) % kRowBufs) * rows_cap;
             ++jpass;
-            if (tid == 0) {
-                S.st[2] += 1;
-                S.st[3] += M;
-            }
+            st_joint_passes += 1;
+            st_joint_rows += M;
 
             if constexpr (ONTHEFLY) {
                 // ---- the projections of this pass's rows into the joint space, as Sec. 3.4 has
@@ -1101,13 +1101,14 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             auto add = [&](int slot, long long v) {
                 atomicAdd((unsigned long long *)&p.out_stats[slot], (unsigned long long)v);
             };
-            add(TDT_STAT_PRED_PASSES, S.st[0]);
-            add(TDT_STAT_PRED_ROWS, S.st[1]);
-            add(TDT_STAT_JOINT_PASSES, S.st[2]);
-            add(TDT_STAT_JOINT_ROWS, S.st[3]);
-            atomicMax((unsigned long long *)&p.out_stats[TDT_STAT_OUTER_MAX], (unsigned long long)S.st[4]);
+            add(TDT_STAT_PRED_PASSES, st_pred_passes);
+            add(TDT_STAT_PRED_ROWS, st_pred_rows);
+            add(TDT_STAT_JOINT_PASSES, st_joint_passes);
+            add(TDT_STAT_JOINT_ROWS, st_joint_rows);
+            // every label-loop iteration takes one predictor pass
+            atomicMax((unsigned long long *)&p.out_stats[TDT_STAT_OUTER_MAX], (unsigned long long)st_pred_passes);
             if (!ok) add(TDT_STAT_ABORT, 1);
-            if (cl == 0) {   // where the first cluster's time went, in wall-clock ticks
+            if (TDT_PHASE_TIMERS && cl == 0) {   // where the first cluster's time went, in wall-clock ticks
                 add(TDT_STAT_TICKS_PRED, S.tk[kTkP]);
                 add(TDT_STAT_TICKS_PROJ, S.tk[kTkQ]);
                 add(TDT_STAT_TICKS_JOINT, S.tk[kTkJ]);

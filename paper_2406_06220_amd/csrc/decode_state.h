@@ -7,10 +7,15 @@
 
 #include "tdt_internal.h"
 
-// 1: thread 0 also times staging / multiply / epilogue inside each work item (costs a
-// little; for profiling builds)
+// Profiling builds.  TDT_PHASE_TIMERS=1: thread 0 of the first hypothesis group books the device
+// wall clock per phase (predictor, projection, joint, decision, waits) into the statistics; it
+// costs one to two microseconds per label, so the default build leaves the entries at zero.
+// TDT_FINE_TIMERS=1 (implies the former): also staging / multiply / epilogue inside each work item.
 #ifndef TDT_FINE_TIMERS
 #define TDT_FINE_TIMERS 0
+#endif
+#ifndef TDT_PHASE_TIMERS
+#define TDT_PHASE_TIMERS TDT_FINE_TIMERS
 #endif
 
 // 1: profiling build.  Thread 0 of workgroup 0 records (event id, device wall clock) pairs of a
@@ -96,7 +101,6 @@ struct HypShared {
     unsigned char pend_found[kDeferred];
     int aborted;
     // kept by thread 0 only: work counters and wall-clock ticks per phase
-    long long st[5];   // predictor passes, predictor rows, joint passes, joint rows, label-loop iterations
     long long tk[5];   // P, Q, J, D, barrier
     long long tk_last, tk_start;
     // thread 0 (profiling builds): ticks spent staging / multiplying / in epilogues, per phase P, Q, J

@@ -149,7 +149,7 @@ __device__ inline WeightCursor weight_cursor(const Seg &sg, long long wrow, int 
 }
 
 // Loads are unconditional (address clamped into the row) and nothing uses a fragment before
-// all CH loads have been issued; what a clamped load fetched is masked where it is used.
+// all CH loads have been issued.
 __device__ inline void weight_prefetch(const WeightCursor &wc, const Seg &sg, int kpart, int ksplit, int c0,
                                        uint4 (&b)[CH])
 {
@@ -165,38 +165,47 @@ __device__ inline void tile_accumulate(const ActTile<uint16_t> &A, const Seg &sg
                                        int kpart, int ksplit, uint4 (&b)[CH], bool have_first, f32x4 &acc,
                                        int lane)
 {
-    const uint16_t *a0 = A.planes + (size_t)(lane & 15) * A.ldb + wc.kq;
+    const uint16_t *arow = A.planes + (size_t)(lane & 15) * A.ldb;
     const size_t plane = (size_t)RT * A.ldb;
     const int n_my = __builtin_amdgcn_readfirstlane(wc.n_my);   // the same in every lane
-    // the last k-step this wavefront may read activations of (steps beyond its share re-read it)
-    const int s_last = kpart + (n_my > 0 ? n_my - 1 : 0) * ksplit;
+    // Nothing is masked.  A weight fragment beyond the end of its row (K no multiple of 32) or of
+    // a column that is padding was fetched from a clamped, valid address: the first meets
+    // activation zeros (the tile is zero from K up to a multiple of 32), the second lands in a
+    // column no epilogue looks at.  A step beyond the wavefront's share reads, as its activation
+    // fragment, the padding at the end of each tile row, which nothing ever writes and which is
+    // zero from the start of the kernel.
+    const int zoff = A.ldb - 8;
+    auto aoff = [&](int c) { return c < n_my ? (kpart + c * ksplit) * 32 + wc.kq : zoff; };
     // One accumulator per plane of the split: three independent chains of products instead of
     // one, added up at the end.
     f32x4 acc1 = f32x4{0.0f, 0.0f, 0.0f, 0.0f}, acc2 = acc1;
     for (int c0 = 0; c0 < n_my; c0 += CH) {
-        if (c0 > 0 || !have_first) weight_prefetch(wc, sg, kpart, ksplit, c0, b);
-        // Every chunk runs all CH steps without a branch: a step beyond this wavefront's share
-        // multiplies by zeros.  The activation fragments of step j + 1 are requested from LDS
-        // before the products of step j are issued.
+        if (c0 > 0 || !have_first) {
+            TR(50);
+            weight_prefetch(wc, sg, kpart, ksplit, c0, b);
+#if TDT_TRACE
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            TR(51);
+#endif
+        }
+        // the activation fragments of step j + 1 are requested from LDS before the products of
+        // step j are issued
         bf16x8 x[2][3];
         {
-            const int s = min(kpart + c0 * ksplit, s_last);
-            x[0][0] = *reinterpret_cast<const bf16x8 *>(a0 + s * 32);
-            x[0][1] = *reinterpret_cast<const bf16x8 *>(a0 + plane + s * 32);
-            x[0][2] = *reinterpret_cast<const bf16x8 *>(a0 + 2 * plane + s * 32);
+            const uint16_t *a = arow + aoff(c0);
+            x[0][0] = *reinterpret_cast<const bf16x8 *>(a);
+            x[0][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
+            x[0][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
         }
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
             if (j + 1 < CH) {
-                const int sn = min(kpart + (c0 + j + 1) * ksplit, s_last);
-                x[(j + 1) & 1][0] = *reinterpret_cast<const bf16x8 *>(a0 + sn * 32);
-                x[(j + 1) & 1][1] = *reinterpret_cast<const bf16x8 *>(a0 + plane + sn * 32);
-                x[(j + 1) & 1][2] = *reinterpret_cast<const bf16x8 *>(a0 + 2 * plane + sn * 32);
+                const uint16_t *a = arow + aoff(c0 + j + 1);
+                x[(j + 1) & 1][0] = *reinterpret_cast<const bf16x8 *>(a);
+                x[(j + 1) & 1][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
+                x[(j + 1) & 1][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
             }
-            const int s = kpart + (c0 + j) * ksplit;
-            const bool ok = wc.live && c0 + j < n_my && s * 32 + wc.kq < sg.K;
-            const uint4 m = make_uint4(ok ? b[j].x : 0u, ok ? b[j].y : 0u, ok ? b[j].z : 0u, ok ? b[j].w : 0u);
-            const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&m);
+            const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&b[j]);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][0], bv, acc, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][1], bv, acc1, 0, 0, 0);
             acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][2], bv, acc2, 0, 0, 0);
