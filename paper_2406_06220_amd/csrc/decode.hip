@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     extern __shared__ __align__(16) unsigned char dyn_lds[];
     __shared__ HypShared S;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ncl = p.n_clusters;
     const int C = gridDim.x / ncl;
     // Workgroups go to the chip's kXcds dies round-robin by blockIdx, and each die has its own

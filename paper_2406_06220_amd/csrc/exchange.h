@@ -144,7 +144,7 @@ __device__ inline bool cluster_barrier(HypShared &S, BarrierInfo &bi, int *abort
 __device__ inline void build_list(HypShared &S, const unsigned char *flag, int G, int *list,
                                   int *n_out)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool f = tid < G && flag[tid] != 0;
     const unsigned long long m = __ballot(f);
     if (lane == 0) S.wave_cnt[wave] = __popcll(m);
@@ -165,7 +165,7 @@ __device__ inline void build_list(HypShared &S, const unsigned char *flag, int G
 __device__ inline void build_two_lists(HypShared &S, int G, const unsigned char *flag_a, int *list_a, int *n_a,
                                        const unsigned char *flag_b, int *list_b, int *n_b)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool fa = tid < G && flag_a[tid] != 0, fb = tid < G && flag_b[tid] != 0;
     const unsigned long long ma = __ballot(fa), mb = __ballot(fb);
     if (lane == 0) {

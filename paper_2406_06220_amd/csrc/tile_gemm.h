@@ -70,7 +70,7 @@ template <> struct ActTile<float> {
 template <typename WT, int KIT, typename CtxF, typename LoadF, typename MixF>
 __device__ inline void stage_segment_impl(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int Kpad = ((K + 31) / 32) * 32;
     constexpr int RPW = RT / kWaves;    // rows per wavefront
     decltype(ctx(0)) c[RPW];
@@ -161,54 +161,61 @@ __device__ inline void weight_prefetch(const WeightCursor &wc, const Seg &sg, in
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// the products of one chunk of CH k-steps (from step c0 of this wavefront's share) with the
+// weight fragments b.  Nothing is masked.  A weight fragment beyond the end of its row (K no
+// multiple of 32) or of a column that is padding was fetched from a clamped, valid address: the
+// first meets activation zeros (the tile is zero from K up to a multiple of 32), the second
+// lands in a column no epilogue looks at.  A step beyond the wavefront's share reads, as its
+// activation fragment, the padding at the end of each tile row, which nothing ever writes and
+// which is zero from the start of the kernel.  The activation fragments of step j + 1 are
+// requested from LDS before the products of step j are issued.
+__device__ inline void chunk_products(const uint16_t *arow, size_t plane, int zoff, int kq, int kpart, int ksplit,
+                                      int c0, int n_my, const uint4 (&b)[CH], f32x4 &acc0, f32x4 &acc1, f32x4 &acc2)
+{
+    auto aoff = [&](int c) { return c < n_my ? (kpart + c * ksplit) * 32 + kq : zoff; };
+    bf16x8 x[2][3];
+    {
+        const uint16_t *a = arow + aoff(c0);
+        x[0][0] = *reinterpret_cast<const bf16x8 *>(a);
+        x[0][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
+        x[0][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
+    }
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        if (j + 1 < CH) {
+            const uint16_t *a = arow + aoff(c0 + j + 1);
+            x[(j + 1) & 1][0] = *reinterpret_cast<const bf16x8 *>(a);
+            x[(j + 1) & 1][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
+            x[(j + 1) & 1][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
+        }
+        const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&b[j]);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][0], bv, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][1], bv, acc1, 0, 0, 0);
+        acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][2], bv, acc2, 0, 0, 0);
+    }
+}
+
+// b holds the wavefront's first chunk of weight fragments, b2 its second (if it has one): the
+// first was requested before the item waited for its rows, the second as soon as the registers
+// of the staged rows were free again, so that it travels while the first is multiplied.
+// Further chunks are requested into a buffer as soon as its products have been issued.
 __device__ inline void tile_accumulate(const ActTile<uint16_t> &A, const Seg &sg, const WeightCursor &wc,
-                                       int kpart, int ksplit, uint4 (&b)[CH], bool have_first, f32x4 &acc,
-                                       int lane)
+                                       int kpart, int ksplit, uint4 (&b)[CH], uint4 (&b2)[CH], f32x4 &acc, int lane)
 {
     const uint16_t *arow = A.planes + (size_t)(lane & 15) * A.ldb;
     const size_t plane = (size_t)RT * A.ldb;
-    const int n_my = __builtin_amdgcn_readfirstlane(wc.n_my);   // the same in every lane
-    // Nothing is masked.  A weight fragment beyond the end of its row (K no multiple of 32) or of
-    // a column that is padding was fetched from a clamped, valid address: the first meets
-    // activation zeros (the tile is zero from K up to a multiple of 32), the second lands in a
-    // column no epilogue looks at.  A step beyond the wavefront's share reads, as its activation
-    // fragment, the padding at the end of each tile row, which nothing ever writes and which is
-    // zero from the start of the kernel.
     const int zoff = A.ldb - 8;
-    auto aoff = [&](int c) { return c < n_my ? (kpart + c * ksplit) * 32 + wc.kq : zoff; };
+    const int n_my = __builtin_amdgcn_readfirstlane(wc.n_my);   // the same in every lane
     // One accumulator per plane of the split: three independent chains of products instead of
     // one, added up at the end.
     f32x4 acc1 = f32x4{0.0f, 0.0f, 0.0f, 0.0f}, acc2 = acc1;
-    for (int c0 = 0; c0 < n_my; c0 += CH) {
-        if (c0 > 0 || !have_first) {
-            TR(50);
-            weight_prefetch(wc, sg, kpart, ksplit, c0, b);
-#if TDT_TRACE
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            TR(51);
-#endif
-        }
-        // the activation fragments of step j + 1 are requested from LDS before the products of
-        // step j are issued
-        bf16x8 x[2][3];
-        {
-            const uint16_t *a = arow + aoff(c0);
-            x[0][0] = *reinterpret_cast<const bf16x8 *>(a);
-            x[0][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
-            x[0][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
-        }
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            if (j + 1 < CH) {
-                const uint16_t *a = arow + aoff(c0 + j + 1);
-                x[(j + 1) & 1][0] = *reinterpret_cast<const bf16x8 *>(a);
-                x[(j + 1) & 1][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
-                x[(j + 1) & 1][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
-            }
-            const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&b[j]);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][0], bv, acc, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][1], bv, acc1, 0, 0, 0);
-            acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][2], bv, acc2, 0, 0, 0);
+    for (int c0 = 0; c0 < n_my; c0 += 2 * CH) {
+        chunk_products(arow, plane, zoff, wc.kq, kpart, ksplit, c0, n_my, b, acc, acc1, acc2);
+        if (c0 + 2 * CH < n_my) weight_prefetch(wc, sg, kpart, ksplit, c0 + 2 * CH, b);
+        TR(50);
+        if (c0 + CH < n_my) {
+            chunk_products(arow, plane, zoff, wc.kq, kpart, ksplit, c0 + CH, n_my, b2, acc, acc1, acc2);
+            if (c0 + 3 * CH < n_my) weight_prefetch(wc, sg, kpart, ksplit, c0 + 3 * CH, b2);
         }
     }
     // smallest terms first
@@ -217,21 +224,27 @@ __device__ inline void tile_accumulate(const ActTile<uint16_t> &A, const Seg &sg
 
 template <typename WT> struct Backend;
 template <> struct Backend<uint16_t> {
-    struct Pre {   // weight fragments fetched while the activations are being staged
+    struct Pre {   // weight fragments fetched before the activations can be read
         WeightCursor wc;
-        uint4 b[CH];
+        uint4 b[CH], b2[CH];
     };
+    // first chunk: requested before the item waits for the rows it depends on
     template <typename RowF>
     __device__ static void prefetch(Pre &pre, const Seg &sg, RowF rowidx, int ct, int kpart, int ksplit, int lane)
     {
         pre.wc = weight_cursor(sg, rowidx(ct, lane & 15), kpart, ksplit, lane);
         weight_prefetch(pre.wc, sg, kpart, ksplit, 0, pre.b);
     }
+    // second chunk: requested once the registers of the staged rows are free again
+    __device__ static void prefetch_more(Pre &pre, const Seg &sg, int kpart, int ksplit)
+    {
+        if (__builtin_amdgcn_readfirstlane(pre.wc.n_my) > CH) weight_prefetch(pre.wc, sg, kpart, ksplit, CH, pre.b2);
+    }
     template <typename RowF>
     __device__ static void accumulate(const ActTile<uint16_t> &A, const Seg &sg, RowF, int, int kpart, int ksplit,
                                       Accum<uint16_t> &acc, int lane, Pre &pre)
     {
-        tile_accumulate(A, sg, pre.wc, kpart, ksplit, pre.b, true, acc.c, lane);
+        tile_accumulate(A, sg, pre.wc, kpart, ksplit, pre.b, pre.b2, acc.c, lane);
     }
     __device__ static void spill(HypShared &S, const Accum<uint16_t> &acc, int wave, int lane)
     {
@@ -270,6 +283,7 @@ template <> struct Backend<float> {
         pre.n_my = nsteps > kpart ? (nsteps - kpart + ksplit - 1) >> __builtin_ctz(ksplit) : 0;
         fetch(pre, sg, kpart, ksplit, 0);
     }
+    __device__ static void prefetch_more(Pre &, const Seg &, int, int) {}
     template <typename RowF>
     __device__ static void accumulate(const ActTile<float> &A, const Seg &sg, RowF, int, int kpart, int ksplit,
                                       Accum<float> &acc, int lane, Pre &pre)
@@ -322,7 +336,7 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
                                 const float *__restrict__ bias, const float *any_floats, StageF stage,
                                 RowF rowidx, PreF pre_round, ParkF park, EpiF epi, WaitF wait)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nseg = in.count();
     // The bias load below is unconditional, so that it is issued with the other loads of the
     // item: where there is no bias, any_floats must be a readable float array that covers every
@@ -363,10 +377,12 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
                 else __syncthreads();
                 TR(13);
                 stage(sg);
+                if (mine) Backend<WT>::prefetch_more(pre, sg, kpart, ksplit);
                 TR(14);
                 __syncthreads();
                 TR(15);
             }
+            else if (mine) Backend<WT>::prefetch_more(pre, sg, kpart, ksplit);
             if (TDT_FINE_TIMERS && threadIdx.x == 0) { const long long n = wall_clock64(); S.tk_fine[S.fine_phase][0] += n - tq; tq = n; }
             if (mine) Backend<WT>::accumulate(A, sg, rowidx, ct, kpart, ksplit, acc, lane, pre);
             TR(16);
