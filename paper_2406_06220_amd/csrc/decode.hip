@@ -264,10 +264,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     const float ps = __uint_as_float((unsigned)(pend_u[j] >> 32));
                     if (ps > 0.0f) part = ps * expf(pm - S.pend_m[q]);
                 }
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+                part = wave_sum(part);
                 // log_softmax at the maximum = -log(sum exp(l - max))
-                if (lane == 0) S.score[S.pend_g[q]] -= logf(part);
+                if (lane == 63) S.score[S.pend_g[q]] -= logf(part);
             }
         }
         __syncthreads();
@@ -777,7 +776,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     cg = it - ti * n_cg;
                 }
                 const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
-                // running statistics of row tid / 32 over this item's columns (lanes 0 and 32)
+                // running statistics of row tid / 32 over this item's columns (lanes 31 and 63)
                 float rm = -INFINITY, rs = 0.0f, rdm = -INFINITY;
                 int ra = 0, rda = 0;
                 run_item<WT>(
@@ -839,20 +838,24 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 }
                             }
                         }
-#pragma unroll
-                        for (int off = 16; off > 0; off >>= 1) {
-                            const float om = __shfl_xor(m, off, 64), odm = __shfl_xor(dm, off, 64);
-                            const int oa = __shfl_xor(a, off, 64), oda = __shfl_xor(da, off, 64);
-                            if (om > m || (om == m && oa < a)) { m = om; a = oa; }
-                            if (odm > dm || (odm == dm && oda < da)) { dm = odm; da = oda; }
-                        }
-                        float s = 0.0f;   // sum over the round's label columns of exp(logit - m)
+                        // the row's maximum (in every lane of the half-wavefront), then the lowest
+                        // column that reaches it and the sum of exp(logit - maximum) (in lane 31)
+                        auto fmax2 = [](float x, float y) { return fmaxf(x, y); };
+                        auto imin2 = [](int x, int y) { return min(x, y); };
+                        const float mrow = half_broadcast(half_reduce(m, -INFINITY, fmax2), lane);
+                        a = half_reduce(m == mrow ? a : 0x7fffffff, 0x7fffffff, imin2);
+                        float s = 0.0f;
 #pragma unroll
                         for (int e = 0; e < kWaves * CT / 32; ++e)
-                            if (lg[e] > -INFINITY) s += __expf(lg[e] - m);
-#pragma unroll
-                        for (int off = 16; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-                        if (sub == 0) {   // rounds ascend through the columns: '>' keeps the first maximum
+                            if (lg[e] > -INFINITY) s += __expf(lg[e] - mrow);
+                        s = half_reduce(s, 0.0f, [](float x, float y) { return x + y; });
+                        if (D > 0) {   // the duration head, the same way
+                            const float drow = half_broadcast(half_reduce(dm, -INFINITY, fmax2), lane);
+                            da = half_reduce(dm == drow ? da : 0x7fffffff, 0x7fffffff, imin2);
+                            dm = drow;
+                        }
+                        m = mrow;
+                        if (sub == 31) {   // rounds ascend through the columns: '>' keeps the first maximum
                             if (s > 0.0f) {
                                 if (m > rm) {
                                     rs = (rs > 0.0f ? rs * __expf(rm - m) : 0.0f) + s;
@@ -862,14 +865,14 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                     rs += s * __expf(m - rm);
                                 }
                             }
-                            if (dm > rdm) {
+                            if (D > 0 && dm > rdm) {
                                 rdm = dm;
                                 rda = da;
                             }
                         }
                     },
                     wait_hook);
-                if ((tid & 31) == 0 && ti * RT + (tid >> 5) < M) {
+                if ((tid & 31) == 31 && ti * RT + (tid >> 5) < M) {
                     const int r = ti * RT + (tid >> 5);
                     if (rs > 0.0f)
                         __hip_atomic_fetch_max(row_lab + r, pack_best(rm, ra), __ATOMIC_RELAXED, TDT_AGENT);

@@ -28,6 +28,45 @@ template <> struct W2<uint16_t> {
 // hardware exponential and reciprocal: about 1e-7 absolute error on a value in (0, 1)
 __device__ inline float fast_sigmoid(float x) { return __frcp_rn(1.0f + __expf(-x)); }
 
+// ---- reductions across lanes on the data-parallel-primitive path of the vector ALU (no LDS
+// round trip per step, unlike a shuffle).  Rows are the four groups of 16 lanes of a wavefront:
+// row_shr:n hands lane i the value of lane i - n of its row (the identity where there is none);
+// row_bcast:15 hands every lane of rows 1 and 3 the value of lane 15 of the row before.  After
+// the five steps lane 31 holds the reduction over lanes 0..31 and lane 63 that over lanes
+// 32..63; a sixth step (row_bcast:31) would leave the whole wavefront's in lane 63.
+template <int CTRL, int ROW_MASK> __device__ inline float dpp_move(float identity, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, ROW_MASK,
+                                                      0xf, false));
+}
+template <int CTRL, int ROW_MASK> __device__ inline int dpp_move(int identity, int v)
+{
+    return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xf, false);
+}
+// op over each half of the wavefront; the result is valid in lanes 31 and 63
+template <typename T, typename Op> __device__ inline T half_reduce(T v, T identity, Op op)
+{
+    v = op(v, dpp_move<0x111, 0xf>(identity, v));   // row_shr:1
+    v = op(v, dpp_move<0x112, 0xf>(identity, v));   // row_shr:2
+    v = op(v, dpp_move<0x114, 0xf>(identity, v));   // row_shr:4
+    v = op(v, dpp_move<0x118, 0xf>(identity, v));   // row_shr:8
+    v = op(v, dpp_move<0x142, 0xa>(identity, v));   // row_bcast:15 into rows 1 and 3
+    return v;
+}
+// the value lane 31 holds, in lanes 0..31, and the value lane 63 holds, in lanes 32..63
+__device__ inline float half_broadcast(float v, int lane)
+{
+    const float lo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
+    const float hi = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+    return lane < 32 ? lo : hi;
+}
+// sum over the whole wavefront, valid in lane 63
+__device__ inline float wave_sum(float v)
+{
+    v = half_reduce(v, 0.0f, [](float a, float b) { return a + b; });
+    return v + dpp_move<0x143, 0xc>(0.0f, v);   // row_bcast:31 into rows 2 and 3
+}
+
 // ---- coherent exchange primitives (see the header comment)
 #define TDT_AGENT __HIP_MEMORY_SCOPE_AGENT
 __device__ inline float ld_co(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, TDT_AGENT); }
