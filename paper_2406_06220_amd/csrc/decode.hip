@@ -153,6 +153,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     }
     __syncthreads();
 
+    // A value that is the same in every lane of the wavefront (e.g. read from LDS at an address that
+    // depends on the wavefront only), moved to a scalar register: what is computed from it -- row
+    // pointers above all -- then runs on the scalar unit and loads take a scalar base address.
+    auto uni = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
     const int Hp = p.h_pred, E = p.emb_dim, L = p.pred_layers;
     const bool lstm = p.pred_kind == TDT_PRED_LSTM;
     // the activation tile starts out as zeros: rows a work item does not stage keep what they
@@ -305,6 +309,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         split_tiles(C, n_tiles, NT, max_cg, n_cg, tpg);
         JointPlan jp;
         jp.Kw = (short)Kw;
+        jp.rcp_kw = ((1 << 20) + Kw - 1) / Kw;   // (r * rcp_kw) >> 20 == r / Kw for r < 16384, Kw <= 64
         jp.n_tiles = (short)n_tiles;
         jp.n_cg = (short)n_cg;
         jp.tpg = tpg;
@@ -451,7 +456,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             const float *src = sg.part == 1 ? h_cur : x_prev;
                             stage_segment<WT>(
                                 A, sg.K, nrows,
-                                [&](int i) { return src + (size_t)(b0 + plist[ti * RT + i]) * Hp + k0; },
+                                [&](int i) { return src + (size_t)(b0 + uni(plist[ti * RT + i])) * Hp + k0; },
                                 [](const float *row, int k) { return ld_co2(row + k); },
                                 [](const float *, int, float2 v) { return v; });
                         },
@@ -555,7 +560,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         if (lstm) {
                             stage_segment<WT>(
                                 A, sg.K, nrows,
-                                [&](int i) { return src + (size_t)(b0 + S.act_list[ti * RT + i]) * Hp + k0; },
+                                [&](int i) { return src + (size_t)(b0 + uni(S.act_list[ti * RT + i])) * Hp + k0; },
                                 [](const float *row, int k) { return ld_co2(row + k); },
                                 [](const float *, int, float2 v) { return v; });
                         } else {
@@ -713,7 +718,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                             } else if (lstm) {
                                 stage_segment<WT>(
                                     A, sg.K, nrows,
-                                    [&](int i) { return src_h + (size_t)(b0 + jl[ti * RT + i]) * Hp + k0; },
+                                    [&](int i) { return src_h + (size_t)(b0 + uni(jl[ti * RT + i])) * Hp + k0; },
                                     [](const float *row, int k) { return ld_co2(row + k); },
                                     [](const float *, int, float2 v) { return v; });
                             } else {
@@ -785,14 +790,14 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         const int k0 = sg.k0;
                         stage_segment<WT>(
                             A, sg.K, min(RT, M - ti * RT),
-                            [&](int i) {
+                            [&](int i) {   // the row is the same in all lanes of the wavefront
                                 const int r = ti * RT + i;
-                                const int q = r / Kw;
-                                const int g = jl[q];
-                                const int f = S.time[g] + (r - q * Kw);
+                                const int q = (r * jp.rcp_kw) >> 20;   // r / Kw
+                                const int g = uni(jl[q]);
+                                const int f = uni(S.time[g]) + (r - q * Kw);
                                 JointRow c;
-                                c.valid = f < S.len[g];
-                                c.enc = p.enc_proj + ((size_t)S.gid[g] * T + (c.valid ? f : 0)) * H + k0;
+                                c.valid = f < uni(S.len[g]);
+                                c.enc = p.enc_proj + ((size_t)uni(S.gid[g]) * T + (c.valid ? f : 0)) * H + k0;
                                 c.pred = p.pred_proj + (size_t)(b0 + g) * H + k0;
                                 return c;
                             },

@@ -63,6 +63,7 @@ constexpr int kTabPerThread = kWaves * RT * CT / kThreads;
 struct JointPlan {
     short Kw, n_tiles, n_cg, ti0;
     int tpg, cg0;
+    int rcp_kw;   // ceil(2^20 / Kw)
 };
 
 struct HypShared {

@@ -90,6 +90,11 @@ __device__ inline void stage_segment_impl(const ActTile<WT> &A, int K, int nrows
             }
         }
     __builtin_amdgcn_sched_barrier(0);
+    TR(60);
+#if TDT_TRACE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    TR(61);
+#endif
 #pragma unroll
     for (int ii = 0; ii < RPW; ++ii)
         if (wave + ii * kWaves < nrows) {
