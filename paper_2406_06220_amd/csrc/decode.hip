@@ -514,16 +514,18 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         }
 
         TR(2);
-        // ---- Q: everything that is a product with the new predictor state: its projection into
-        // the joint space (Sec. 3.4), and for an LSTM the recurrent part W_hh * h of the first
+        // ---- Q: everything that is a product with the new predictor state of an LSTM: its
+        // projection into the joint space (Sec. 3.4), and the recurrent part W_hh * h of the first
         // layer's next step.  Two sections of column tiles, each with its matrix and its input.
+        // (A stateless predictor has no such phase: its projected output is a sum of per-label
+        // table rows that the joint pass reads directly.)
         if (TDT_FINE_TIMERS && tid == 0) S.fine_phase = 1;
         phase_bucket = kTkQ;
-        {
-            const float *src_a = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * Bw * Hp : nullptr;
-            const float *src_b = lstm ? p.hbuf + ((size_t)(pp ^ 1) * L) * Bw * Hp : nullptr;
+        if (lstm) {
+            const float *src_a = p.hbuf + ((size_t)(pp ^ 1) * L + (L - 1)) * Bw * Hp;
+            const float *src_b = p.hbuf + ((size_t)(pp ^ 1) * L) * Bw * Hp;
             // (projections on the fly: only the recurrent product is left here)
-            const int NT_A = ONTHEFLY ? 0 : (H + CT - 1) / CT, NT_B = lstm ? (Hp + 3) / 4 : 0;
+            const int NT_A = ONTHEFLY ? 0 : (H + CT - 1) / CT, NT_B = (Hp + 3) / 4;
             if (n_tiles_a != q_for_tiles) {
                 // fewest tiles per work item that give every workgroup at most one item
                 int t = max(1, ((NT_A + NT_B) * n_tiles_a + C - 1) / C);
@@ -557,28 +559,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     S, A, in, n_ct, sec_b ? nullptr : p.b_pred, sec_b ? p.b_lstm[0] : p.b_pred,
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
-                        if (lstm) {
-                            stage_segment<WT>(
-                                A, sg.K, nrows,
-                                [&](int i) { return src + (size_t)(b0 + uni(S.act_list[ti * RT + i])) * Hp + k0; },
-                                [](const float *row, int k) { return ld_co2(row + k); },
-                                [](const float *, int, float2 v) { return v; });
-                        } else {
-                            // stateless: table L-1 embeds the newest label, table 0 the older one
-                            stage_segment<WT>(
-                                A, sg.K, nrows,
-                                [&](int i) {
-                                    const int g = S.act_list[ti * RT + i];
-                                    return make_int2(S.last[g], S.last2[g]);
-                                },
-                                [&](int2 lab, int k) {
-                                    const int kk = k0 + k, c = kk / E;
-                                    const int tok = (c == L - 1) ? lab.x : lab.y;
-                                    return W2<WT>::load(static_cast<const WT *>(p.emb) +
-                                                        ((size_t)c * (V + 1) + tok) * E + (kk - c * E));
-                                },
-                                [](int2, int, typename W2<WT>::Raw v) { return W2<WT>::cvt(v); });
-                        }
+                        stage_segment<WT>(
+                            A, sg.K, nrows,
+                            [&](int i) { return src + (size_t)(b0 + uni(S.act_list[ti * RT + i])) * Hp + k0; },
+                            [](const float *row, int k) { return ld_co2(row + k); },
+                            [](const float *, int, float2 v) { return v; });
                     },
                     [&](int ct, int j) -> long long {
                         if (sec_b) {   // a column tile = 4 hidden units x 4 gates
@@ -788,30 +773,85 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     S, A, in, n_ct, p.b_out, p.b_out,
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
-                        stage_segment<WT>(
-                            A, sg.K, min(RT, M - ti * RT),
-                            [&](int i) {   // the row is the same in all lanes of the wavefront
-                                const int r = ti * RT + i;
-                                const int q = (r * jp.rcp_kw) >> 20;   // r / Kw
-                                const int g = uni(jl[q]);
-                                const int f = uni(S.time[g]) + (r - q * Kw);
-                                JointRow c;
-                                c.valid = f < uni(S.len[g]);
-                                c.enc = p.enc_proj + ((size_t)uni(S.gid[g]) * T + (c.valid ? f : 0)) * H + k0;
-                                c.pred = p.pred_proj + (size_t)(b0 + g) * H + k0;
-                                return c;
-                            },
-                            [](const JointRow &c, int k) {
-                                EncPred v;
-                                if constexpr (ONTHEFLY) v.e = ld_co2(c.enc + k);   // written a phase ago
-                                else v.e = *reinterpret_cast<const float2 *>(c.enc + k);
-                                v.p = ld_co2(c.pred + k);
-                                return v;
-                            },
-                            [](const JointRow &c, int, EncPred v) {
-                                return make_float2(c.valid ? fmaxf(v.e.x + v.p.x, 0.0f) : 0.0f,
-                                                   c.valid ? fmaxf(v.e.y + v.p.y, 0.0f) : 0.0f);
-                            });
+                        const int nrows = min(RT, M - ti * RT);
+                        // where row i of the tile reads its projected encoder frame and its projected
+                        // predictor output (the row is the same in all lanes of the wavefront)
+                        auto row_of = [&](int i) {
+                            const int r = ti * RT + i;
+                            const int q = (r * jp.rcp_kw) >> 20;   // r / Kw
+                            const int g = uni(jl[q]);
+                            const int f = uni(S.time[g]) + (r - q * Kw);
+                            JointRow c;
+                            c.valid = f < uni(S.len[g]);
+                            c.enc = p.enc_proj + ((size_t)uni(S.gid[g]) * T + (c.valid ? f : 0)) * H + k0;
+                            c.pred = c.pred2 = nullptr;
+                            c.g = g;
+                            return c;
+                        };
+                        if (!p.pred_tab) {
+                            // the predictor output was projected by this iteration's phase Q (or, on
+                            // the fly, by the phase before this pass): coherent loads
+                            stage_segment<WT>(
+                                A, sg.K, nrows,
+                                [&](int i) {
+                                    JointRow c = row_of(i);
+                                    c.pred = p.pred_proj + (size_t)(b0 + c.g) * H + k0;
+                                    return c;
+                                },
+                                [](const JointRow &c, int k) {
+                                    EncPred v;
+                                    if constexpr (ONTHEFLY) v.e = ld_co2(c.enc + k);   // written a phase ago
+                                    else v.e = *reinterpret_cast<const float2 *>(c.enc + k);
+                                    v.p = ld_co2(c.pred + k);
+                                    return v;
+                                },
+                                [](const JointRow &c, int, EncPred v) {
+                                    return make_float2(c.valid ? fmaxf(v.e.x + v.p.x, 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.y + v.p.y, 0.0f) : 0.0f);
+                                });
+                        } else if (L == 1) {
+                            // stateless predictor, one label of context: a row of its table
+                            stage_segment<WT>(
+                                A, sg.K, nrows,
+                                [&](int i) {
+                                    JointRow c = row_of(i);
+                                    c.pred = p.pred_tab + (size_t)uni(S.last[c.g]) * H + k0;
+                                    return c;
+                                },
+                                [](const JointRow &c, int k) {
+                                    EncPred v;
+                                    v.e = *reinterpret_cast<const float2 *>(c.enc + k);
+                                    v.p = *reinterpret_cast<const float2 *>(c.pred + k);
+                                    return v;
+                                },
+                                [](const JointRow &c, int, EncPred v) {
+                                    return make_float2(c.valid ? fmaxf(v.e.x + v.p.x, 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.y + v.p.y, 0.0f) : 0.0f);
+                                });
+                        } else {
+                            // two labels of context: the older label's row of table 0 plus the newest
+                            // label's row of table 1 (which carries the bias) is the projected output
+                            // (three loads per slot: one row of the wavefront at a time)
+                            stage_segment<WT, 1>(
+                                A, sg.K, nrows,
+                                [&](int i) {
+                                    JointRow c = row_of(i);
+                                    c.pred = p.pred_tab + (size_t)uni(S.last2[c.g]) * H + k0;
+                                    c.pred2 = p.pred_tab + ((size_t)(V + 1) + uni(S.last[c.g])) * H + k0;
+                                    return c;
+                                },
+                                [](const JointRow &c, int k) {
+                                    EncPred2 v;
+                                    v.e = *reinterpret_cast<const float2 *>(c.enc + k);
+                                    v.p = *reinterpret_cast<const float2 *>(c.pred + k);
+                                    v.p2 = *reinterpret_cast<const float2 *>(c.pred2 + k);
+                                    return v;
+                                },
+                                [](const JointRow &c, int, EncPred2 v) {
+                                    return make_float2(c.valid ? fmaxf(v.e.x + (v.p.x + v.p2.x), 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.y + (v.p.y + v.p2.y), 0.0f) : 0.0f);
+                                });
+                        }
                     },
                     [&](int ct, int j) -> long long {
                         const int n = (tile0 + ct) * CT + j;

@@ -123,9 +123,15 @@ struct Seg {
 struct EncPred {
     float2 e, p;
 };
+// ... and with a stateless predictor of two labels of context, whose projected output is the sum
+// of two table rows
+struct EncPred2 {
+    float2 e, p, p2;
+};
 // where one row of a joint pass reads them (valid false: past the end of the utterance)
 struct JointRow {
-    const float *enc, *pred;
+    const float *enc, *pred, *pred2;
+    int g;   // the hypothesis (slot in its group)
     bool valid;
 };
 

@@ -1,8 +1,11 @@
 // Dense projections computed once per call, before the label loop starts:
 //   encoder projection (paper Sec. 3.4; the precomputation at line 2 of Algorithm 3)
 //     out[r][n] = sum_k enc[r][k] * w_enc[n][k] + b_enc[n]
-//   and, with the same kernel, the table w_ih[0] * emb[label] + b_lstm[0] of the first LSTM
-//   layer's input product for every label.
+//   and, with the same kernel, what the predictor side can tabulate per label: the first LSTM
+//   layer's input product w_ih[0] * emb[label] + b_lstm[0], or -- for a stateless predictor,
+//   whose output is nothing but embeddings of the last labels -- its whole projection into the
+//   joint space, one table per context position: w_pred[:, c*E .. (c+1)*E) * emb_c[label]
+//   (the last table with b_pred added).
 // A dense contraction over all B*T frames, so it runs on the matrix cores:
 // bf16 operands, fp32 accumulation, fp32 output (v_mfma_f32_32x32x16_bf16).
 // Both operands are K-contiguous ("NT" GEMM), which is the layout the MFMA lane
@@ -23,14 +26,19 @@ constexpr int GEMM_THREADS = 256;            // 4 wavefronts, each a 64x64 sub-t
 // 32 rows a wavefront reads for one k-slice spread over all LDS banks.
 __device__ inline int lds_off(int row, int chunk) { return row * BK + ((chunk ^ (row & 7)) << 3); }
 
-// One product C = A * W^T + bias and the workgroups it takes.
+// One product C = A * W^T + bias and the workgroups it takes.  Rows of W are ldw apart (a
+// slice of the columns of a wider matrix can be multiplied); bias may be null.
 struct LinearProblem {
     const uint16_t *A, *W;
     const float *bias;
     float *C;
     long long M;
-    int N, K, group;
+    int N, K, ldw, group;
     unsigned blocks;
+};
+constexpr int kMaxProblems = 3;   // products one preparation launch can hold
+struct LinearBatch {
+    LinearProblem q[kMaxProblems];
 };
 
 // the 128 x 128 output tile of workgroup `block` (of q.blocks) of one product
@@ -41,7 +49,7 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
     const float *__restrict__ bias = q.bias;
     float *__restrict__ C = q.C;
     const long long M = q.M;
-    const int N = q.N, K = q.K, group = q.group;
+    const int N = q.N, K = q.K, ldw = q.ldw, group = q.group;
     __shared__ __align__(16) uint16_t As[BM * BK];
     __shared__ __align__(16) uint16_t Bs[BN * BK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -77,7 +85,7 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
             const int n = n0 + row;
             ra[j] = (m < M && k < K) ? *reinterpret_cast<const uint4 *>(A + m * K + k)
                                      : make_uint4(0, 0, 0, 0);
-            rb[j] = (n < N && k < K) ? *reinterpret_cast<const uint4 *>(W + (long long)n * K + k)
+            rb[j] = (n < N && k < K) ? *reinterpret_cast<const uint4 *>(W + (long long)n * ldw + k)
                                      : make_uint4(0, 0, 0, 0);
         }
     };
@@ -124,7 +132,7 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
         for (int j = 0; j < 2; ++j) {
             const int n = n0 + wn * 64 + j * 32 + (lane & 31);
             if (n >= N) continue;
-            const float bn = bias[n];
+            const float bn = bias ? bias[n] : 0.0f;
             const int nc = group > 0 ? (n % group) * (N / group) + n / group : n;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
@@ -140,30 +148,33 @@ __global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(LinearProbl
 }
 
 // Everything a decode call needs before its decode kernel, in one launch: the encoder
-// projection, the per-label input table of the first LSTM layer (q1.blocks == 0: none), and
-// the clearing of the workspace's zero region and of the statistics.  The three are
-// independent; a workgroup takes its task from its index.  Both products' workgroup counts
-// are multiples of the number of dies, so each keeps its die-aware order of tiles.
-__global__ __launch_bounds__(GEMM_THREADS) void prepare_bf16_kernel(LinearProblem q0, LinearProblem q1, uint4 *zero,
-                                                                   size_t n16, long long *out_stats)
+// projection, the per-label tables of the predictor side (a product with blocks == 0 is
+// absent), and the clearing of the workspace's zero region and of the statistics.  The tasks
+// are independent; a workgroup takes its task from its index.  Every product's workgroup count
+// is a multiple of the number of dies, so each keeps its die-aware order of tiles.
+__global__ __launch_bounds__(GEMM_THREADS) void prepare_bf16_kernel(LinearBatch batch, uint4 *zero, size_t n16,
+                                                                   long long *out_stats)
 {
-    const unsigned b = blockIdx.x;
-    if (b < q0.blocks) {
-        gemm_tile_bf16(q0, b);
-    } else if (b < q0.blocks + q1.blocks) {
-        gemm_tile_bf16(q1, b - q0.blocks);
-    } else {
-        const unsigned zb = b - q0.blocks - q1.blocks, nzb = gridDim.x - q0.blocks - q1.blocks;
-        for (size_t i = (size_t)zb * GEMM_THREADS + threadIdx.x; i < n16; i += (size_t)nzb * GEMM_THREADS)
-            zero[i] = make_uint4(0, 0, 0, 0);
-        if (out_stats && zb == 0 && threadIdx.x < TDT_STAT_COUNT) out_stats[threadIdx.x] = 0;
+    unsigned b = blockIdx.x, used = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxProblems; ++i) {
+        if (b < batch.q[i].blocks) {
+            gemm_tile_bf16(batch.q[i], b);
+            return;
+        }
+        b -= batch.q[i].blocks;
+        used += batch.q[i].blocks;
     }
+    const unsigned zb = b, nzb = gridDim.x - used;
+    for (size_t i = (size_t)zb * GEMM_THREADS + threadIdx.x; i < n16; i += (size_t)nzb * GEMM_THREADS)
+        zero[i] = make_uint4(0, 0, 0, 0);
+    if (out_stats && zb == 0 && threadIdx.x < TDT_STAT_COUNT) out_stats[threadIdx.x] = 0;
 }
 
 // float32 models (small): classic 64x64 tile, 4x4 outputs per thread.
 __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
     const float *__restrict__ A, const float *__restrict__ W, const float *__restrict__ bias,
-    float *__restrict__ C, long long M, int N, int K, int group)
+    float *__restrict__ C, long long M, int N, int K, int ldw, int group)
 {
     __shared__ float As[16][65];
     __shared__ float Ws[16][65];
@@ -181,7 +192,7 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
             const long long m = m0 + row;
             const int n = n0 + row;
             As[kk][row] = (m < M && k < K) ? A[m * K + k] : 0.0f;
-            Ws[kk][row] = (n < N && k < K) ? W[(long long)n * K + k] : 0.0f;
+            Ws[kk][row] = (n < N && k < K) ? W[(long long)n * ldw + k] : 0.0f;
         }
         __syncthreads();
 #pragma unroll
@@ -205,15 +216,15 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + tx * 4 + j;
-            if (n < N) C[m * N + (group > 0 ? (n % group) * (N / group) + n / group : n)] = acc[i][j] + bias[n];
+            if (n < N) C[m * N + (group > 0 ? (n % group) * (N / group) + n / group : n)] = acc[i][j] + (bias ? bias[n] : 0.0f);
         }
     }
 }
 
 }  // namespace
 
-static LinearProblem linear_problem(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
-                                    int group, float *out)
+static LinearProblem linear_problem(const void *a, int64_t rows, int K, const void *w, int ldw, int N,
+                                    const float *bias, int group, float *out)
 {
     LinearProblem q{};
     q.A = static_cast<const uint16_t *>(a);
@@ -223,6 +234,7 @@ static LinearProblem linear_problem(const void *a, int64_t rows, int K, const vo
     q.M = rows;
     q.N = N;
     q.K = K;
+    q.ldw = ldw;
     q.group = group;
     const long long row_tiles = (rows + BM - 1) / BM, rounds = (row_tiles + kXcds - 1) / kXcds;
     q.blocks = (unsigned)(rounds * kXcds * ((N + BN - 1) / BN));
@@ -230,34 +242,45 @@ static LinearProblem linear_problem(const void *a, int64_t rows, int K, const vo
 }
 
 hipError_t launch_prepare_bf16(const void *enc, int64_t rows, const tdt_weights_t *w, float *enc_proj,
-                               float *emb_gates, void *zero_begin, size_t zero_bytes, long long *out_stats,
-                               hipStream_t stream)
+                               float *emb_gates, float *pred_tab, void *zero_begin, size_t zero_bytes,
+                               long long *out_stats, hipStream_t stream)
 {
-    const LinearProblem q0 = linear_problem(enc, rows, w->d_enc, w->w_enc, w->h_joint, w->b_enc, 0, enc_proj);
-    LinearProblem q1{};
-    if (w->pred_kind == TDT_PRED_LSTM)   // stored [label][unit][gate]
-        q1 = linear_problem(w->emb, w->vocab + 1, w->emb_dim, w->w_ih[0], 4 * w->h_pred, w->b_lstm[0], w->h_pred,
-                            emb_gates);
+    LinearBatch batch{};
+    int n = 0;
+    batch.q[n++] = linear_problem(enc, rows, w->d_enc, w->w_enc, w->d_enc, w->h_joint, w->b_enc, 0, enc_proj);
+    if (w->pred_kind == TDT_PRED_LSTM) {   // stored [label][unit][gate]
+        batch.q[n++] = linear_problem(w->emb, w->vocab + 1, w->emb_dim, w->w_ih[0], w->emb_dim, 4 * w->h_pred,
+                                      w->b_lstm[0], w->h_pred, emb_gates);
+    } else if (pred_tab) {
+        const size_t E = (size_t)w->emb_dim, rows_tab = (size_t)w->vocab + 1;
+        for (int c = 0; c < w->pred_layers; ++c)
+            batch.q[n++] = linear_problem(static_cast<const uint16_t *>(w->emb) + c * rows_tab * E, (int64_t)rows_tab,
+                                          w->emb_dim, static_cast<const uint16_t *>(w->w_pred) + c * E, w->h_pred,
+                                          w->h_joint, c == w->pred_layers - 1 ? w->b_pred : nullptr, 0,
+                                          pred_tab + c * rows_tab * w->h_joint);
+    }
+    unsigned blocks = 0;
+    for (int i = 0; i < n; ++i) blocks += batch.q[i].blocks;
     const size_t n16 = zero_bytes / 16;
     size_t zb = (n16 + GEMM_THREADS - 1) / GEMM_THREADS;
     if (zb > 256) zb = 256;
     if (zb < 1) zb = 1;
-    hipLaunchKernelGGL(prepare_bf16_kernel, dim3(q0.blocks + q1.blocks + (unsigned)zb), dim3(GEMM_THREADS), 0, stream,
-                       q0, q1, static_cast<uint4 *>(zero_begin), n16, out_stats);
+    hipLaunchKernelGGL(prepare_bf16_kernel, dim3(blocks + (unsigned)zb), dim3(GEMM_THREADS), 0, stream, batch,
+                       static_cast<uint4 *>(zero_begin), n16, out_stats);
     return hipGetLastError();
 }
 
-hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
+hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int ldw, int N, const float *bias,
                          int dtype, int group, float *out, hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;
     if (dtype == 1) {
-        const LinearProblem q = linear_problem(a, rows, K, w, N, bias, group, out);
+        const LinearProblem q = linear_problem(a, rows, K, w, ldw, N, bias, group, out);
         hipLaunchKernelGGL(enc_proj_bf16_kernel, dim3(q.blocks), dim3(GEMM_THREADS), 0, stream, q);
     } else {
         dim3 grid((unsigned)(((N + 63) / 64) * ((rows + 63) / 64)));
         hipLaunchKernelGGL(enc_proj_f32_kernel, grid, dim3(256), 0, stream, static_cast<const float *>(a),
-                           static_cast<const float *>(w), bias, out, (long long)rows, N, K, group);
+                           static_cast<const float *>(w), bias, out, (long long)rows, N, K, ldw, group);
     }
     return hipGetLastError();
 }
@@ -265,7 +288,22 @@ hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int 
 hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,
                                      float *out, hipStream_t stream)
 {
-    return launch_linear(enc, rows, w->d_enc, w->w_enc, w->h_joint, w->b_enc, w->dtype, 0, out, stream);
+    return launch_linear(enc, rows, w->d_enc, w->w_enc, w->d_enc, w->h_joint, w->b_enc, w->dtype, 0, out, stream);
+}
+
+// stateless predictor, float32 models: the per-label tables of the projected predictor output
+hipError_t launch_pred_tables(const tdt_weights_t *w, float *pred_tab, hipStream_t stream)
+{
+    const size_t E = (size_t)w->emb_dim, rows_tab = (size_t)w->vocab + 1;
+    const size_t esz = w->dtype == 1 ? 2 : 4;
+    for (int c = 0; c < w->pred_layers; ++c) {
+        const hipError_t e = launch_linear(
+            static_cast<const char *>(w->emb) + c * rows_tab * E * esz, (int64_t)rows_tab, w->emb_dim,
+            static_cast<const char *>(w->w_pred) + c * E * esz, w->h_pred, w->h_joint,
+            c == w->pred_layers - 1 ? w->b_pred : nullptr, w->dtype, 0, pred_tab + c * rows_tab * w->h_joint, stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace tdt

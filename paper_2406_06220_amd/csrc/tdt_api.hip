@@ -56,6 +56,10 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T)
     L.emb_gates = off;
     if (lstm_layers > 0)
         off = align_up(off + (size_t)(w->vocab + 1) * 4 * w->h_pred * sizeof(float), 256);
+    // stateless predictor: its projected output per label, one table per context position
+    L.pred_tab = off;
+    if (lstm_layers == 0)
+        off = align_up(off + (size_t)w->pred_layers * (w->vocab + 1) * w->h_joint * sizeof(float), 256);
     L.partials = off;
     off = align_up(off + 2 * (size_t)kPartialEntries * sizeof(LsePartial), 256);
     // everything from here on is cleared by the init kernel of every call
@@ -263,12 +267,18 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     float *enc_proj = reinterpret_cast<float *>(ws + L.enc_proj);
 
     float *emb_gates = reinterpret_cast<float *>(ws + L.emb_gates);
+    // A stateless predictor's output depends on the last labels only, so its projection into the
+    // joint space (Sec. 3.4) is tabulated per label once per call and the label loop has no
+    // predictor-side product left.  (Not with projections on the fly, which is there to measure
+    // the arrangement without any precomputation.)
+    float *pred_tab = weights->pred_kind == TDT_PRED_STATELESS && !on_the_fly
+                          ? reinterpret_cast<float *>(ws + L.pred_tab) : nullptr;
     if (!reuse_enc_proj && weights->dtype == 1) {
-        // one launch: the projection, the first LSTM layer's per-label table, the clearing
+        // one launch: the projection, the predictor side's per-label tables, the clearing
         // (projections on the fly: no rows for the projection here)
-        if (launch_prepare_bf16(enc, on_the_fly ? 0 : (int64_t)B * T, weights, enc_proj, emb_gates, ws + L.zero_begin,
-                                L.zero_end - L.zero_begin, reinterpret_cast<long long *>(out_stats),
-                                s) != hipSuccess)
+        if (launch_prepare_bf16(enc, on_the_fly ? 0 : (int64_t)B * T, weights, enc_proj, emb_gates, pred_tab,
+                                ws + L.zero_begin, L.zero_end - L.zero_begin,
+                                reinterpret_cast<long long *>(out_stats), s) != hipSuccess)
             return TDT_ERR_LAUNCH;
     } else if (launch_init(ws + L.zero_begin, L.zero_end - L.zero_begin,
                            reinterpret_cast<long long *>(out_stats), s) != hipSuccess) {
@@ -280,10 +290,11 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         // first LSTM layer: its input product depends on the label only, so it is a table,
         // stored [label][unit][gate]
         if (weights->pred_kind == TDT_PRED_LSTM &&
-            launch_linear(weights->emb, weights->vocab + 1, weights->emb_dim, weights->w_ih[0],
+            launch_linear(weights->emb, weights->vocab + 1, weights->emb_dim, weights->w_ih[0], weights->emb_dim,
                           4 * weights->h_pred, weights->b_lstm[0], weights->dtype, weights->h_pred, emb_gates,
                           s) != hipSuccess)
             return TDT_ERR_LAUNCH;
+        if (pred_tab && launch_pred_tables(weights, pred_tab, s) != hipSuccess) return TDT_ERR_LAUNCH;
     }
 
     DecodeParams p{};
@@ -322,6 +333,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     p.b_out = weights->b_out;
     p.enc_proj = enc_proj;
     p.emb_gates = emb_gates;
+    p.pred_tab = pred_tab;
     p.enc_len = enc_len;
     p.out_labels = out_labels;
     p.out_frames = out_frames;

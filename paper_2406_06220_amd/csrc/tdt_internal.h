@@ -56,6 +56,8 @@ struct DecodeParams {
     const void *enc;         // [B][T][d_enc]   (read by the kernel only when it projects on the fly)
     float *enc_proj;         // [B][T][H]; on the fly: written row by row as joint passes need them
     const float *emb_gates;  // [V+1][h_pred][4 gates]: w_ih[0] * emb[label] + b_lstm[0] (LSTM only)
+    const float *pred_tab;   // [ctx][V+1][H]: projected predictor output per label and context position
+                             // (stateless predictor with precomputed projections only, else null)
     const int32_t *enc_len;  // [B]
     // outputs
     int32_t *out_labels, *out_frames, *out_len, *out_status;
@@ -79,7 +81,7 @@ struct DecodeParams {
 };
 
 struct WorkspaceLayout {
-    size_t enc_proj, emb_gates, hbuf, cbuf, rgate, pred_proj, partials, row_lab, row_dur, barrier, abort_flag, total;
+    size_t enc_proj, emb_gates, pred_tab, hbuf, cbuf, rgate, pred_proj, partials, row_lab, row_dur, barrier, abort_flag, total;
     size_t row_entries;            // uint64 entries in each of row_lab / row_dur
     size_t zero_begin, zero_end;   // byte range the init kernel clears
 };
@@ -95,16 +97,21 @@ StateLayout state_layout(const tdt_weights_t *w, int B);
 // launches (each returns a hipError_t)
 hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w,
                                      float *out, hipStream_t stream);
-// out[r][c(n)] = sum_k a[r][k] * w[n][k] + bias[n]; a and w in the model's dtype, out float32.
-// c(n) = n, or with group > 0 (N a multiple of group): c(n) = (n % group) * (N / group) + n / group,
-// which puts the N / group outputs n, n + group, n + 2 group, ... side by side.
-hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int N, const float *bias,
+// out[r][c(n)] = sum_k a[r][k] * w[n * ldw + k] + bias[n] (bias may be null); a and w in the
+// model's dtype, out float32.  c(n) = n, or with group > 0 (N a multiple of group):
+// c(n) = (n % group) * (N / group) + n / group, which puts the N / group outputs n, n + group,
+// n + 2 group, ... side by side.
+hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int ldw, int N, const float *bias,
                          int dtype, int group, float *out, hipStream_t stream);
-// bf16 models: encoder projection, the first LSTM layer's per-label table and the clearing of the
-// zero region in one launch
+// bf16 models: encoder projection, the predictor side's per-label tables (first LSTM layer's
+// input product into emb_gates; a stateless predictor's projected output into pred_tab, which may
+// be null: then none) and the clearing of the zero region in one launch
 hipError_t launch_prepare_bf16(const void *enc, int64_t rows, const tdt_weights_t *w, float *enc_proj,
-                               float *emb_gates, void *zero_begin, size_t zero_bytes, long long *out_stats,
-                               hipStream_t stream);
+                               float *emb_gates, float *pred_tab, void *zero_begin, size_t zero_bytes,
+                               long long *out_stats, hipStream_t stream);
+// stateless predictor: pred_tab[c][label][:] = w_pred[:, c*E .. (c+1)*E) * emb_c[label] (+ b_pred
+// in the last table), one launch per table
+hipError_t launch_pred_tables(const tdt_weights_t *w, float *pred_tab, hipStream_t stream);
 hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats,
                        hipStream_t stream);
 // which compiled form of the decode kernel a call runs

@@ -67,52 +67,58 @@ template <> struct ActTile<float> {
 // afterwards.  Rows beyond nrows are skipped altogether (the condition is the same for all
 // lanes of a wavefront): the tile keeps whatever those rows held, their products are never
 // looked at, and a row of the product depends on no other row of the tile.
-template <typename WT, int KIT, typename CtxF, typename LoadF, typename MixF>
+// RB: rows of a wavefront whose loads are in flight together (all RT / kWaves of them, or fewer
+// where a row's loads take many registers; the rounds then follow each other).
+template <typename WT, int KIT, int RB, typename CtxF, typename LoadF, typename MixF>
 __device__ inline void stage_segment_impl(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
 {
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int Kpad = ((K + 31) / 32) * 32;
     constexpr int RPW = RT / kWaves;    // rows per wavefront
-    decltype(ctx(0)) c[RPW];
+    static_assert(RPW % RB == 0, "rows per round must divide the rows of a wavefront");
 #pragma unroll
-    for (int ii = 0; ii < RPW; ++ii) {
-        const int i = wave + ii * kWaves;
-        c[ii] = ctx(i < nrows ? i : 0);
-    }
-    decltype(load(c[0], 0)) v[RPW][KIT];
+    for (int i0 = 0; i0 < RPW; i0 += RB) {
+        decltype(ctx(0)) c[RB];
 #pragma unroll
-    for (int ii = 0; ii < RPW; ++ii)
-        if (wave + ii * kWaves < nrows) {
-#pragma unroll
-            for (int kk = 0; kk < KIT; ++kk) {
-                const int k = lane * 2 + kk * 128;
-                v[ii][kk] = load(c[ii], k < K ? k : K - 2);
-            }
+        for (int ii = 0; ii < RB; ++ii) {
+            const int i = wave + (i0 + ii) * kWaves;
+            c[ii] = ctx(i < nrows ? i : 0);
         }
-    __builtin_amdgcn_sched_barrier(0);
-    TR(60);
+        decltype(load(c[0], 0)) v[RB][KIT];
+#pragma unroll
+        for (int ii = 0; ii < RB; ++ii)
+            if (wave + (i0 + ii) * kWaves < nrows) {
+#pragma unroll
+                for (int kk = 0; kk < KIT; ++kk) {
+                    const int k = lane * 2 + kk * 128;
+                    v[ii][kk] = load(c[ii], k < K ? k : K - 2);
+                }
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        TR(60);
 #if TDT_TRACE
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    TR(61);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        TR(61);
 #endif
 #pragma unroll
-    for (int ii = 0; ii < RPW; ++ii)
-        if (wave + ii * kWaves < nrows) {
+        for (int ii = 0; ii < RB; ++ii)
+            if (wave + (i0 + ii) * kWaves < nrows) {
 #pragma unroll
-            for (int kk = 0; kk < KIT; ++kk) {
-                const int i = wave + ii * kWaves, k = lane * 2 + kk * 128;
-                const float2 x = mix(c[ii], k < K ? k : K - 2, v[ii][kk]);
-                if (k < Kpad) A.store2(i, k, make_float2(k < K ? x.x : 0.0f, k < K ? x.y : 0.0f));
+                for (int kk = 0; kk < KIT; ++kk) {
+                    const int i = wave + (i0 + ii) * kWaves, k = lane * 2 + kk * 128;
+                    const float2 x = mix(c[ii], k < K ? k : K - 2, v[ii][kk]);
+                    if (k < Kpad) A.store2(i, k, make_float2(k < K ? x.x : 0.0f, k < K ? x.y : 0.0f));
+                }
             }
-        }
+    }
 }
 
-template <typename WT, typename CtxF, typename LoadF, typename MixF>
+template <typename WT, int RB = RT / kWaves, typename CtxF, typename LoadF, typename MixF>
 __device__ inline void stage_segment(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
 {
     // 64 lanes x 2 inputs per step: pick the unrolling that covers K without spare loads
-    if (K <= 640) stage_segment_impl<WT, 5>(A, K, nrows, ctx, load, mix);
-    else stage_segment_impl<WT, KSEG / 128>(A, K, nrows, ctx, load, mix);
+    if (K <= 640) stage_segment_impl<WT, 5, RB>(A, K, nrows, ctx, load, mix);
+    else stage_segment_impl<WT, KSEG / 128, RB>(A, K, nrows, ctx, load, mix);
 }
 
 // accumulators of one wavefront for one 16x16 tile
