@@ -27,22 +27,62 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
-def algorithmic_bytes(cfg, stats) -> float:
-    """Bytes the method has to move for the passes the decode kernel executed:
-    per predictor pass the LSTM matrices and the predictor projection, per joint
-    pass the output matrix, plus one gathered enc_proj row (float32) per scored
-    (hypothesis, frame) row and the predictor rows' state."""
+def matrix_bytes(cfg):
+    """Bytes of the matrices the decode kernel streams: per predictor pass (the recurrent matrix of
+    the first LSTM layer -- its input product is a per-label table --, both matrices of every
+    deeper layer and the predictor projection; nothing for a stateless predictor, whose
+    projected output is tabulated per label) and per joint pass (the output matrix)."""
     wb = 2 if cfg.dtype == "bf16" else 4
-    H, Hp, E, O = cfg.h_joint, cfg.h_pred, cfg.emb_dim, cfg.n_out
-    pred = H * Hp * wb
+    H, Hp, O = cfg.h_joint, cfg.h_pred, cfg.n_out
+    pred = 0
     if cfg.pred_kind == "lstm":
-        in_dim = E
-        for _ in range(cfg.pred_layers):
-            pred += 4 * Hp * (in_dim + Hp) * wb
-            in_dim = Hp
-    joint = O * H * wb
-    return (stats["pred_passes"] * pred + stats["joint_passes"] * joint
-            + stats["joint_rows"] * H * 4 + stats["pred_rows"] * Hp * 4)
+        pred = H * Hp * wb + 4 * Hp * Hp * wb + (cfg.pred_layers - 1) * 8 * Hp * Hp * wb
+    return pred, O * H * wb
+
+
+def row_bytes(cfg):
+    """Bytes per predictor row (LSTM: the label's table row of the first layer, the recurrent
+    pre-activations, cell state read and written, hidden state written, per layer) and per scored
+    (hypothesis, frame) row (the projected encoder frame and the projected predictor output, or
+    the table rows that make it up), all float32."""
+    H, Hp = cfg.h_joint, cfg.h_pred
+    if cfg.pred_kind == "lstm":
+        return cfg.pred_layers * (4 + 4 + 2 + 1) * Hp * 4, 2 * H * 4
+    return 0, (1 + cfg.pred_layers) * H * 4
+
+
+def algorithmic_bytes(cfg, stats):
+    """Two counts of the bytes the method has to move for the passes the decode kernel executed.
+    `per_group_pass`: every pass of every hypothesis group streams the matrices (each group runs
+    its own label loop); it grows with the number of groups at constant time.  `one_stream_per_step`:
+    the matrices once per dependent step of the slowest group -- its label-loop iterations and its
+    joint passes -- which does not depend on how the batch is split.  Both include the per-row
+    bytes of all rows."""
+    pred, joint = matrix_bytes(cfg)
+    prow, jrow = row_bytes(cfg)
+    rows = stats["pred_rows"] * prow + stats["joint_rows"] * jrow
+    per_group = stats["pred_passes"] * pred + stats["joint_passes"] * joint + rows
+    one_stream = stats["outer_max"] * pred + stats["joint_passes_max"] * joint + rows
+    return float(per_group), float(one_stream)
+
+
+def roofline_block(cfg, stats, kernel_ms, kernel_ms_min=None):
+    per_group, one_stream = algorithmic_bytes(cfg, stats)
+    k_s = kernel_ms * 1e-3
+    blk = {"bound": "hbm", "kernel": "decode_kernel",
+           "achieved": per_group / k_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": per_group / k_s / 1e9 / HBM_PEAK_GBS,
+           "algorithmic_bytes_per_launch": per_group,
+           "achieved_one_stream_per_step": one_stream / k_s / 1e9,
+           "frac_one_stream_per_step": one_stream / k_s / 1e9 / HBM_PEAK_GBS,
+           "algorithmic_bytes_one_stream_per_step": one_stream,
+           "kernel_ms": kernel_ms,
+           "traffic": traffic_from_profiles(cfg.name),
+           "traffic_source": "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE / WRITE_SIZE of an earlier "
+                             "run of this command, not measured in this run)"}
+    if kernel_ms_min is not None:
+        blk["kernel_ms_min"] = kernel_ms_min
+    return blk
 
 
 def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0, algorithm=0, projections=0):
@@ -190,6 +230,33 @@ def cpu_baseline(res, min_seconds=10.0, max_runs=64):
                 labels_match_gpu=bool(same))
 
 
+def describe(cfg):
+    return (f"{cfg.name}: B={cfg.B} T={cfg.T} d_enc={cfg.d_enc} {cfg.pred_kind}x{cfg.pred_layers} "
+            f"h_pred={cfg.h_pred} H={cfg.h_joint} V={cfg.vocab} D={cfg.n_dur} S={cfg.max_symbols}, "
+            f"{cfg.dtype} weights, fp32 accumulation")
+
+
+def config_block(cfg, r):
+    """The figures of one workload as time_workload measured it."""
+    st = r["out"]["stats"]
+    return {"workload": describe(cfg), "value": r["frames"] / r["sec_per_step"], "unit": "frames/s",
+            "ms_per_step": r["sec_per_step"] * 1e3, "us_per_batch": r["sec_per_step"] * 1e6,
+            "frames_per_batch": r["frames"], "labels_per_batch": int(r["out"]["len"].sum()),
+            "roofline": roofline_block(cfg, st, r["decode_kernel_ms"], r["decode_kernel_ms_min"]),
+            "enc_proj": enc_proj_figures(cfg, r["enc_proj_ms"]),
+            "decode_stats": st}
+
+
+def release_device_memory():
+    """Give what the finished workloads held back to the driver (the large configuration needs
+    several GB)."""
+    import gc
+    import torch
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
+
 def traffic_from_profiles(name):
     """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -209,6 +276,9 @@ def main():
     ap.add_argument("--clusters", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the B=128 line")
+    ap.add_argument("--phase-timers", action="store_true",
+                    help="load the profiling build of the library (python -m paper_2406_06220_amd.build "
+                         "--phase-timers), whose statistics carry the per-phase wall-clock ticks")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy and a 256 MiB elementwise "
                          "kernel, so that a rocprofv3 --pmc run of this command holds dispatches of "
@@ -221,6 +291,8 @@ def main():
     import torch
     from paper_2406_06220_amd import binding, synth
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.phase_timers:
+        binding.LIB_PATH = binding.TIMERS_LIB_PATH
     binding.load_library()
 
     if args.copy_calibration:
@@ -235,9 +307,6 @@ def main():
     cfg = synth.CONFIGS[args.workload]
     res = time_workload(cfg, args.steps, args.warmup, args.window, args.clusters)
     st = res["out"]["stats"]
-    alg = algorithmic_bytes(cfg, st)
-    k_s = res["decode_kernel_ms"] * 1e-3
-    achieved = alg / k_s / 1e9
     line = {
         "metric": "decoded encoder frames/sec (greedy decode only)",
         "value": res["frames"] / res["sec_per_step"],
@@ -246,38 +315,33 @@ def main():
         "ms_per_step": res["sec_per_step"] * 1e3,
         "us_per_batch": res["sec_per_step"] * 1e6,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: B={cfg.B} T={cfg.T} d_enc={cfg.d_enc} "
-                               f"{cfg.pred_kind}x{cfg.pred_layers} h_pred={cfg.h_pred} H={cfg.h_joint} "
-                               f"V={cfg.vocab} D={cfg.n_dur} S={cfg.max_symbols}, "
-                               f"{cfg.dtype} weights, fp32 accumulation",
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype_detail": ("bfloat16 weights and encoder output on the bf16 matrix cores; float32 activations, each "
+                         "split exactly into three bfloat16 terms; float32 accumulation"
+                         if cfg.dtype == "bf16" else "float32 throughout, float32 matrix-core products"),
+        "config": {"workload": describe(cfg),
                    "frames_per_batch": res["frames"],
                    "labels_per_batch": int(res["out"]["len"].sum()),
                    "window": args.window or "auto", "clusters": args.clusters or "auto"},
         "decode_stats": st,
-        "roofline": {"bound": "hbm", "kernel": "decode_kernel",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "algorithmic_bytes_per_launch": alg,
-                     "kernel_ms": res["decode_kernel_ms"],
-                     "kernel_ms_min": res["decode_kernel_ms_min"],
-                     "traffic": traffic_from_profiles(cfg.name)},
+        "roofline": roofline_block(cfg, st, res["decode_kernel_ms"], res["decode_kernel_ms_min"]),
         "enc_proj": enc_proj_figures(cfg, res["enc_proj_ms"]),
     }
     if not args.no_extra and args.workload == "cfg2_rnnt_lstm":
         cfg_b = synth.CONFIGS["cfg2_rnnt_lstm_b128"]
         rb = time_workload(cfg_b, max(args.steps // 2, 3), max(args.warmup, 1), args.window, args.clusters)
-        alg_b = algorithmic_bytes(cfg_b, rb["out"]["stats"])
-        ach_b = alg_b / (rb["decode_kernel_ms"] * 1e-3) / 1e9
-        line["b128"] = {"workload": cfg_b.name, "value": rb["frames"] / rb["sec_per_step"],
-                        "unit": "frames/s", "us_per_batch": rb["sec_per_step"] * 1e6,
-                        "frames_per_batch": rb["frames"],
-                        "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": ach_b,
-                                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach_b / HBM_PEAK_GBS,
-                                     "algorithmic_bytes_per_launch": alg_b,
-                                     "kernel_ms": rb["decode_kernel_ms"],
-                                     "traffic": traffic_from_profiles(cfg_b.name)},
-                        "decode_stats": rb["out"]["stats"]}
+        line["b128"] = config_block(cfg_b, rb)
+        del rb
+        # the other benchmark configurations (the TDT model at both batch sizes, the stateless
+        # model, the large TDT model), each timed like the headline workload, fewer steps
+        line["configs"] = {}
+        for name, steps in (("cfg3_tdt_lstm", 10), ("cfg3_tdt_lstm_b128", 10), ("cfg4_rnnt_stateless", 10),
+                            ("cfg5_large_tdt", 3)):
+            c = synth.CONFIGS[name]
+            r = time_workload(c, min(steps, args.steps), 1)
+            line["configs"][name] = config_block(c, r)
+            del r
+            release_device_memory()
         # the same batch fed piece by piece (50 frames = 2 s of audio at config 2's frame rate)
         line["chunked"] = time_chunked(cfg, 50, max(args.steps // 2, 3), max(args.warmup, 1))
         line["chunked"]["labels_match_whole"] = bool(line["chunked"]["labels"] == int(res["out"]["len"].sum()))
@@ -306,6 +370,12 @@ def main():
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(res)
     print(json.dumps(line))
+    sys.stdout.flush()
+    # Nothing of this program's should still hold device memory, events or streams when the
+    # interpreter runs its exit handlers (under a profiler the runtime may be finalised before
+    # them): drop the tensors, drain the device, return the cached blocks.
+    del res
+    release_device_memory()
 
 
 if __name__ == "__main__":

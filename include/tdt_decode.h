@@ -171,6 +171,7 @@ enum tdt_stat {
     TDT_STAT_JOINT_PASSES = 2, /* batched joint passes executed (Alg. 3 lines 7 and 13) */
     TDT_STAT_JOINT_ROWS = 3,  /* (hypothesis, frame) rows those passes scored */
     TDT_STAT_OUTER_MAX = 4,   /* largest number of label-loop iterations of any group */
+    TDT_STAT_JOINT_PASSES_MAX = 6, /* largest number of joint passes of any group */
     TDT_STAT_ABORT = 5,       /* non-zero if an internal wait timed out (the hypotheses of the groups
                                  concerned carry TDT_HYP_ABORTED in out_status) */
     /* library builds with phase timers only (-DTDT_PHASE_TIMERS=1; zero otherwise, because

@@ -17,10 +17,13 @@ from . import synth
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtdt_decode.so")
+# the same library built with -DTDT_PHASE_TIMERS=1 (``python -m paper_2406_06220_amd.build --phase-timers``);
+# set LIB_PATH to it before the first call to get the per-phase ticks in the statistics
+TIMERS_LIB_PATH = os.path.join(_PKG, "libtdt_decode_timers.so")
 
 TDT_MAX_LSTM_LAYERS = 4
 TDT_STAT_NAMES = {"pred_passes": 0, "pred_rows": 1, "joint_passes": 2, "joint_rows": 3,
-                  "outer_max": 4, "abort": 5, "ticks_pred": 8, "ticks_proj": 9, "ticks_joint": 10,
+                  "outer_max": 4, "abort": 5, "joint_passes_max": 6, "ticks_pred": 8, "ticks_proj": 9, "ticks_joint": 10,
                   "ticks_decide": 11, "ticks_barrier": 12, "ticks_total": 13,
                   **{f"ticks_{ph}_{part}": 14 + 3 * a + b
                      for a, ph in enumerate(("pred", "proj", "joint"))

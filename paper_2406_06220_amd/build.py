@@ -20,17 +20,29 @@ def sources():
     return sorted(glob.glob(os.path.join(PKG, "csrc", "*.hip")))
 
 
-def build_library(verbose: bool = False) -> str:
-    cmd = (["hipcc"] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"),
-                                      "-I", os.path.join(PKG, "csrc")] + sources() + ["-o", LIB])
+TIMERS_LIB = os.path.join(PKG, "libtdt_decode_timers.so")
+
+
+def build_library(verbose: bool = False, defines=(), out: str = LIB) -> str:
+    cmd = (["hipcc"] + HIPCC_FLAGS + [f"-D{d}" for d in defines] +
+           ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc")] + sources() + ["-o", out])
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    log = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
-    return LIB
+        raise RuntimeError("hipcc failed:\n" + log)
+    if verbose and log.strip():
+        print(log)
+    return out
+
+
+def build_timers_library(verbose: bool = False) -> str:
+    """The profiling build: the decode kernel books wall-clock ticks per phase into the statistics."""
+    return build_library(verbose, defines=("TDT_PHASE_TIMERS=1",), out=TIMERS_LIB)
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import sys
+    if "--phase-timers" in sys.argv:
+        print(build_timers_library(verbose=True))
+    else:
+        print(build_library(verbose=True))

@@ -1155,6 +1155,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             add(TDT_STAT_JOINT_ROWS, st_joint_rows);
             // every label-loop iteration takes one predictor pass
             atomicMax((unsigned long long *)&p.out_stats[TDT_STAT_OUTER_MAX], (unsigned long long)st_pred_passes);
+            atomicMax((unsigned long long *)&p.out_stats[TDT_STAT_JOINT_PASSES_MAX],
+                      (unsigned long long)st_joint_passes);
             if (!ok) add(TDT_STAT_ABORT, 1);
             if (TDT_PHASE_TIMERS && cl == 0) {   // where the first cluster's time went, in wall-clock ticks
                 add(TDT_STAT_TICKS_PRED, S.tk[kTkP]);
