@@ -125,14 +125,15 @@ def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0, alg
     dec.options.reuse_enc_proj = 0
     k_all = [a.elapsed_time(b) for a, b in ev]
     k_ms = float(np.mean(k_all))
-    # ---- the encoder projection on its own (the dense contraction of the path)
+    # ---- the encoder projection on its own (the dense contraction of the path), as the decode
+    #      call runs it: over the valid frames of every utterance
     proj = torch.empty((cfg.B * cfg.T, cfg.h_joint), dtype=torch.float32, device=dev)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(steps)]
     for a, b in ev:
         a.record(stream)
-        binding.tdt_encoder_projection(enc_d.data_ptr(), cfg.B * cfg.T, model.c, proj.data_ptr(),
-                                       stream.cuda_stream)
+        binding.tdt_encoder_projection_valid(enc_d.data_ptr(), len_d.data_ptr(), cfg.B, cfg.T, model.c,
+                                             proj.data_ptr(), stream.cuda_stream)
         b.record(stream)
     torch.cuda.synchronize(dev)
     e_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
@@ -140,9 +141,8 @@ def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0, alg
                 decode_kernel_ms_min=float(np.min(k_all)), enc_proj_ms=e_ms, frames=frames, u_cap=u_cap)
 
 
-def enc_proj_figures(cfg, ms):
-    """Rates of the encoder-projection GEMM over all B*T rows (padding included, as launched)."""
-    rows = cfg.B * cfg.T
+def enc_proj_figures(cfg, ms, rows):
+    """Rates of the encoder-projection GEMM over the `rows` valid frames of the batch."""
     wb = 2 if cfg.dtype == "bf16" else 4
     flops = 2.0 * rows * cfg.d_enc * cfg.h_joint
     nbytes = rows * cfg.d_enc * wb + cfg.d_enc * cfg.h_joint * wb + rows * cfg.h_joint * 4
@@ -243,7 +243,7 @@ def config_block(cfg, r):
             "ms_per_step": r["sec_per_step"] * 1e3, "us_per_batch": r["sec_per_step"] * 1e6,
             "frames_per_batch": r["frames"], "labels_per_batch": int(r["out"]["len"].sum()),
             "roofline": roofline_block(cfg, st, r["decode_kernel_ms"], r["decode_kernel_ms_min"]),
-            "enc_proj": enc_proj_figures(cfg, r["enc_proj_ms"]),
+            "enc_proj": enc_proj_figures(cfg, r["enc_proj_ms"], r["frames"]),
             "decode_stats": st}
 
 
@@ -325,7 +325,7 @@ def main():
                    "window": args.window or "auto", "clusters": args.clusters or "auto"},
         "decode_stats": st,
         "roofline": roofline_block(cfg, st, res["decode_kernel_ms"], res["decode_kernel_ms_min"]),
-        "enc_proj": enc_proj_figures(cfg, res["enc_proj_ms"]),
+        "enc_proj": enc_proj_figures(cfg, res["enc_proj_ms"], res["frames"]),
     }
     if not args.no_extra and args.workload == "cfg2_rnnt_lstm":
         cfg_b = synth.CONFIGS["cfg2_rnnt_lstm_b128"]

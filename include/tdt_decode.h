@@ -203,7 +203,8 @@ int tdt_workspace_bytes(const tdt_weights_t *weights, int B, int T, int u_cap, s
  * batched hypothesis arrays the outputs mirror).
  *
  *   enc         DEVICE [B][T][d_enc], dtype per weights->dtype.  Frames at or
- *               beyond enc_len[b] are never read.
+ *               beyond enc_len[b] are never read (nor projected: the encoder projection
+ *               walks the valid frames only).
  *   enc_len     DEVICE [B] int32 valid frames per utterance; values outside
  *               [0, T] are clamped and flagged in out_status.
  *   durations   HOST [n_dur] frame increments of the duration classes
@@ -312,6 +313,15 @@ int tdt_greedy_decode_chunk(const void *enc, const int32_t *enc_len, int B, int 
  */
 int tdt_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *weights,
                            float *out, void *stream);
+
+/*
+ * The same projection as the decode calls run it (Alg. 3 line 2 on utterances of different
+ * lengths): enc DEVICE [B][T][d_enc], enc_len DEVICE [B]; out DEVICE [B][T][h_joint] float32, of
+ * which only rows t < min(max(enc_len[b], 0), T) are written -- frames beyond an utterance's
+ * length are neither read nor written.  B * T must not exceed 2^31.
+ */
+int tdt_encoder_projection_valid(const void *enc, const int32_t *enc_len, int B, int T,
+                                 const tdt_weights_t *weights, float *out, void *stream);
 
 /* Static, human-readable name of a status code. */
 const char *tdt_status_string(int status);

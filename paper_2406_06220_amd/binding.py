@@ -38,7 +38,8 @@ TDT_ERR_TOO_LARGE = -7
 TDT_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ("tdt_workspace_bytes", "tdt_greedy_decode", "tdt_greedy_decode_static", "tdt_state_bytes",
-           "tdt_greedy_decode_chunk", "tdt_encoder_projection", "tdt_status_string")
+           "tdt_greedy_decode_chunk", "tdt_encoder_projection", "tdt_encoder_projection_valid",
+           "tdt_status_string")
 
 
 class tdt_weights_t(C.Structure):
@@ -95,6 +96,9 @@ def load_library():
         lib.tdt_encoder_projection.restype = C.c_int
         lib.tdt_encoder_projection.argtypes = [C.c_void_p, C.c_int64, C.POINTER(tdt_weights_t),
                                                C.c_void_p, C.c_void_p]
+        lib.tdt_encoder_projection_valid.restype = C.c_int
+        lib.tdt_encoder_projection_valid.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                                     C.POINTER(tdt_weights_t), C.c_void_p, C.c_void_p]
         lib.tdt_status_string.restype = C.c_char_p
         lib.tdt_status_string.argtypes = [C.c_int]
         _lib = lib
@@ -128,6 +132,12 @@ def tdt_workspace_bytes(weights: tdt_weights_t, B: int, T: int, u_cap: int) -> i
 def tdt_encoder_projection(enc_ptr: int, rows: int, weights: tdt_weights_t, out_ptr: int,
                            stream: int = 0) -> None:
     _check(load_library().tdt_encoder_projection(enc_ptr, rows, C.byref(weights), out_ptr, stream))
+
+
+def tdt_encoder_projection_valid(enc_ptr: int, enc_len_ptr: int, B: int, T: int, weights: tdt_weights_t,
+                                 out_ptr: int, stream: int = 0) -> None:
+    _check(load_library().tdt_encoder_projection_valid(enc_ptr, enc_len_ptr, B, T, C.byref(weights), out_ptr,
+                                                       stream))
 
 
 def tdt_greedy_decode(enc_ptr: int, enc_len_ptr: int, B: int, T: int, weights: tdt_weights_t,

@@ -22,24 +22,87 @@ namespace {
 constexpr int BM = 128, BN = 128, BK = 64;   // workgroup tile
 constexpr int GEMM_THREADS = 256;            // 4 wavefronts, each a 64x64 sub-tile
 
-// 16-byte chunk index c of a row is stored at chunk (c ^ (row & 7)) so that the
-// 32 rows a wavefront reads for one k-slice spread over all LDS banks.
-__device__ inline int lds_off(int row, int chunk) { return row * BK + ((chunk ^ (row & 7)) << 3); }
+// A tile row is 128 bytes, half of the 64 four-byte LDS banks; rows r and r + 1 lie in different
+// halves.  16-byte chunk c of row r is stored at chunk c ^ ((r >> 1) & 7), so that the 16 rows a
+// quarter of a wavefront reads for one k-slice (same c, consecutive r) fall on 16 different
+// chunk positions, i.e. on all 64 banks.
+__device__ inline int lds_off(int row, int chunk) { return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3); }
 
 // One product C = A * W^T + bias and the workgroups it takes.  Rows of W are ldw apart (a
 // slice of the columns of a wider matrix can be multiplied); bias may be null.
+// With `lens` the rows are the frames of B utterances of T frames each, of which only the first
+// min(max(lens[b], 0), T) of utterance b are multiplied (Alg. 3 line 2 projects the encoder
+// output; frames beyond an utterance's length are never looked at, so they are neither read nor
+// written): the workgroups then walk the valid frames in order, 128 at a time, and M = B * T only
+// bounds their number.
 struct LinearProblem {
     const uint16_t *A, *W;
     const float *bias;
     float *C;
     long long M;
     int N, K, ldw, group;
+    const int32_t *lens;
+    int B, T;
     unsigned blocks;
 };
 constexpr int kMaxProblems = 3;   // products one preparation launch can hold
 struct LinearBatch {
     LinearProblem q[kMaxProblems];
 };
+
+// Which frames rows m0 .. m0 + ROWS - 1 of the packed sequence of valid frames are: row_of[i] =
+// b * T + t, or -1 beyond the last valid frame.  Called by all GEMM_THREADS threads of a workgroup;
+// returns false (for all of them) if the tile holds no valid frame at all.  Every thread sums a
+// stretch of the utterances' lengths, the stretches' sums are scanned across the workgroup, and
+// each row finds its utterance by a search over the stretches and a walk through its stretch.
+template <int ROWS>
+__device__ inline bool valid_row_map(const int32_t *lens, int B, int T, long long m0, long long *row_of, int *scan,
+                                     int *wsum)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (B + GEMM_THREADS - 1) / GEMM_THREADS;
+    const int b_lo = min(tid * per, B), b_hi = min(b_lo + per, B);
+    int mine = 0;   // B * T < 2^31, so every sum of lengths fits an int
+    for (int b = b_lo; b < b_hi; ++b) mine += min(max(lens[b], 0), T);
+    int v = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(v, off, 64);
+        if (lane >= off) v += t;
+    }
+    if (lane == 63) wsum[wave] = v;
+    __syncthreads();
+    int base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < GEMM_THREADS / 64; ++w) {
+        if (w < wave) base += wsum[w];
+        total += wsum[w];
+    }
+    scan[tid] = base + v - mine;   // valid frames before stretch tid
+    __syncthreads();
+    if (m0 >= total) return false;
+    if (tid < ROWS) {
+        const long long m = m0 + tid;
+        long long src = -1;
+        if (m < total) {
+            int lo = 0, hi = GEMM_THREADS - 1;   // the last stretch that starts at or before m
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (scan[mid] <= m) lo = mid; else hi = mid - 1;
+            }
+            long long before = scan[lo];
+            int b = min(lo * per, B);
+            for (;; ++b) {   // ends, because m < total
+                const int len = min(max(lens[b], 0), T);
+                if (m < before + len) break;
+                before += len;
+            }
+            src = (long long)b * T + (m - before);
+        }
+        row_of[tid] = src;
+    }
+    return true;
+}
 
 // the 128 x 128 output tile of workgroup `block` (of q.blocks) of one product
 __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
@@ -50,8 +113,21 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
     float *__restrict__ C = q.C;
     const long long M = q.M;
     const int N = q.N, K = q.K, ldw = q.ldw, group = q.group;
-    __shared__ __align__(16) uint16_t As[BM * BK];
-    __shared__ __align__(16) uint16_t Bs[BN * BK];
+    // the operand tiles (two buffers each) and, once the products are done, the output tile on
+    // its way to memory share one block of LDS
+    constexpr int CLD = BN + 4;   // floats per row of the output tile (padded: rows 8 apart meet other banks)
+    constexpr size_t kTileBytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t);
+    constexpr size_t kOutBytes = (size_t)BM * CLD * sizeof(float);
+    __shared__ __align__(16) unsigned char lds_raw[kOutBytes > kTileBytes ? kOutBytes : kTileBytes];
+    uint16_t (*As)[BM * BK] = reinterpret_cast<uint16_t (*)[BM * BK]>(lds_raw);
+    uint16_t (*Bs)[BN * BK] = reinterpret_cast<uint16_t (*)[BN * BK]>(lds_raw + 2 * (size_t)BM * BK * sizeof(uint16_t));
+    float *Cs = reinterpret_cast<float *>(lds_raw);
+    __shared__ long long row_of[BM];   // source / destination row of each row of the tile, -1: none
+    __shared__ int scan[GEMM_THREADS], wsum[GEMM_THREADS / 64];
+#ifdef TDT_GEMM_PAD_LDS
+    __shared__ int pad_lds[TDT_GEMM_PAD_LDS];
+    if (threadIdx.x == 9999) pad_lds[threadIdx.x] = 0;
+#endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     // 1-D grid.  Consecutive workgroups go to consecutive XCDs, each with an L2 of its own, so
@@ -65,6 +141,12 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
     const long long m0 = mt * BM;
     const int n0 = (int)(j % nt_n) * BN;
     if (m0 >= M) return;   // the last round of row tiles may be partial (uniform over the workgroup)
+    if (q.lens) {
+        if (!valid_row_map<BM>(q.lens, q.B, q.T, m0, row_of, scan, wsum)) return;   // uniform
+    } else if (tid < BM) {
+        row_of[tid] = m0 + tid < M ? m0 + tid : -1;
+    }
+    __syncthreads();
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -74,37 +156,37 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    uint4 ra[4], rb[4];
-    auto load_tiles = [&](int k0) {
+    // Two register sets and two LDS buffers: K tile kt is multiplied from LDS while tile kt + 1
+    // sits in (or is still on its way into) one register set and tile kt + 2 is being requested
+    // into the other -- at this kernel's few hundred bytes per flop-microsecond it is the number
+    // of bytes in flight per compute unit that decides how much of the HBM rate it gets.
+    uint4 ra[2][4], rb[2][4];
+    long long a_row[4];   // source row of the tile rows this thread loads
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a_row[j] = row_of[(tid + j * GEMM_THREADS) >> 3];
+    auto load_tiles = [&](int k0, uint4 (&xa)[4], uint4 (&xb)[4]) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int c = tid + j * GEMM_THREADS;   // 0..1023
             const int row = c >> 3, kc = c & 7;
             const int k = k0 + kc * 8;
-            const long long m = m0 + row;
             const int n = n0 + row;
-            ra[j] = (m < M && k < K) ? *reinterpret_cast<const uint4 *>(A + m * K + k)
-                                     : make_uint4(0, 0, 0, 0);
-            rb[j] = (n < N && k < K) ? *reinterpret_cast<const uint4 *>(W + (long long)n * ldw + k)
+            xa[j] = (a_row[j] >= 0 && k < K) ? *reinterpret_cast<const uint4 *>(A + a_row[j] * K + k)
+                                             : make_uint4(0, 0, 0, 0);
+            xb[j] = (n < N && k < K) ? *reinterpret_cast<const uint4 *>(W + (long long)n * ldw + k)
                                      : make_uint4(0, 0, 0, 0);
         }
     };
-    auto store_tiles = [&]() {
+    auto store_tiles = [&](int buf, const uint4 (&xa)[4], const uint4 (&xb)[4]) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int c = tid + j * GEMM_THREADS;
             const int row = c >> 3, kc = c & 7;
-            *reinterpret_cast<uint4 *>(As + lds_off(row, kc)) = ra[j];
-            *reinterpret_cast<uint4 *>(Bs + lds_off(row, kc)) = rb[j];
+            *reinterpret_cast<uint4 *>(As[buf] + lds_off(row, kc)) = xa[j];
+            *reinterpret_cast<uint4 *>(Bs[buf] + lds_off(row, kc)) = xb[j];
         }
     };
-
-    const int nk = (K + BK - 1) / BK;
-    load_tiles(0);
-    for (int kt = 0; kt < nk; ++kt) {
-        store_tiles();
-        __syncthreads();
-        if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+    auto products = [&](int buf) {
 #pragma unroll
         for (int s = 0; s < BK / 16; ++s) {
             const int chunk = s * 2 + (lane >> 5);
@@ -113,8 +195,8 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
             for (int i = 0; i < 2; ++i) {
                 const int ar = wm * 64 + i * 32 + (lane & 31);
                 const int br = wn * 64 + i * 32 + (lane & 31);
-                a[i] = *reinterpret_cast<const bf16x8 *>(As + lds_off(ar, chunk));
-                b[i] = *reinterpret_cast<const bf16x8 *>(Bs + lds_off(br, chunk));
+                a[i] = *reinterpret_cast<const bf16x8 *>(As[buf] + lds_off(ar, chunk));
+                b[i] = *reinterpret_cast<const bf16x8 *>(Bs[buf] + lds_off(br, chunk));
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -122,27 +204,84 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
+    };
+
+    const int nk = (K + BK - 1) / BK;
+    load_tiles(0, ra[0], rb[0]);
+    if (nk > 1) load_tiles(BK, ra[1], rb[1]);
+    store_tiles(0, ra[0], rb[0]);
+    __syncthreads();
+    // two K tiles per trip, so that the register sets are named at compile time; one workgroup
+    // barrier per K tile (the buffer written after the products was last read before the
+    // previous barrier)
+    for (int kt = 0; kt < nk; kt += 2) {
+        if (kt + 2 < nk) load_tiles((kt + 2) * BK, ra[0], rb[0]);
+        products(0);
+        if (kt + 1 < nk) store_tiles(1, ra[1], rb[1]);
         __syncthreads();
+        if (kt + 1 < nk) {
+            if (kt + 3 < nk) load_tiles((kt + 3) * BK, ra[1], rb[1]);
+            products(1);
+            if (kt + 2 < nk) store_tiles(0, ra[0], rb[0]);
+            __syncthreads();
+        }
     }
 
     // accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32
+    if (group > 0) {
+        // outputs regrouped column by column (the LSTM table): scattered four-byte stores
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+                if (n >= N) continue;
+                const float bn = bias ? bias[n] : 0.0f;
+                const int nc = (n % group) * (N / group) + n / group;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const long long dst = row_of[wm * 64 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)];
+                    if (dst >= 0) C[dst * N + nc] = acc[i][j][e] + bn;
+                }
+            }
+        return;
+    }
+    // The output tile goes through LDS so that it leaves as whole rows: a lane then stores 16
+    // bytes, half a wavefront one 512-byte row, and the row's destination is looked up once per
+    // row instead of once per element.  (The operand tiles are dead: every wavefront has passed
+    // the barrier that followed the last products.)
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = n0 + wn * 64 + j * 32 + (lane & 31);
-            if (n >= N) continue;
-            const float bn = bias ? bias[n] : 0.0f;
-            const int nc = group > 0 ? (n % group) * (N / group) + n / group : n;
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const long long m = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                if (m < M) C[m * N + nc] = acc[i][j][e] + bn;
+                const int r = wm * 64 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                Cs[r * CLD + wn * 64 + j * 32 + (lane & 31)] = acc[i][j][e];
             }
+    __syncthreads();
+    {
+        const int c4 = (lane & 31) * 4;                 // this lane's four columns of the tile
+        const int n = n0 + c4;
+        float4 bn = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (bias && n < N) {                            // N is a multiple of 8, so n + 3 < N too
+            bn = *reinterpret_cast<const float4 *>(bias + n);
         }
+#pragma unroll 4
+        for (int it = 0; it < BM / (2 * GEMM_THREADS / 64); ++it) {
+            const int r = (it * (GEMM_THREADS / 64) + wave) * 2 + (lane >> 5);
+            const long long dst = row_of[r];
+            float4 v = *reinterpret_cast<const float4 *>(Cs + r * CLD + c4);
+            v.x += bn.x;
+            v.y += bn.y;
+            v.z += bn.z;
+            v.w += bn.w;
+            if (dst >= 0 && n < N) *reinterpret_cast<float4 *>(C + dst * N + n) = v;
+        }
+    }
 }
 
-__global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(LinearProblem q)
+__global__ __launch_bounds__(GEMM_THREADS, 2) void enc_proj_bf16_kernel(LinearProblem q)
 {
     gemm_tile_bf16(q, blockIdx.x);
 }
@@ -152,7 +291,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void enc_proj_bf16_kernel(LinearProbl
 // absent), and the clearing of the workspace's zero region and of the statistics.  The tasks
 // are independent; a workgroup takes its task from its index.  Every product's workgroup count
 // is a multiple of the number of dies, so each keeps its die-aware order of tiles.
-__global__ __launch_bounds__(GEMM_THREADS) void prepare_bf16_kernel(LinearBatch batch, uint4 *zero, size_t n16,
+__global__ __launch_bounds__(GEMM_THREADS, 2) void prepare_bf16_kernel(LinearBatch batch, uint4 *zero, size_t n16,
                                                                    long long *out_stats)
 {
     unsigned b = blockIdx.x, used = 0;
@@ -171,17 +310,26 @@ __global__ __launch_bounds__(GEMM_THREADS) void prepare_bf16_kernel(LinearBatch 
     if (out_stats && zb == 0 && threadIdx.x < TDT_STAT_COUNT) out_stats[threadIdx.x] = 0;
 }
 
-// float32 models (small): classic 64x64 tile, 4x4 outputs per thread.
-__global__ __launch_bounds__(256) void enc_proj_f32_kernel(
+// float32 models (small): classic 64x64 tile, 4x4 outputs per thread.  lens as in LinearProblem
+// (null: all M rows).
+__global__ __launch_bounds__(GEMM_THREADS) void enc_proj_f32_kernel(
     const float *__restrict__ A, const float *__restrict__ W, const float *__restrict__ bias,
-    float *__restrict__ C, long long M, int N, int K, int ldw, int group)
+    float *__restrict__ C, long long M, int N, int K, int ldw, int group, const int32_t *lens, int B, int T)
 {
     __shared__ float As[16][65];
     __shared__ float Ws[16][65];
+    __shared__ long long row_of[64];
+    __shared__ int scan[GEMM_THREADS], wsum[GEMM_THREADS / 64];
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     const int nt_n = (N + 63) / 64;
     const long long m0 = (long long)(blockIdx.x / nt_n) * 64;
     const int n0 = (blockIdx.x % nt_n) * 64;
+    if (lens) {
+        if (!valid_row_map<64>(lens, B, T, m0, row_of, scan, wsum)) return;   // uniform
+    } else if (tid < 64) {
+        row_of[tid] = m0 + tid < M ? m0 + tid : -1;
+    }
+    __syncthreads();
     float acc[4][4] = {};
     for (int k0 = 0; k0 < K; k0 += 16) {
 #pragma unroll
@@ -189,9 +337,9 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
             const int idx = tid + j * 256;
             const int row = idx >> 4, kk = idx & 15;
             const int k = k0 + kk;
-            const long long m = m0 + row;
+            const long long m = row_of[row];
             const int n = n0 + row;
-            As[kk][row] = (m < M && k < K) ? A[m * K + k] : 0.0f;
+            As[kk][row] = (m >= 0 && k < K) ? A[m * K + k] : 0.0f;
             Ws[kk][row] = (n < N && k < K) ? W[(long long)n * ldw + k] : 0.0f;
         }
         __syncthreads();
@@ -211,8 +359,8 @@ __global__ __launch_bounds__(256) void enc_proj_f32_kernel(
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const long long m = m0 + ty * 4 + i;
-        if (m >= M) continue;
+        const long long m = row_of[ty * 4 + i];
+        if (m < 0) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + tx * 4 + j;
@@ -241,13 +389,18 @@ static LinearProblem linear_problem(const void *a, int64_t rows, int K, const vo
     return q;
 }
 
-hipError_t launch_prepare_bf16(const void *enc, int64_t rows, const tdt_weights_t *w, float *enc_proj,
-                               float *emb_gates, float *pred_tab, void *zero_begin, size_t zero_bytes,
-                               long long *out_stats, hipStream_t stream)
+hipError_t launch_prepare_bf16(const void *enc, const int32_t *enc_len, int B, int T, const tdt_weights_t *w,
+                               float *enc_proj, float *emb_gates, float *pred_tab, void *zero_begin,
+                               size_t zero_bytes, long long *out_stats, hipStream_t stream)
 {
     LinearBatch batch{};
     int n = 0;
-    batch.q[n++] = linear_problem(enc, rows, w->d_enc, w->w_enc, w->d_enc, w->h_joint, w->b_enc, 0, enc_proj);
+    // (B == 0: no encoder projection in this launch)
+    batch.q[n] = linear_problem(enc, (int64_t)B * T, w->d_enc, w->w_enc, w->d_enc, w->h_joint, w->b_enc, 0, enc_proj);
+    batch.q[n].lens = enc_len;
+    batch.q[n].B = B;
+    batch.q[n].T = T;
+    ++n;
     if (w->pred_kind == TDT_PRED_LSTM) {   // stored [label][unit][gate]
         batch.q[n++] = linear_problem(w->emb, w->vocab + 1, w->emb_dim, w->w_ih[0], w->emb_dim, 4 * w->h_pred,
                                       w->b_lstm[0], w->h_pred, emb_gates);
@@ -279,8 +432,29 @@ hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int 
         hipLaunchKernelGGL(enc_proj_bf16_kernel, dim3(q.blocks), dim3(GEMM_THREADS), 0, stream, q);
     } else {
         dim3 grid((unsigned)(((N + 63) / 64) * ((rows + 63) / 64)));
-        hipLaunchKernelGGL(enc_proj_f32_kernel, grid, dim3(256), 0, stream, static_cast<const float *>(a),
-                           static_cast<const float *>(w), bias, out, (long long)rows, N, K, ldw, group);
+        hipLaunchKernelGGL(enc_proj_f32_kernel, grid, dim3(GEMM_THREADS), 0, stream, static_cast<const float *>(a),
+                           static_cast<const float *>(w), bias, out, (long long)rows, N, K, ldw, group,
+                           static_cast<const int32_t *>(nullptr), 0, 0);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_encoder_projection_valid(const void *enc, const int32_t *enc_len, int B, int T,
+                                           const tdt_weights_t *w, float *out, hipStream_t stream)
+{
+    const int64_t rows = (int64_t)B * T;
+    if (rows <= 0) return hipSuccess;
+    if (w->dtype == 1) {
+        LinearProblem q = linear_problem(enc, rows, w->d_enc, w->w_enc, w->d_enc, w->h_joint, w->b_enc, 0, out);
+        q.lens = enc_len;
+        q.B = B;
+        q.T = T;
+        hipLaunchKernelGGL(enc_proj_bf16_kernel, dim3(q.blocks), dim3(GEMM_THREADS), 0, stream, q);
+    } else {
+        dim3 grid((unsigned)(((w->h_joint + 63) / 64) * ((rows + 63) / 64)));
+        hipLaunchKernelGGL(enc_proj_f32_kernel, grid, dim3(GEMM_THREADS), 0, stream, static_cast<const float *>(enc),
+                           static_cast<const float *>(w->w_enc), w->b_enc, out, (long long)rows, w->h_joint,
+                           w->d_enc, w->d_enc, 0, enc_len, B, T);
     }
     return hipGetLastError();
 }

@@ -164,6 +164,21 @@ int tdt_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w
     return TDT_OK;
 }
 
+int tdt_encoder_projection_valid(const void *enc, const int32_t *enc_len, int B, int T,
+                                 const tdt_weights_t *weights, float *out, void *stream)
+{
+    if (!weights) return TDT_ERR_NULL;
+    const int st = check_model(weights);
+    if (st != TDT_OK) return st;
+    if (!enc || !enc_len || !out) return TDT_ERR_NULL;
+    if (check_model_pointers(weights, false) != TDT_OK) return TDT_ERR_NULL;
+    if (B < 1 || T < 1 || (int64_t)B * T > ((int64_t)1 << 31)) return TDT_ERR_SHAPE;
+    if (launch_encoder_projection_valid(enc, enc_len, B, T, weights, out, static_cast<hipStream_t>(stream)) !=
+        hipSuccess)
+        return TDT_ERR_LAUNCH;
+    return TDT_OK;
+}
+
 int tdt_state_bytes(const tdt_weights_t *weights, int B, size_t *bytes)
 {
     if (!weights || !bytes) return TDT_ERR_NULL;
@@ -276,7 +291,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     if (!reuse_enc_proj && weights->dtype == 1) {
         // one launch: the projection, the predictor side's per-label tables, the clearing
         // (projections on the fly: no rows for the projection here)
-        if (launch_prepare_bf16(enc, on_the_fly ? 0 : (int64_t)B * T, weights, enc_proj, emb_gates, pred_tab,
+        if (launch_prepare_bf16(enc, enc_len, on_the_fly ? 0 : B, T, weights, enc_proj, emb_gates, pred_tab,
                                 ws + L.zero_begin, L.zero_end - L.zero_begin,
                                 reinterpret_cast<long long *>(out_stats), s) != hipSuccess)
             return TDT_ERR_LAUNCH;
@@ -285,7 +300,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         return TDT_ERR_LAUNCH;
     }
     if (!reuse_enc_proj && weights->dtype != 1) {
-        if (!on_the_fly && launch_encoder_projection(enc, (int64_t)B * T, weights, enc_proj, s) != hipSuccess)
+        if (!on_the_fly && launch_encoder_projection_valid(enc, enc_len, B, T, weights, enc_proj, s) != hipSuccess)
             return TDT_ERR_LAUNCH;
         // first LSTM layer: its input product depends on the label only, so it is a table,
         // stored [label][unit][gate]

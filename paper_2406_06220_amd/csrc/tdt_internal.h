@@ -106,9 +106,13 @@ hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int 
 // bf16 models: encoder projection, the predictor side's per-label tables (first LSTM layer's
 // input product into emb_gates; a stateless predictor's projected output into pred_tab, which may
 // be null: then none) and the clearing of the zero region in one launch
-hipError_t launch_prepare_bf16(const void *enc, int64_t rows, const tdt_weights_t *w, float *enc_proj,
-                               float *emb_gates, float *pred_tab, void *zero_begin, size_t zero_bytes,
-                               long long *out_stats, hipStream_t stream);
+// (the projection covers frames t < enc_len[b] of each of the B utterances only; B == 0: none)
+hipError_t launch_prepare_bf16(const void *enc, const int32_t *enc_len, int B, int T, const tdt_weights_t *w,
+                               float *enc_proj, float *emb_gates, float *pred_tab, void *zero_begin,
+                               size_t zero_bytes, long long *out_stats, hipStream_t stream);
+// the encoder projection of the valid frames of B utterances (any dtype)
+hipError_t launch_encoder_projection_valid(const void *enc, const int32_t *enc_len, int B, int T,
+                                           const tdt_weights_t *w, float *out, hipStream_t stream);
 // stateless predictor: pred_tab[c][label][:] = w_pred[:, c*E .. (c+1)*E) * emb_c[label] (+ b_pred
 // in the last table), one launch per table
 hipError_t launch_pred_tables(const tdt_weights_t *w, float *pred_tab, hipStream_t stream);

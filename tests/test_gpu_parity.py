@@ -77,11 +77,67 @@ def test_encoder_projection(oracle_lib, gpu, dtype, rows, d_enc, H):
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     om = oracle_lib.OracleModel(cfg, w)
-    idx = sorted(set([0, 1, rows // 2, rows - 2, rows - 1] + list(range(0, rows, max(1, rows // 23)))))
-    for r in idx:
+    for r in range(rows):            # every row: a wrong tile anywhere must show
         ref = om.enc_proj_frame(enc[0, r])
-        np.testing.assert_allclose(got[r], ref, atol=2e-4, rtol=1e-5)
+        np.testing.assert_allclose(got[r], ref, atol=2e-4, rtol=1e-5, err_msg=f"row {r}")
     assert (got[rows:] == 7.0).all(), "rows past the end were written"
+
+
+@pytest.mark.parametrize("dtype,B,T,d_enc,H", [("bf16", 9, 150, 136, 200), ("bf16", 300, 7, 32, 40),
+                                               ("fp32", 5, 90, 24, 72)])
+def test_encoder_projection_of_valid_frames(oracle_lib, gpu, dtype, B, T, d_enc, H):
+    """tdt_encoder_projection_valid: every valid frame's row equals the oracle's, rows of padding
+    frames are left as they were, NaN in the padding of the input changes nothing."""
+    import torch
+    cfg = synth.small_config("encvalid", dtype=dtype, d_enc=d_enc, h_joint=H, seed=43, B=B, T=T,
+                             len_lo=0, len_hi=T)
+    w = synth.generate_model(cfg)
+    w["b_enc"] = np.random.default_rng(6).standard_normal(H).astype(np.float32)
+    enc, ln = synth.generate_inputs(cfg)
+    ln[0], ln[-1] = T, 0
+    for b in range(B):
+        enc[b, ln[b]:] = np.nan
+    parity.announce(f"tdt_encoder_projection_valid dtype={dtype} B={B} T={T} d_enc={d_enc} H={H}")
+    model = gpu.DeviceModel(cfg, w)
+    enc_d = model.upload_enc(enc)
+    len_d = torch.from_numpy(ln).to(model.device)
+    out = torch.full((B, T, H), 7.0, dtype=torch.float32, device=model.device)
+    gpu.tdt_encoder_projection_valid(enc_d.data_ptr(), len_d.data_ptr(), B, T, model.c, out.data_ptr(),
+                                     torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    om = oracle_lib.OracleModel(cfg, w)
+    for b in range(B):
+        for t in range(ln[b]):
+            np.testing.assert_allclose(got[b, t], om.enc_proj_frame(enc[b, t]), atol=2e-4, rtol=1e-5,
+                                       err_msg=f"utterance {b} frame {t}")
+        assert (got[b, ln[b]:] == 7.0).all(), f"padding rows of utterance {b} were written"
+
+
+@pytest.mark.parametrize("name", ["bf16", "fp32"])
+def test_padding_frames_are_neither_read_nor_needed(oracle_lib, gpu, name):
+    """Frames at or beyond an utterance's length are never read (Alg. 3 line 2 projects the
+    encoder output of the utterance, not its padding): with NaN in every padding frame the decode
+    gives the oracle's hypotheses of the clean input -- ragged lengths, several row tiles of the
+    projection, utterances of length 0 and of full length among them."""
+    if name == "bf16":
+        cfg = synth.small_config("g_pad_bf16", dtype="bf16", pred_kind="lstm", d_enc=72, h_pred=40,
+                                 emb_dim=24, h_joint=136, vocab=50, B=23, T=57, len_lo=0, len_hi=57,
+                                 seed=91, default_blank_bias=0.8, durations=(0, 1, 2))
+    else:
+        cfg = synth.small_config("g_pad_fp32", d_enc=24, h_pred=16, emb_dim=16, h_joint=40, vocab=19,
+                                 B=37, T=31, len_lo=0, len_hi=31, seed=92, default_blank_bias=0.6)
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    ln[0], ln[1] = 0, cfg.T
+    poisoned = enc.copy()
+    for b in range(cfg.B):
+        poisoned[b, ln[b]:] = np.nan
+    u_cap = cfg.T * cfg.max_symbols
+    out = run_gpu(gpu, cfg, w, poisoned, ln, u_cap)
+    res = parity.compare(oracle_lib, oracle_lib.OracleModel(cfg, w), cfg, enc, ln, out, u_cap)
+    assert res["replayed"] <= 1, res
+    assert np.isfinite(out["score"]).all()
 
 
 # ------------------------------------------------------------------ the paper's Fig. 2

@@ -23,20 +23,24 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 def test_algorithmic_bytes_closed_form():
+    """The two byte counts of the roofline figure, retyped for config 2 (one LSTM layer whose input
+    product is a per-label table, so only its recurrent matrix is streamed) and for the stateless
+    config 4 (no predictor-side matrix at all: two table rows per scored row)."""
     import bench
     cfg = synth.CONFIGS["cfg2_rnnt_lstm"]
-    stats = dict(pred_passes=3, joint_passes=5, joint_rows=70, pred_rows=11)
-    lstm = 4 * 640 * (640 + 640) * 2          # W_ih and W_hh of the one layer, bf16
-    pred = lstm + 640 * 640 * 2               # + W_pred
-    joint = 1025 * 640 * 2                    # W_out
-    assert bench.algorithmic_bytes(cfg, stats) == 3 * pred + 5 * joint + 70 * 640 * 4 + 11 * 640 * 4
-    assert pred == 7_372_800 and joint == 1_312_000     # the per-pass figures quoted in the design notes
-    cfg5 = synth.CONFIGS["cfg5_large_tdt"]
-    one = bench.algorithmic_bytes(cfg5, dict(pred_passes=1, joint_passes=0, joint_rows=0, pred_rows=0))
-    assert one == 2 * (4 * 640 * 1280 * 2) + 1024 * 640 * 2
-    f = bench.enc_proj_figures(cfg, 1.0)
-    assert abs(f["achieved_tflops"] - 2 * 8000 * 512 * 640 / 1e-3 / 1e12) < 1e-9
-    assert abs(f["achieved_gbs"] - (8000 * 512 * 2 + 512 * 640 * 2 + 8000 * 640 * 4) / 1e-3 / 1e9) < 1e-9
+    stats = dict(pred_passes=30, joint_passes=50, joint_rows=70, pred_rows=11, outer_max=7, joint_passes_max=9)
+    pred = 4 * 640 * 640 * 2 + 640 * 640 * 2      # W_hh and W_pred, bf16
+    joint = 1025 * 640 * 2                        # W_out
+    rows = 11 * 11 * 640 * 4 + 70 * 2 * 640 * 4   # table row, pre-activations, cell r/w, h | enc + pred row
+    per_group, one_stream = bench.algorithmic_bytes(cfg, stats)
+    assert per_group == 30 * pred + 50 * joint + rows
+    assert one_stream == 7 * pred + 9 * joint + rows
+    cfg = synth.CONFIGS["cfg4_rnnt_stateless"]
+    per_group, one_stream = bench.algorithmic_bytes(cfg, stats)
+    assert per_group == 50 * joint + 70 * 3 * 640 * 4
+    assert one_stream == 9 * joint + 70 * 3 * 640 * 4
+    cfg = synth.CONFIGS["cfg5_large_tdt"]          # two layers: the second streams both its matrices
+    assert bench.matrix_bytes(cfg)[0] == 1024 * 640 * 2 + 4 * 640 * 640 * 2 + 8 * 640 * 640 * 2
 
 
 def test_generators_are_seeded_and_round_to_nearest_even():
