@@ -604,10 +604,13 @@ def test_config5_large_tdt_sampled_rows(oracle_lib, gpu):
     enc, ln = synth.generate_inputs(cfg)
     u_cap = 4096
     out = run_gpu(gpu, cfg, w, enc, ln, u_cap)
-    rows = [0, 37, 101, 170, 213, 255]
+    rows = list(range(0, cfg.B, 8))          # 32 of the 256 utterances, the oracle on all host threads
     om = oracle_lib.OracleModel(cfg, w)
     res = parity.compare(oracle_lib, om, cfg, enc, ln, out, u_cap, rows=rows)
-    assert res["replayed"] <= 1, res
+    parity.announce(f"  -> {res}")
+    assert res["replayed"] <= 2, res
+    # the score budget is watched, not just met: half of the 1e-3 allowed
+    assert res["max_score_err"] <= 5e-4, res
     for b in range(cfg.B):
         n = out["len"][b]
         lab, fr = out["labels"][b, :n], out["frames"][b, :n]

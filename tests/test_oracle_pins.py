@@ -368,6 +368,42 @@ def test_replay_tolerates_only_near_ties(oracle_lib):
     assert hit >= 1
 
 
+def test_replay_tolerates_near_ties_of_the_duration_head(oracle_lib):
+    """The TDT twin of the test above (Sec. 3.3: the frame step comes from the duration head).  The
+    class of duration 2 is a copy of the class of duration 1, in model A lifted by 5e-4 (so 2 wins
+    wherever the pair is on top), in model B lowered by 5e-4 (1 wins).  The label logits are the same
+    in both, so B's hypothesis is a greedy decode of A up to near-ties of the duration head: A's
+    replay accepts it at a tolerance of 1e-3, counting the ties, and rejects it at 1e-4."""
+    cfg = synth.small_config("tie_dur", pred_kind="lstm", durations=(0, 1, 2), T=24, len_lo=24, len_hi=24,
+                             seed=33, B=3, default_blank_bias=0.4)
+    V = cfg.vocab
+    wa = synth.generate_model(cfg)
+    wa["w_out"][V + 1 + 2] = wa["w_out"][V + 1 + 1]
+    wa["b_out"][V + 1 + 1] = wa["b_out"][V + 1 + 2] = 2.0      # the pair is usually on top
+    wb = {k: v.copy() for k, v in wa.items()}
+    wa["b_out"][V + 1 + 2] += 5e-4
+    wb["b_out"][V + 1 + 2] -= 5e-4
+    enc, ln = synth.generate_inputs(cfg)
+    S, u_cap = cfg.max_symbols, cfg.T * cfg.max_symbols
+    ma, mb = oracle_lib.OracleModel(cfg, wa), oracle_lib.OracleModel(cfg, wb)
+    ra = oracle_lib.decode_batch(ma, enc, ln, S, u_cap)
+    rb = oracle_lib.decode_batch(mb, enc, ln, S, u_cap)
+    differ = 0
+    for b in range(cfg.B):
+        na, nb = ra["len"][b], rb["len"][b]
+        lab, fr = rb["labels"][b, :nb], rb["frames"][b, :nb]
+        same = na == nb and (lab == ra["labels"][b, :na]).all() and (fr == ra["frames"][b, :na]).all()
+        got = oracle_lib.replay_utt(ma, enc[b], int(ln[b]), S, u_cap, lab, fr, tol=1e-3)
+        assert got["ok"], b
+        assert abs(got["score"] - rb["score"][b]) < 1e-4      # the label logits are the same
+        if same:
+            continue
+        differ += 1
+        assert got["n_tie"] >= 1
+        assert not oracle_lib.replay_utt(ma, enc[b], int(ln[b]), S, u_cap, lab, fr, tol=1e-4)["ok"]
+    assert differ >= 1
+
+
 # --------------------------------------------------------------------------- P11
 # Piecewise decoding (an extension beyond the paper) is defined by one requirement:
 # the chunks of an utterance, decoded in order with the carried state, give the
