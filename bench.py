@@ -85,7 +85,8 @@ def roofline_block(cfg, stats, kernel_ms, kernel_ms_min=None):
     return blk
 
 
-def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0, algorithm=0, projections=0):
+def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0, algorithm=0, projections=0,
+                  joint_kernel=0):
     import torch
     from paper_2406_06220_amd import binding, synth
     dev = "cuda:0"
@@ -94,7 +95,8 @@ def time_workload(cfg, steps, warmup, window=0, n_clusters=0, joint_tiles=0, alg
     u_cap = cfg.T * cfg.max_symbols
     model = binding.DeviceModel(cfg, w, dev)
     dec = binding.Decoder(model, cfg.B, cfg.T, u_cap, window=window, n_clusters=n_clusters,
-                          joint_tiles=joint_tiles, algorithm=algorithm, projections=projections)
+                          joint_tiles=joint_tiles, algorithm=algorithm, projections=projections,
+                          joint_kernel=joint_kernel)
     enc_d = model.upload_enc(enc)
     len_d = torch.from_numpy(ln).to(dev)
     stream = torch.cuda.current_stream(dev)
@@ -274,6 +276,7 @@ def main():
     ap.add_argument("--workload", default="cfg2_rnnt_lstm")
     ap.add_argument("--window", type=int, default=0)
     ap.add_argument("--clusters", type=int, default=0)
+    ap.add_argument("--joint-kernel", type=int, default=0, help="0 automatic, 1 tiled, 2 streaming joint pass")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the B=128 line")
     ap.add_argument("--phase-timers", action="store_true",
@@ -305,7 +308,7 @@ def main():
         del src, dst
 
     cfg = synth.CONFIGS[args.workload]
-    res = time_workload(cfg, args.steps, args.warmup, args.window, args.clusters)
+    res = time_workload(cfg, args.steps, args.warmup, args.window, args.clusters, joint_kernel=args.joint_kernel)
     st = res["out"]["stats"]
     line = {
         "metric": "decoded encoder frames/sec (greedy decode only)",

@@ -149,8 +149,19 @@ typedef struct {
  *               hypotheses; kept to measure what the precomputation is worth.  Needs
  *               TDT_ALG_LABEL_LOOPING and no reuse_enc_proj; not available for
  *               tdt_greedy_decode_chunk (TDT_ERR_UNSUPPORTED).
+ *   joint_kernel  how the joint pass multiplies by the output matrix.  TDT_JOINT_AUTO (0): by the
+ *               model's shape.  TDT_JOINT_TILED: work items of a few column tiles each, results
+ *               exchanged through LDS per round (the form for output layers of about a thousand
+ *               columns).  TDT_JOINT_STREAMING: every wavefront walks column tiles of its own with
+ *               many weight fragments in flight and reduces its statistics once per work item
+ *               (chosen automatically from 4096 outputs on, where a pass is bound by the rate at
+ *               which a compute unit pulls its share of the matrix).  Same hypotheses either way.
+ *               Streaming needs bfloat16 weights, h_joint <= 1024, TDT_ALG_LABEL_LOOPING,
+ *               TDT_PROJ_PRECOMPUTED and, if n_clusters is given, at least 4 groups
+ *               (TDT_ERR_UNSUPPORTED otherwise).
  */
 enum tdt_algorithm { TDT_ALG_LABEL_LOOPING = 0, TDT_ALG_FRAME_LOOPING = 1 };
+enum tdt_joint_kernel { TDT_JOINT_AUTO = 0, TDT_JOINT_TILED = 1, TDT_JOINT_STREAMING = 2 };
 enum tdt_projections { TDT_PROJ_PRECOMPUTED = 0, TDT_PROJ_ON_THE_FLY = 1 };
 
 typedef struct {
@@ -162,6 +173,7 @@ typedef struct {
     int32_t wait_timeout_us;
     int32_t selftest_stall;
     int32_t projections; /* enum tdt_projections */
+    int32_t joint_kernel; /* enum tdt_joint_kernel */
 } tdt_options_t;
 
 /* counters written to out_stats (int64 each); sums over all hypothesis groups */

@@ -57,7 +57,7 @@ class tdt_weights_t(C.Structure):
 class tdt_options_t(C.Structure):
     _fields_ = [("window", C.c_int32), ("n_clusters", C.c_int32), ("reuse_enc_proj", C.c_int32),
                 ("joint_tiles", C.c_int32), ("algorithm", C.c_int32), ("wait_timeout_us", C.c_int32),
-                ("selftest_stall", C.c_int32), ("projections", C.c_int32)]
+                ("selftest_stall", C.c_int32), ("projections", C.c_int32), ("joint_kernel", C.c_int32)]
 
 
 _lib = None
@@ -235,7 +235,7 @@ class Decoder:
 
     def __init__(self, model: DeviceModel, B: int, T: int, u_cap: int,
                  window: int = 0, n_clusters: int = 0, joint_tiles: int = 0, algorithm: int = 0,
-                 projections: int = 0):
+                 projections: int = 0, joint_kernel: int = 0):
         import torch
         self.model, self.B, self.T, self.u_cap = model, B, T, u_cap
         dev = model.device
@@ -254,6 +254,7 @@ class Decoder:
         self.options.joint_tiles = joint_tiles
         self.options.algorithm = algorithm
         self.options.projections = projections
+        self.options.joint_kernel = joint_kernel
 
     def __call__(self, enc_dev, enc_len_dev, max_symbols: Optional[int] = None, stream=None):
         import torch

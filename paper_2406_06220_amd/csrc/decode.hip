@@ -78,7 +78,12 @@ namespace {
 // emitted a label.  Same hypotheses; there to measure what the re-ordering is worth.
 // ONTHEFLY: no projections ahead of the loops (the arrangement Sec. 3.4 compares against): every
 // joint pass first projects the encoder frames and the predictor outputs of its own rows.
-template <typename WT, bool CHUNKED, bool FRAMELOOP, bool ONTHEFLY>
+// WIDEJ: the joint pass streams the output matrix (for output layers of many thousands of columns,
+// where a work item holds a hundred column tiles and the pass is bound by how fast a compute unit
+// can pull its share of the matrix): every wavefront walks column tiles of its own, with many
+// weight fragments in flight and no workgroup barrier between tiles, and keeps running argmax /
+// softmax statistics per lane that are reduced once per work item (wide_item in tile_gemm.h).
+template <typename WT, bool CHUNKED, bool FRAMELOOP, bool ONTHEFLY, bool WIDEJ = false>
 __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_lds[];
@@ -293,6 +298,13 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         const int groups = (NT + tiles_per_item - 1) / tiles_per_item;
         auto_rows = max(1, C / groups) * RT;
     }
+    // streaming joint pass: dies the group's workgroups are spread over, workgroups per die, this
+    // one's die and place on it, column tiles per die and this die's first
+    const int wide_ndie = C >= kXcds ? kXcds : C, wide_per = C / wide_ndie;
+    const int wide_die = rank / wide_per, wide_j = rank - wide_die * wide_per;
+    const int wide_ntd_all = ((O + CT - 1) / CT + wide_ndie - 1) / wide_ndie;
+    const int wide_t0 = wide_die * wide_ntd_all;
+    const int wide_ntd = max(0, min(wide_ntd_all, (O + CT - 1) / CT - wide_t0));   // this die's column tiles
     // How a joint pass is cut depends only on how many hypotheses search: tabulated here, one
     // thread per count, so that a pass looks it up instead of dividing.
     for (int n = tid + 1; n <= G; n += kThreads) {
@@ -308,6 +320,22 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         int n_cg, tpg;
         split_tiles(C, n_tiles, NT, max_cg, n_cg, tpg);
         JointPlan jp;
+        jp.w_lo = jp.w_hi = 0;
+        if constexpr (WIDEJ) {
+            // The streaming pass deals its work die by die: die d of the chip multiplies by the same
+            // eighth of the output matrix's column tiles in every pass, whatever the number of row
+            // tiles, so that this eighth stays in the die's L2 (the whole matrix does not fit it,
+            // and every row tile of every group streams it).  The workgroups a group has on a die
+            // share (row tile, column tile) pairs of that die, row tile by row tile; a workgroup's
+            // share is the range [w_lo, w_hi) of them and may span two row tiles.  Every workgroup
+            // that takes part owns one softmax partial per row, so n_cg is their number.
+            const int total = n_tiles * wide_ntd, chunk = (total + wide_per - 1) / wide_per;
+            n_cg = wide_ndie * wide_per;
+            if (rank < n_cg) {
+                jp.w_lo = min(total, wide_j * chunk);
+                jp.w_hi = min(total, jp.w_lo + chunk);
+            }
+        }
         jp.Kw = (short)Kw;
         jp.rcp_kw = ((1 << 20) + Kw - 1) / Kw;   // (r * rcp_kw) >> 20 == r / Kw for r < 16384, Kw <= 64
         jp.n_tiles = (short)n_tiles;
@@ -450,7 +478,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     // column idx % 16), so the four gates of a unit sit in four neighbouring lanes.
                     float c_old[kTabPerThread];   // the unit's cell value (used by the lane of gate 0)
                     run_item<WT>(
-                        S, A, in, n_ct, bl, bl,
+                        S, A, in, tile0, n_ct, bl, bl,
                         [&](const Seg &sg) {
                             const int k0 = sg.k0;
                             const float *src = sg.part == 1 ? h_cur : x_prev;
@@ -556,7 +584,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 run_item<WT>(
                     // the recurrent section has no bias of its own; its placeholder must still
                     // cover the section's 4 * h_pred weight rows (run_item reads it unconditionally)
-                    S, A, in, n_ct, sec_b ? nullptr : p.b_pred, sec_b ? p.b_lstm[0] : p.b_pred,
+                    S, A, in, tile0, n_ct, sec_b ? nullptr : p.b_pred, sec_b ? p.b_lstm[0] : p.b_pred,
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
                         stage_segment<WT>(
@@ -680,7 +708,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         return f < S.len[g] ? f : -1;
                     };
                     run_item<WT>(
-                        S, A, ein, n_ct, sec_p ? p.b_pred : p.b_enc, p.b_pred,
+                        S, A, ein, tile0, n_ct, sec_p ? p.b_pred : p.b_enc, p.b_pred,
                         [&](const Seg &sg) {
                             const int k0 = sg.k0;
                             if (!sec_p) {
@@ -759,19 +787,8 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             in.K0 = H;
             in.w1 = nullptr;
             in.K1 = 0;
-            for (int it = rank; it < n_tiles * n_cg; it += C) {
-                int ti = jp.ti0, cg = jp.cg0;   // the first item is tabulated
-                if (it != rank) {
-                    ti = it / n_cg;
-                    cg = it - ti * n_cg;
-                }
-                const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
-                // running statistics of row tid / 32 over this item's columns (lanes 31 and 63)
-                float rm = -INFINITY, rs = 0.0f, rdm = -INFINITY;
-                int ra = 0, rda = 0;
-                run_item<WT>(
-                    S, A, in, n_ct, p.b_out, p.b_out,
-                    [&](const Seg &sg) {
+            // staging of row tile ti of this pass: relu(projected encoder frame + projected predictor output)
+            auto stage_joint = [&](const Seg &sg, int ti) {
                         const int k0 = sg.k0;
                         const int nrows = min(RT, M - ti * RT);
                         // where row i of the tile reads its projected encoder frame and its projected
@@ -852,7 +869,51 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                                        c.valid ? fmaxf(v.e.y + (v.p.y + v.p2.y), 0.0f) : 0.0f);
                                 });
                         }
-                    },
+                                };
+            if constexpr (WIDEJ) {
+                // the streaming form: this workgroup's share of its die's (row tile, column tile)
+                // pairs, one row tile (staged once) at a time
+                const Seg sg = in.get(0);   // H <= KSEG: one stretch
+                const int ti_lo = jp.w_lo / max(wide_ntd, 1), ti_hi = jp.w_hi > jp.w_lo ? (jp.w_hi - 1) / max(wide_ntd, 1) : -1;
+                if (rank < n_cg) {
+                    // rows of row tiles this workgroup does not touch: an empty softmax partial
+                    for (int r = tid; r < M; r += kThreads) {
+                        const int t = r / RT;
+                        if (jp.w_hi <= jp.w_lo || t < ti_lo || t > ti_hi)
+                            st_co64(reinterpret_cast<unsigned long long *>(pbuf + (size_t)r * n_cg + rank), 0ull);
+                    }
+                }
+                for (int idx = jp.w_lo; idx < jp.w_hi;) {
+                    const int ti = idx / wide_ntd, c0 = idx - ti * wide_ntd;
+                    const int n_ct = min(wide_ntd - c0, jp.w_hi - idx);
+                    WideRowStats ws;
+                    wide_item(S, A, sg, wide_t0 + c0, n_ct, V, O, p.b_out, [&]() { stage_joint(sg, ti); }, wait_hook, ws);
+                    if (tid < RT && ti * RT + tid < M) {   // thread i holds row i of the tile
+                        const int r = ti * RT + tid;
+                        if (ws.s > 0.0f)
+                            __hip_atomic_fetch_max(row_lab + r, pack_best(ws.m, ws.a), __ATOMIC_RELAXED, TDT_AGENT);
+                        if (ws.dm > -INFINITY)
+                            __hip_atomic_fetch_max(row_dur + r, pack_best(ws.dm, ws.da), __ATOMIC_RELAXED, TDT_AGENT);
+                        const unsigned long long lp = (unsigned long long)__float_as_uint(ws.m) |
+                                                      ((unsigned long long)__float_as_uint(ws.s) << 32);
+                        st_co64(reinterpret_cast<unsigned long long *>(pbuf + (size_t)r * n_cg + rank), lp);
+                    }
+                    idx += n_ct;
+                }
+            }
+            for (int it = rank; !WIDEJ && it < n_tiles * n_cg; it += C) {
+                int ti = jp.ti0, cg = jp.cg0;   // the first item is tabulated
+                if (it != rank) {
+                    ti = it / n_cg;
+                    cg = it - ti * n_cg;
+                }
+                const int tile0 = cg * tpg, n_ct = min(tpg, NT - tile0);
+                // running statistics of row tid / 32 over this item's columns (lanes 31 and 63)
+                float rm = -INFINITY, rs = 0.0f, rdm = -INFINITY;
+                int ra = 0, rda = 0;
+                run_item<WT>(
+                    S, A, in, tile0, n_ct, p.b_out, p.b_out,
+                    [&](const Seg &sg) { stage_joint(sg, ti); },
                     [&](int ct, int j) -> long long {
                         const int n = (tile0 + ct) * CT + j;
                         return n < O ? n : -1;
@@ -1214,6 +1275,9 @@ hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats
 static const void *kernel_for(const tdt_weights_t *w, DecodeVariant v)
 {
     const bool bf16 = w->dtype == 1;
+    if (v.wide_joint)   // bfloat16, label-looping, precomputed projections (checked by the caller)
+        return v.chunked ? (const void *)decode_kernel<uint16_t, true, false, false, true>
+                         : (const void *)decode_kernel<uint16_t, false, false, false, true>;
     if (v.on_the_fly)
         return bf16 ? (const void *)decode_kernel<uint16_t, false, false, true>
                     : (const void *)decode_kernel<float, false, false, true>;

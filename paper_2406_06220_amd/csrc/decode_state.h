@@ -64,6 +64,7 @@ struct JointPlan {
     short Kw, n_tiles, n_cg, ti0;
     int tpg, cg0;
     int rcp_kw;   // ceil(2^20 / Kw)
+    int w_lo, w_hi;   // streaming joint pass: this workgroup's range of its die's (row tile, column tile) pairs
 };
 
 struct HypShared {
@@ -113,9 +114,12 @@ struct HypShared {
 // `part` of the phase, multiplied by columns [k0, k0 + K) of the rows of weight matrix
 // `w` (row stride wld).  A phase has one or two inputs (the LSTM has the layer input and
 // the hidden state); an input longer than KSEG is walked in KSEG pieces.
+// One stretch of at most KSEG inputs of a weight matrix.  float32: w is the row-major matrix, wld
+// its row length.  bfloat16: w is the fragment-major copy (1 KiB fragments, a tile's fragments in
+// order of their step), nst the steps of a whole row.
 struct Seg {
     const void *w;
-    int wld, k0, K, part;
+    int wld, k0, K, part, nst;
 };
 
 // what the joint pass loads for two inputs of one row: projected encoder frame and
@@ -158,6 +162,7 @@ struct PhaseInputs {
         s.wld = first ? K0 : K1;
         s.k0 = (first ? i : i - n0) * KSEG;
         s.K = min(KSEG, s.wld - s.k0);
+        s.nst = (s.wld + 31) >> 5;
         return s;
     }
 };

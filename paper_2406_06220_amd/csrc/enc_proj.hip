@@ -124,10 +124,6 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
     float *Cs = reinterpret_cast<float *>(lds_raw);
     __shared__ long long row_of[BM];   // source / destination row of each row of the tile, -1: none
     __shared__ int scan[GEMM_THREADS], wsum[GEMM_THREADS / 64];
-#ifdef TDT_GEMM_PAD_LDS
-    __shared__ int pad_lds[TDT_GEMM_PAD_LDS];
-    if (threadIdx.x == 9999) pad_lds[threadIdx.x] = 0;
-#endif
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     // 1-D grid.  Consecutive workgroups go to consecutive XCDs, each with an L2 of its own, so
@@ -463,6 +459,110 @@ hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_we
                                      float *out, hipStream_t stream)
 {
     return launch_linear(enc, rows, w->d_enc, w->w_enc, w->d_enc, w->h_joint, w->b_enc, w->dtype, 0, out, stream);
+}
+
+// ---------------------------------------------------------------------------
+// fragment-major copies of the streamed matrices
+// ---------------------------------------------------------------------------
+namespace {
+struct PackJob {
+    const uint16_t *src;
+    uint4 *dst;
+    int N, K, gate_h;   // gate_h > 0: LSTM gate matrix of gate_h hidden units
+    int steps;
+    long long first, pieces;   // 16-byte pieces: its first in the batch, how many
+};
+constexpr int kMaxPackJobs = 3 + 2 * TDT_MAX_LSTM_LAYERS;
+struct PackBatch {
+    PackJob j[kMaxPackJobs];
+    int n;
+    long long pieces;
+};
+
+__global__ __launch_bounds__(256) void pack_weights_kernel(PackBatch b)
+{
+    for (long long piece = (long long)blockIdx.x * 256 + threadIdx.x; piece < b.pieces;
+         piece += (long long)gridDim.x * 256) {
+        int ji = 0;
+        while (ji + 1 < b.n && piece >= b.j[ji + 1].first) ++ji;
+        const PackJob &q = b.j[ji];
+        const long long local = piece - q.first;
+        const int lane = (int)(local & 63);
+        const long long frag = local >> 6;
+        const int step = (int)(frag % q.steps), tile = (int)(frag / q.steps);
+        const int j = lane & 15, k = step * 32 + (lane >> 4) * 8;
+        long long row;
+        if (q.gate_h > 0) {
+            const int unit = tile * 4 + (j >> 2);
+            row = unit < q.gate_h ? (long long)(j & 3) * q.gate_h + unit : -1;
+        } else {
+            row = tile * 16 + j < q.N ? tile * 16 + j : -1;
+        }
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row >= 0 && k < q.K) v = *reinterpret_cast<const uint4 *>(q.src + row * q.K + k);   // K % 8 == 0
+        q.dst[local] = v;
+    }
+}
+
+PackedMatrix place(size_t &off, int tiles, int K)
+{
+    PackedMatrix m;
+    m.offset = off;
+    m.tiles = tiles;
+    m.steps = (K + 31) / 32;
+    off += (size_t)m.tiles * m.steps * 1024;
+    return m;
+}
+}  // namespace
+
+PackedLayout packed_layout(const tdt_weights_t *w)
+{
+    PackedLayout pl{};
+    size_t off = 0;
+    if (w->dtype != 1) return pl;
+    const bool lstm = w->pred_kind == TDT_PRED_LSTM;
+    pl.w_enc = place(off, (w->h_joint + 15) / 16, w->d_enc);
+    pl.w_pred = place(off, (w->h_joint + 15) / 16, w->h_pred);
+    pl.w_out = place(off, (w->vocab + 1 + w->n_dur + 15) / 16, w->h_joint);
+    for (int l = 0; lstm && l < w->pred_layers; ++l) {
+        // the first layer's input product is a per-label table: its matrix is not streamed
+        if (l > 0) pl.w_ih[l] = place(off, (w->h_pred + 3) / 4, w->h_pred);
+        pl.w_hh[l] = place(off, (w->h_pred + 3) / 4, w->h_pred);
+    }
+    pl.total = off;
+    return pl;
+}
+
+hipError_t launch_pack_weights(const tdt_weights_t *w, const PackedLayout &pl, bool on_the_fly, void *packed,
+                               hipStream_t stream)
+{
+    if (w->dtype != 1 || pl.total == 0) return hipSuccess;
+    PackBatch b{};
+    const bool lstm = w->pred_kind == TDT_PRED_LSTM;
+    auto add = [&](const void *src, const PackedMatrix &m, int N, int K, int gate_h) {
+        PackJob &q = b.j[b.n++];
+        q.src = static_cast<const uint16_t *>(src);
+        q.dst = reinterpret_cast<uint4 *>(static_cast<char *>(packed) + m.offset);
+        q.N = N;
+        q.K = K;
+        q.gate_h = gate_h;
+        q.steps = m.steps;
+        q.first = b.pieces;
+        q.pieces = (long long)m.tiles * m.steps * 64;
+        b.pieces += q.pieces;
+    };
+    // what a call does not multiply by stays unpacked: the encoder projection and, with a
+    // stateless predictor, its projection are products of the kernel only when it projects on the fly
+    if (on_the_fly) add(w->w_enc, pl.w_enc, w->h_joint, w->d_enc, 0);
+    if (on_the_fly || lstm) add(w->w_pred, pl.w_pred, w->h_joint, w->h_pred, 0);
+    add(w->w_out, pl.w_out, w->vocab + 1 + w->n_dur, w->h_joint, 0);
+    for (int l = 0; lstm && l < w->pred_layers; ++l) {
+        if (l > 0) add(w->w_ih[l], pl.w_ih[l], 4 * w->h_pred, w->h_pred, w->h_pred);
+        add(w->w_hh[l], pl.w_hh[l], 4 * w->h_pred, w->h_pred, w->h_pred);
+    }
+    const long long blocks = (b.pieces + 255) / 256;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream, b);
+    return hipGetLastError();
 }
 
 // stateless predictor, float32 models: the per-label tables of the projected predictor output

@@ -49,6 +49,8 @@ WorkspaceLayout workspace_layout(const tdt_weights_t *w, int B, int T)
     const size_t lstm_layers = w->pred_kind == TDT_PRED_LSTM ? (size_t)w->pred_layers : 0;
     // per-hypothesis arrays are addressed by (cluster, slot): n_clusters * ceil(B / n_clusters) rows
     const size_t rows = (size_t)B + kMaxGrid;
+    L.packed = off;
+    off = align_up(off + packed_layout(w).total, 256);
     L.enc_proj = off;
     off = align_up(off + (size_t)B * T * w->h_joint * sizeof(float), 256);
     L.pred_proj = off;
@@ -215,7 +217,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     }
     if (!any_pos) return TDT_ERR_DURATIONS;
     int window = 0, n_clusters = 0, joint_tiles = 0, algorithm = TDT_ALG_LABEL_LOOPING;
-    int wait_timeout_us = 0, selftest_stall = 0;
+    int wait_timeout_us = 0, selftest_stall = 0, joint_kernel = TDT_JOINT_AUTO;
     bool reuse_enc_proj = false, on_the_fly = false;
     if (options) {
         window = options->window;
@@ -235,14 +237,32 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         if (on_the_fly && (state || reuse_enc_proj || algorithm != TDT_ALG_LABEL_LOOPING)) return TDT_ERR_UNSUPPORTED;
         if (window < 0 || window > kMaxWindow || n_clusters < 0 || joint_tiles < 0 || joint_tiles > 64)
             return TDT_ERR_UNSUPPORTED;
+        joint_kernel = options->joint_kernel;
+        if (joint_kernel < TDT_JOINT_AUTO || joint_kernel > TDT_JOINT_STREAMING) return TDT_ERR_UNSUPPORTED;
     }
+    // the streaming joint pass: one stretch of the reduction, bfloat16, the default loops
+    const bool can_stream = weights->dtype == 1 && weights->h_joint <= 1024 &&
+                            algorithm == TDT_ALG_LABEL_LOOPING && !on_the_fly;
+    if (joint_kernel == TDT_JOINT_STREAMING && !can_stream) return TDT_ERR_UNSUPPORTED;
+    bool wide_joint = joint_kernel == TDT_JOINT_STREAMING ||
+                      (joint_kernel == TDT_JOINT_AUTO && can_stream && weights->vocab + 1 + weights->n_dur >= 4096);
     const WorkspaceLayout L = workspace_layout(weights, B, T);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < L.total)
         return TDT_ERR_WORKSPACE;
 
-    const DecodeVariant variant{state != nullptr, algorithm == TDT_ALG_FRAME_LOOPING, on_the_fly};
-    const int max_grid = decode_max_grid(weights, variant);
+    DecodeVariant variant{state != nullptr, algorithm == TDT_ALG_FRAME_LOOPING, on_the_fly, wide_joint};
+    int max_grid = decode_max_grid(weights, variant);
     if (max_grid < 1) return TDT_ERR_LAUNCH;
+    // the streaming joint pass keeps one softmax partial per row and workgroup of a group, and the
+    // decision step reads them with one lane each: at most 64 workgroups a group
+    const int min_stream_clusters = (max_grid + 63) / 64;
+    if (wide_joint && n_clusters != 0 && n_clusters < min_stream_clusters) {
+        if (joint_kernel == TDT_JOINT_STREAMING) return TDT_ERR_UNSUPPORTED;
+        wide_joint = false;
+        variant.wide_joint = false;
+        max_grid = decode_max_grid(weights, variant);
+        if (max_grid < 1) return TDT_ERR_LAUNCH;
+    }
     const int min_clusters = (B + kMaxHypsPerCluster - 1) / kMaxHypsPerCluster;
     if (n_clusters == 0) {
         // Measured on the paper-sized models (B = 1 ... 512, 2 ... 16 clusters).  A cluster runs
@@ -270,6 +290,15 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         }
         if (n_clusters > B && B > 1) n_clusters = B;
         if (n_clusters < min_clusters) n_clusters = min_clusters;
+        if (wide_joint) {
+            // the streaming joint pass: a group's pass lasts as long as its workgroups need for the
+            // output matrix, whatever the number of rows up to a full row tile -- groups of one
+            // row tile (measured at B = 256: 16 groups 45 ms, 8 groups 51 ms, 4 groups 59 ms)
+            const int full = (B + 15) / 16;   // row tiles of 16
+            if (n_clusters < full) n_clusters = full < 16 ? full : 16;
+            if (n_clusters < min_clusters) n_clusters = min_clusters;
+            if (n_clusters < min_stream_clusters) n_clusters = min_stream_clusters;   // some may stay empty
+        }
     }
     if (n_clusters < min_clusters || n_clusters > max_grid) return TDT_ERR_UNSUPPORTED;
     // every cluster gets max_grid / n_clusters workgroups; the launch is rounded up to whole
@@ -288,6 +317,8 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     // the arrangement without any precomputation.)
     float *pred_tab = weights->pred_kind == TDT_PRED_STATELESS && !on_the_fly
                           ? reinterpret_cast<float *>(ws + L.pred_tab) : nullptr;
+    const PackedLayout PL = packed_layout(weights);
+    if (launch_pack_weights(weights, PL, on_the_fly, ws + L.packed, s) != hipSuccess) return TDT_ERR_LAUNCH;
     if (!reuse_enc_proj && weights->dtype == 1) {
         // one launch: the projection, the predictor side's per-label tables, the clearing
         // (projections on the fly: no rows for the projection here)
@@ -346,6 +377,16 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     p.b_pred = weights->b_pred;
     p.w_out = weights->w_out;
     p.b_out = weights->b_out;
+    if (weights->dtype == 1) {   // the kernel multiplies by the fragment-major copies
+        const char *pk = ws + L.packed;
+        p.w_enc = pk + PL.w_enc.offset;
+        p.w_pred = pk + PL.w_pred.offset;
+        p.w_out = pk + PL.w_out.offset;
+        for (int l = 0; l < TDT_MAX_LSTM_LAYERS; ++l) {
+            p.w_ih[l] = pk + PL.w_ih[l].offset;   // (layer 0: not streamed, never read)
+            p.w_hh[l] = pk + PL.w_hh[l].offset;
+        }
+    }
     p.enc_proj = enc_proj;
     p.emb_gates = emb_gates;
     p.pred_tab = pred_tab;

@@ -81,6 +81,7 @@ struct DecodeParams {
 };
 
 struct WorkspaceLayout {
+    size_t packed;                 // the bfloat16 matrices the decode kernel streams, fragment by fragment
     size_t enc_proj, emb_gates, pred_tab, hbuf, cbuf, rgate, pred_proj, partials, row_lab, row_dur, barrier, abort_flag, total;
     size_t row_entries;            // uint64 entries in each of row_lab / row_dur
     size_t zero_begin, zero_end;   // byte range the init kernel clears
@@ -116,6 +117,26 @@ hipError_t launch_encoder_projection_valid(const void *enc, const int32_t *enc_l
 // stateless predictor: pred_tab[c][label][:] = w_pred[:, c*E .. (c+1)*E) * emb_c[label] (+ b_pred
 // in the last table), one launch per table
 hipError_t launch_pred_tables(const tdt_weights_t *w, float *pred_tab, hipStream_t stream);
+// Fragment-major copies of the bfloat16 weight matrices the decode kernel multiplies by.
+// A matrix [N][K] (row-major) is cut into column tiles of 16 rows of it and steps of 32 inputs;
+// fragment (tile, step) is 1 KiB, lane l's 16 bytes at l * 16: inputs step * 32 + (l / 16) * 8 .. + 7
+// of the tile's row l % 16 -- what lane l feeds the matrix core -- zeros where the matrix ends.
+// Fragments of a tile follow each other by step.  A wavefront's fragment load is then one
+// contiguous KiB; from the row-major matrix it is 16 pieces of 64 bytes from 16 rows, which
+// the texture addresser takes four times as long over.
+// Row of a tile: plain tile*16 + j; for LSTM gate matrices (gate-major [4][h][K]) a tile is
+// 4 hidden units x 4 gates: row (j % 4) * h + tile * 4 + j / 4.
+struct PackedMatrix {
+    size_t offset;   // bytes from the start of the packed region
+    int tiles, steps;
+};
+struct PackedLayout {
+    PackedMatrix w_enc, w_pred, w_out, w_ih[TDT_MAX_LSTM_LAYERS], w_hh[TDT_MAX_LSTM_LAYERS];
+    size_t total;
+};
+PackedLayout packed_layout(const tdt_weights_t *w);
+hipError_t launch_pack_weights(const tdt_weights_t *w, const PackedLayout &pl, bool on_the_fly, void *packed,
+                               hipStream_t stream);
 hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats,
                        hipStream_t stream);
 // which compiled form of the decode kernel a call runs
@@ -123,6 +144,7 @@ struct DecodeVariant {
     bool chunked;      // tdt_greedy_decode_chunk
     bool frame_loop;   // TDT_ALG_FRAME_LOOPING
     bool on_the_fly;   // TDT_PROJ_ON_THE_FLY
+    bool wide_joint;   // the joint pass streams the output matrix (TDT_JOINT_STREAMING)
 };
 hipError_t launch_decode(const DecodeParams &p, const tdt_weights_t *w, DecodeVariant v, int grid,
                          hipStream_t stream);

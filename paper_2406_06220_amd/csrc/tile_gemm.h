@@ -142,41 +142,40 @@ template <> struct Accum<float> {
 constexpr int CH = TDT_CH;   // weight fragments in flight per wavefront
 
 struct WeightCursor {
-    const uint16_t *wr;   // this lane's weight row at its k-quarter (row 0 if the column is padding)
-    bool live;            // false: the column is padding and its fragments are zero
-    int kq, n_my;
+    const uint4 *fr;   // this lane's 16 bytes of the first fragment of the tile's stretch
+    int kq, n_my, last;   // last: the stretch's last step
 };
 
-__device__ inline WeightCursor weight_cursor(const Seg &sg, long long wrow, int kpart, int ksplit, int lane)
+// tile: the column tile's index in the matrix's fragment-major copy
+__device__ inline WeightCursor weight_cursor(const Seg &sg, int tile, int kpart, int ksplit, int lane)
 {
     WeightCursor wc;
     wc.kq = (lane >> 4) * 8;
-    wc.live = wrow >= 0;
-    wc.wr = static_cast<const uint16_t *>(sg.w) + (wc.live ? wrow : 0) * sg.wld + sg.k0;
+    wc.fr = static_cast<const uint4 *>(sg.w) + ((size_t)tile * sg.nst + (sg.k0 >> 5)) * 64 + lane;
     const int nsteps = (sg.K + 31) / 32;
+    wc.last = nsteps - 1;
     // ksplit is a power of two
     wc.n_my = nsteps > kpart ? (nsteps - kpart + ksplit - 1) >> __builtin_ctz(ksplit) : 0;
     return wc;
 }
 
-// Loads are unconditional (address clamped into the row) and nothing uses a fragment before
-// all CH loads have been issued.
-__device__ inline void weight_prefetch(const WeightCursor &wc, const Seg &sg, int kpart, int ksplit, int c0,
+// Loads are unconditional (a step beyond the stretch re-reads its last fragment) and nothing
+// uses a fragment before all CH loads have been issued.  A wavefront's load is one contiguous KiB.
+__device__ inline void weight_prefetch(const WeightCursor &wc, const Seg &, int kpart, int ksplit, int c0,
                                        uint4 (&b)[CH])
 {
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const int k = (kpart + (c0 + j) * ksplit) * 32 + wc.kq;
-        b[j] = *reinterpret_cast<const uint4 *>(wc.wr + (k < sg.K ? k : sg.K - 8));
+        const int s = kpart + (c0 + j) * ksplit;
+        b[j] = wc.fr[(size_t)min(s, wc.last) * 64];
     }
     __builtin_amdgcn_sched_barrier(0);
 }
 
 // the products of one chunk of CH k-steps (from step c0 of this wavefront's share) with the
-// weight fragments b.  Nothing is masked.  A weight fragment beyond the end of its row (K no
-// multiple of 32) or of a column that is padding was fetched from a clamped, valid address: the
-// first meets activation zeros (the tile is zero from K up to a multiple of 32), the second
-// lands in a column no epilogue looks at.  A step beyond the wavefront's share reads, as its
+// weight fragments b.  Nothing is masked: the fragment-major copy holds zeros beyond the end of
+// a row (K no multiple of 32) and in columns that are padding, and the tile is zero from K up
+// to a multiple of 32 as well.  A step beyond the wavefront's share reads, as its
 // activation fragment, the padding at the end of each tile row, which nothing ever writes and
 // which is zero from the start of the kernel.  The activation fragments of step j + 1 are
 // requested from LDS before the products of step j are issued.
@@ -191,6 +190,7 @@ __device__ inline void chunk_products(const uint16_t *arow, size_t plane, int zo
         x[0][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
         x[0][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
     }
+    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // (the schedule: these three reads first)
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
         if (j + 1 < CH) {
@@ -203,6 +203,9 @@ __device__ inline void chunk_products(const uint16_t *arow, size_t plane, int zo
         acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][0], bv, acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][1], bv, acc1, 0, 0, 0);
         acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[j & 1][2], bv, acc2, 0, 0, 0);
+        // keep that order in the schedule: the next step's three LDS reads, then this step's products
+        if (j + 1 < CH) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
     }
 }
 
@@ -241,9 +244,9 @@ template <> struct Backend<uint16_t> {
     };
     // first chunk: requested before the item waits for the rows it depends on
     template <typename RowF>
-    __device__ static void prefetch(Pre &pre, const Seg &sg, RowF rowidx, int ct, int kpart, int ksplit, int lane)
+    __device__ static void prefetch(Pre &pre, const Seg &sg, RowF, int, int tile, int kpart, int ksplit, int lane)
     {
-        pre.wc = weight_cursor(sg, rowidx(ct, lane & 15), kpart, ksplit, lane);
+        pre.wc = weight_cursor(sg, tile, kpart, ksplit, lane);
         weight_prefetch(pre.wc, sg, kpart, ksplit, 0, pre.b);
     }
     // second chunk: requested once the registers of the staged rows are free again
@@ -284,7 +287,7 @@ template <> struct Backend<float> {
         __builtin_amdgcn_sched_barrier(0);
     }
     template <typename RowF>
-    __device__ static void prefetch(Pre &pre, const Seg &sg, RowF rowidx, int ct, int kpart, int ksplit, int lane)
+    __device__ static void prefetch(Pre &pre, const Seg &sg, RowF rowidx, int ct, int, int kpart, int ksplit, int lane)
     {
         const long long wrow = rowidx(ct, lane & 15);
         pre.kq = (lane >> 4) * 4;
@@ -327,6 +330,8 @@ template <> struct Backend<float> {
 
 // One work item: all K segments of the staged rows against n_ct column tiles, a round of
 // (8 / ksplit) column tiles at a time.
+//   tile0                          the item's first column tile, counted in column tiles of the
+//                                  whole matrix (where the fragment-major copy keeps it)
 //   stage(seg)                     stages Seg seg of the item's rows (stage_segment)
 //   rowidx(ct, j)    -> long long  weight row of column j of column tile ct, -1 if none
 //   pre(ct0, n)                    called by all threads at the start of a round, before the
@@ -343,7 +348,7 @@ template <> struct Backend<float> {
 // With one segment the rows are staged once; with several they are staged again for
 // every round.
 template <typename WT, typename StageF, typename RowF, typename PreF, typename ParkF, typename EpiF, typename WaitF>
-__device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseInputs &in, int n_ct,
+__device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseInputs &in, int tile0, int n_ct,
                                 const float *__restrict__ bias, const float *any_floats, StageF stage,
                                 RowF rowidx, PreF pre_round, ParkF park, EpiF epi, WaitF wait)
 {
@@ -380,7 +385,7 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
             if (TDT_FINE_TIMERS && threadIdx.x == 0) tq = wall_clock64();
             typename Backend<WT>::Pre pre;
             // the weights do not depend on the activations: fetch the first of them now
-            if (mine) Backend<WT>::prefetch(pre, sg, rowidx, ct, kpart, ksplit, lane);
+            if (mine) Backend<WT>::prefetch(pre, sg, rowidx, ct, tile0 + ct, kpart, ksplit, lane);
             TR(12);
             if (nseg > 1 || base == 0) {
                 // previous readers of the tile are done
@@ -413,6 +418,229 @@ __device__ inline void run_item(HypShared &S, const ActTile<WT> &A, const PhaseI
         TR(20);
         if (TDT_FINE_TIMERS && threadIdx.x == 0) S.tk_fine[S.fine_phase][2] += wall_clock64() - tq;
     }
+}
+
+// ---------------------------------------------------------------------------
+// The streaming joint pass (bfloat16 weights, one stretch of the reduction).  The 16 rows are
+// staged once; then every wavefront walks groups of WTW column tiles of its own (group wave,
+// wave + 8, ...) with no workgroup barrier in between.  An activation fragment read from LDS is
+// multiplied by WTW weight fragments (the reads of the activations from LDS, not the matrix
+// cores, bound a wavefront that takes one tile at a time).  Weight fragments travel in chunks of
+// WKS k-steps (WKS * WTW fragments) through two register buffers, one being multiplied while the
+// other is on its way, across group borders.  A lane holds column l % 16 and rows
+// (l / 16) * 4 .. + 3 of each tile of its wavefront's current group and keeps running statistics
+// of those four rows over all its tiles -- largest label logit, its column, the sum of
+// exp(logit - largest), largest duration logit and its class -- so that no logit ever goes
+// through LDS; they are reduced across the 16 lanes of a row (DPP rotations) and across the
+// wavefronts (LDS) once per work item.  Ties: a lane walks its columns in ascending order and
+// keeps the first maximum; across lanes and wavefronts the lowest column among equals wins.
+// ---------------------------------------------------------------------------
+#ifndef TDT_WIDE_TW
+#define TDT_WIDE_TW 1
+#endif
+#ifndef TDT_WIDE_KS
+#define TDT_WIDE_KS 8
+#endif
+constexpr int WTW = TDT_WIDE_TW;   // column tiles per group
+constexpr int WKS = TDT_WIDE_KS;   // k-steps per chunk
+
+// what thread i (< 16) of the workgroup holds for row i of the tile after wide_item
+struct WideRowStats {
+    float m, s, dm;   // largest label logit, sum of exp(logit - m) over the item's label columns, largest duration logit
+    int a, da;        // their columns (label; duration class)
+};
+
+// v combined over the 16 lanes of its row by rotations: every lane ends up with the result
+template <typename T, typename Op> __device__ inline T row_allreduce(T v, Op op)
+{
+    v = op(v, dpp_move<0x121, 0xf>(v, v));   // row_ror:1
+    v = op(v, dpp_move<0x122, 0xf>(v, v));   // row_ror:2
+    v = op(v, dpp_move<0x124, 0xf>(v, v));   // row_ror:4
+    v = op(v, dpp_move<0x128, 0xf>(v, v));   // row_ror:8
+    return v;
+}
+
+// one chunk of weight fragments in flight, with the biases of its group's columns
+struct WideChunk {
+    uint4 b[WKS][WTW];
+    float bias[WTW];
+};
+
+template <typename StageF, typename WaitF>
+__device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const Seg &sg, int tile0, int n_ct, int V,
+                                 int O, const float *__restrict__ bias, StageF stage, WaitF wait, WideRowStats &out)
+{
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kq = (lane >> 4) * 8;
+    const int nsteps = (sg.K + 31) / 32;
+    const int nch = (nsteps + WKS - 1) / WKS;                        // chunks per group of tiles
+    const int n_grp = (n_ct + WTW - 1) / WTW;
+    const int my_groups = n_grp > wave ? (n_grp - wave + kWaves - 1) / kWaves : 0;
+    const int total = my_groups * nch;                               // chunks of this wavefront
+    const uint4 *wbase = static_cast<const uint4 *>(sg.w) + (size_t)(sg.k0 >> 5) * 64 + lane;
+    // chunk (t, ci) of this wavefront: tiles tile0 + (wave + t * 8) * WTW + u, k-steps ci * WKS ...
+    // (a tile beyond the item, a column beyond the matrix: a valid row, results never looked at)
+    auto fetch = [&](int t, int ci, WideChunk &w) {
+        const int s0 = ci * WKS;
+#pragma unroll
+        for (int u = 0; u < WTW; ++u) {
+            const int tl = (wave + t * kWaves) * WTW + u;
+            const int col = (tile0 + tl) * CT + (lane & 15);
+            const int cc = tl < n_ct && col < O ? col : 0;
+            const uint4 *fr = wbase + (size_t)(tl < n_ct ? tile0 + tl : tile0) * sg.nst * 64;
+            w.bias[u] = bias[cc];
+#pragma unroll
+            for (int j = 0; j < WKS; ++j) w.b[j][u] = fr[(size_t)min(s0 + j, nsteps - 1) * 64];
+        }
+    };
+    WideChunk wA, wB;
+    int ft = 0, fci = 0;   // the next chunk to request
+    auto fetch_next = [&](WideChunk &w) {
+        fetch(ft, fci, w);
+        if (++fci == nch) { fci = 0; ++ft; }
+    };
+    if (total > 0) fetch_next(wA);   // before the rows this item depends on have arrived
+    TR(70);
+    wait();
+    stage();
+    __syncthreads();
+    TR(71);
+
+    const uint16_t *arow = A.planes + (size_t)(lane & 15) * A.ldb;
+    const size_t plane = (size_t)RT * A.ldb;
+    const int zoff = A.ldb - 8;   // a row's padding: zeros (see chunk_products)
+    f32x4 acc[WTW];
+#pragma unroll
+    for (int u = 0; u < WTW; ++u) acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    float rm[4], rs[4], rdm[4];
+    int ra[4], rda[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        rm[e] = rdm[e] = -INFINITY;
+        rs[e] = 0.0f;
+        ra[e] = rda[e] = 0x7fffffff;
+    }
+    int ct_ = 0, cci = 0;   // the chunk being multiplied
+    // the products of one chunk; at the end of a group the logits of this lane update the statistics
+    auto chunk = [&](const WideChunk &w) {
+        const int s0 = cci * WKS;
+        auto aoff = [&](int s) { return s < nsteps ? s * 32 + kq : zoff; };
+        bf16x8 x[2][3];
+        {
+            const uint16_t *a = arow + aoff(s0);
+            x[0][0] = *reinterpret_cast<const bf16x8 *>(a);
+            x[0][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
+            x[0][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // (the schedule: these three reads first)
+#pragma unroll
+        for (int j = 0; j < WKS; ++j) {
+            if (j + 1 < WKS) {
+                const uint16_t *a = arow + aoff(s0 + j + 1);
+                x[(j + 1) & 1][0] = *reinterpret_cast<const bf16x8 *>(a);
+                x[(j + 1) & 1][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
+                x[(j + 1) & 1][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
+            }
+            // consecutive products go to different accumulators
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+#pragma unroll
+                for (int u = 0; u < WTW; ++u)
+                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        x[j & 1][pl], *reinterpret_cast<const bf16x8 *>(&w.b[j][u]), acc[u], 0, 0, 0);
+            // keep that order in the schedule: the next step's three LDS reads, then this step's products
+            if (j + 1 < WKS) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 3 * WTW, 0);
+        }
+        if (cci == nch - 1) {   // uniform over the wavefront: the group is complete
+#pragma unroll
+            for (int u = 0; u < WTW; ++u) {
+                const int tl = (wave + ct_ * kWaves) * WTW + u;
+                const int col = tl < n_ct ? (tile0 + tl) * CT + (lane & 15) : O;   // O: no column
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float v = acc[u][e] + w.bias[u];
+                    if (col <= V) {
+                        if (v > rm[e]) {
+                            rs[e] = (rs[e] > 0.0f ? rs[e] * __expf(rm[e] - v) : 0.0f) + 1.0f;
+                            rm[e] = v;
+                            ra[e] = col;
+                        } else {
+                            rs[e] += __expf(v - rm[e]);
+                        }
+                    } else if (col < O && v > rdm[e]) {
+                        rdm[e] = v;
+                        rda[e] = col - (V + 1);
+                    }
+                }
+                acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+            cci = 0;
+            ++ct_;
+        } else {
+            ++cci;
+        }
+    };
+    for (int c = 0; c < total; c += 2) {
+        if (c + 1 < total) fetch_next(wB);
+        chunk(wA);
+        TR(72);
+        if (c + 2 < total) fetch_next(wA);
+        if (c + 1 < total) chunk(wB);
+        TR(72);
+    }
+    TR(73);
+
+    // ---- one reduction per work item: across the 16 lanes of a row, then across the wavefronts
+    auto fmax2 = [](float x, float y) { return fmaxf(x, y); };
+    auto imin2 = [](int x, int y) { return min(x, y); };
+    auto fadd2 = [](float x, float y) { return x + y; };
+    float *wstat = &S.cpart[0][0][0];   // [kWaves][RT][5], the partial-result scratch is not in use here
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float m = row_allreduce(rm[e], fmax2);
+        const int a = row_allreduce(rm[e] == m ? ra[e] : 0x7fffffff, imin2);
+        const float sl = rs[e] > 0.0f ? rs[e] * __expf(rm[e] - m) : 0.0f;
+        const float sr = row_allreduce(sl, fadd2);
+        const float dm = row_allreduce(rdm[e], fmax2);
+        const int da = row_allreduce(rdm[e] == dm ? rda[e] : 0x7fffffff, imin2);
+        if ((lane & 15) == 0) {
+            float *w = wstat + ((size_t)wave * RT + (lane >> 4) * 4 + e) * 5;
+            w[0] = m;
+            w[1] = __int_as_float(a);
+            w[2] = sr;
+            w[3] = dm;
+            w[4] = __int_as_float(da);
+        }
+    }
+    __syncthreads();
+    out.m = out.dm = -INFINITY;
+    out.s = 0.0f;
+    out.a = out.da = 0x7fffffff;
+    if (threadIdx.x < RT) {
+        const int i = threadIdx.x;
+        for (int w8 = 0; w8 < kWaves; ++w8) {   // wavefronts hold interleaved tiles: lowest column among equals
+            const float *w = wstat + ((size_t)w8 * RT + i) * 5;
+            const float m = w[0], sr = w[2], dm = w[3];
+            const int a = __float_as_int(w[1]), da = __float_as_int(w[4]);
+            if (sr > 0.0f) {
+                if (m > out.m) {
+                    out.s = (out.s > 0.0f ? out.s * __expf(out.m - m) : 0.0f) + sr;
+                    out.m = m;
+                    out.a = a;
+                } else {
+                    out.s += sr * __expf(m - out.m);
+                    if (m == out.m && a < out.a) out.a = a;
+                }
+            }
+            if (dm > out.dm || (dm == out.dm && da < out.da)) {
+                out.dm = dm;
+                out.da = da;
+            }
+        }
+    }
+    __syncthreads();   // the scratch is free again
+    TR(74);
 }
 
 __device__ inline float cpart_sum(const HypShared &S, int t, int ksplit, int i, int j)

@@ -24,14 +24,16 @@ def gpu():
 
 
 def run_gpu(binding, cfg, w, enc, ln, u_cap, window=0, n_clusters=0, joint_tiles=0, max_symbols=None,
-            repeat=1, algorithm=0, projections=0):
+            repeat=1, algorithm=0, projections=0, joint_kernel=0):
     import torch
     parity.announce(f"tdt_greedy_decode cfg={cfg.name} B={len(ln)} T={enc.shape[1]} u_cap={u_cap} "
                     f"window={window} n_clusters={n_clusters} joint_tiles={joint_tiles} "
-                    f"S={max_symbols or cfg.max_symbols} algorithm={algorithm} projections={projections}")
+                    f"S={max_symbols or cfg.max_symbols} algorithm={algorithm} projections={projections} "
+                    f"joint_kernel={joint_kernel}")
     model = binding.DeviceModel(cfg, w)
     dec = binding.Decoder(model, len(ln), enc.shape[1], u_cap, window=window, n_clusters=n_clusters,
-                          joint_tiles=joint_tiles, algorithm=algorithm, projections=projections)
+                          joint_tiles=joint_tiles, algorithm=algorithm, projections=projections,
+                          joint_kernel=joint_kernel)
     enc_d = model.upload_enc(enc)
     len_d = torch.from_numpy(np.ascontiguousarray(ln, np.int32)).to(model.device)
     out = None
@@ -247,6 +249,44 @@ def test_largest_dimensions(oracle_lib, gpu):
                              len_hi=14, seed=63, default_blank_bias=0.5, max_symbols=3)
     check(oracle_lib, gpu, cfg, projections=1)
     check(oracle_lib, gpu, cfg)
+
+
+# ------------------------------------------------------------------ the streaming joint pass
+BF16_SMALL = [c for c in SMALL if c.dtype == "bf16" and c.h_joint <= 1024]
+# an output layer of several thousand columns on small widths: many column tiles per wavefront,
+# label and duration columns in one tile, a last tile that is mostly padding
+WIDE_OUT = synth.small_config("g_tdt_wide_out_bf16", dtype="bf16", pred_kind="lstm", durations=(0, 1, 2, 4),
+                              d_enc=48, h_pred=56, emb_dim=24, h_joint=72, vocab=4501, B=13, T=40,
+                              len_lo=0, len_hi=40, seed=64, default_blank_bias=2.0, max_symbols=3)
+
+
+@pytest.mark.parametrize("cfg", BF16_SMALL + [WIDE_OUT], ids=[c.name for c in BF16_SMALL + [WIDE_OUT]])
+@pytest.mark.parametrize("window,n_clusters", [(0, 0), (1, 4), (5, 5), (0, 32), (7, 40)])
+def test_streaming_joint_pass(oracle_lib, gpu, cfg, window, n_clusters):
+    """TDT_JOINT_STREAMING forced on models of every shape: every wavefront walks its own column
+    tiles and keeps per-lane argmax / softmax statistics.  Same hypotheses as the oracle."""
+    if n_clusters > max(cfg.B, 4):
+        pytest.skip("more groups than hypotheses")
+    check(oracle_lib, gpu, cfg, window=window, n_clusters=n_clusters, joint_kernel=2)
+
+
+def test_streaming_joint_pass_edges_and_chunks(oracle_lib, gpu):
+    from test_gpu_chunks import check_chunks
+    cfg = WIDE_OUT
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    check(oracle_lib, gpu, cfg, w, enc, ln, u_cap=3, joint_kernel=2)             # capacity reached
+    check(oracle_lib, gpu, cfg, w, enc, ln, max_symbols=1, joint_kernel=2)       # one label a frame
+    check(oracle_lib, gpu, cfg, w, enc[:1], ln[:1] * 0 + cfg.T, joint_kernel=2)  # B = 1
+    out, _ = check(oracle_lib, gpu, cfg)                                         # automatic: streaming (4506 outputs)
+    tiled, _ = check(oracle_lib, gpu, cfg, joint_kernel=1)
+    assert (out["len"] == tiled["len"]).all() and np.abs(out["score"] - tiled["score"]).max() < 1e-3
+    check_chunks(oracle_lib, gpu, cfg, "random", 3, joint_kernel=2)
+    # forcing it where it cannot run is refused
+    f32 = SMALL[2]
+    with pytest.raises(gpu.TdtError) as e:
+        run_gpu(gpu, f32, synth.generate_model(f32), *synth.generate_inputs(f32), 10, joint_kernel=2)
+    assert e.value.code == -3
 
 
 # ------------------------------------------------------------------ the conventional loop order
