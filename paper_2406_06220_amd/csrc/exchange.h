@@ -69,21 +69,39 @@ __device__ inline float wave_sum(float v)
 
 // ---- coherent exchange primitives (see the header comment)
 #define TDT_AGENT __HIP_MEMORY_SCOPE_AGENT
-__device__ inline float ld_co(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, TDT_AGENT); }
-__device__ inline void st_co(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, TDT_AGENT); }
+#define TDT_GLOBAL __attribute__((address_space(1)))
+// Loads through a pointer that is known to point to device memory.  The compiler cannot see that
+// for pointers that went through structures and selections and then emits flat loads, which count
+// against the LDS counter as well: every wait for an LDS access would then wait for them too.
+__device__ inline uint4 ldg_u4(const uint4 *p)
+{
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    const v4u v = *(const TDT_GLOBAL v4u *)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ inline float ldg_f(const float *p) { return *(const TDT_GLOBAL float *)p; }
+
+__device__ inline float ld_co(const float *p)
+{
+    return __hip_atomic_load((const TDT_GLOBAL float *)p, __ATOMIC_RELAXED, TDT_AGENT);
+}
+__device__ inline void st_co(float *p, float v)
+{
+    __hip_atomic_store((TDT_GLOBAL float *)p, v, __ATOMIC_RELAXED, TDT_AGENT);
+}
 __device__ inline float2 ld_co2(const float *p)   // p 8-byte aligned
 {
     const unsigned long long u =
-        __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, TDT_AGENT);
+        __hip_atomic_load((const TDT_GLOBAL unsigned long long *)p, __ATOMIC_RELAXED, TDT_AGENT);
     return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
 }
 __device__ inline unsigned long long ld_co64(const unsigned long long *p)
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, TDT_AGENT);
+    return __hip_atomic_load((const TDT_GLOBAL unsigned long long *)p, __ATOMIC_RELAXED, TDT_AGENT);
 }
 __device__ inline void st_co64(unsigned long long *p, unsigned long long v)
 {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, TDT_AGENT);
+    __hip_atomic_store((TDT_GLOBAL unsigned long long *)p, v, __ATOMIC_RELAXED, TDT_AGENT);
 }
 
 // (logit, index) packed so that an unsigned 64-bit maximum is "largest logit,

@@ -167,7 +167,7 @@ __device__ inline void weight_prefetch(const WeightCursor &wc, const Seg &, int 
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
         const int s = kpart + (c0 + j) * ksplit;
-        b[j] = wc.fr[(size_t)min(s, wc.last) * 64];
+        b[j] = ldg_u4(wc.fr + (size_t)min(s, wc.last) * 64);
     }
     __builtin_amdgcn_sched_barrier(0);
 }
@@ -490,12 +490,15 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
             const uint4 *fr = wbase + (size_t)(tl < n_ct ? tile0 + tl : tile0) * sg.nst * 64;
             w.bias[u] = bias[cc];
 #pragma unroll
-            for (int j = 0; j < WKS; ++j) w.b[j][u] = fr[(size_t)min(s0 + j, nsteps - 1) * 64];
+            for (int j = 0; j < WKS; ++j) w.b[j][u] = ldg_u4(fr + (size_t)min(s0 + j, nsteps - 1) * 64);
         }
     };
     WideChunk wA, wB;
     int ft = 0, fci = 0;   // the next chunk to request
     auto fetch_next = [&](WideChunk &w) {
+#ifdef TDT_PROBE_NOLOAD
+        if (ft == 0 && fci < 2)
+#endif
         fetch(ft, fci, w);
         if (++fci == nch) { fci = 0; ++ft; }
     };
@@ -509,9 +512,13 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
     const uint16_t *arow = A.planes + (size_t)(lane & 15) * A.ldb;
     const size_t plane = (size_t)RT * A.ldb;
     const int zoff = A.ldb - 8;   // a row's padding: zeros (see chunk_products)
-    f32x4 acc[WTW];
+    // one accumulator per plane of the split: three independent chains of products per tile
+    // instead of one (a product that waits for the one before it takes several times as long)
+    f32x4 acc[WTW][3];
 #pragma unroll
-    for (int u = 0; u < WTW; ++u) acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int u = 0; u < WTW; ++u)
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) acc[u][pl] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     float rm[4], rs[4], rdm[4];
     int ra[4], rda[4];
 #pragma unroll
@@ -535,7 +542,12 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
         __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // (the schedule: these three reads first)
 #pragma unroll
         for (int j = 0; j < WKS; ++j) {
+#ifdef TDT_PROBE_NOLDS
+            if (j + 1 < WKS) { x[(j + 1) & 1][0] = x[j & 1][0]; x[(j + 1) & 1][1] = x[j & 1][1]; x[(j + 1) & 1][2] = x[j & 1][2]; }
+            if (false) {
+#else
             if (j + 1 < WKS) {
+#endif
                 const uint16_t *a = arow + aoff(s0 + j + 1);
                 x[(j + 1) & 1][0] = *reinterpret_cast<const bf16x8 *>(a);
                 x[(j + 1) & 1][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
@@ -546,8 +558,8 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
             for (int pl = 0; pl < 3; ++pl)
 #pragma unroll
                 for (int u = 0; u < WTW; ++u)
-                    acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        x[j & 1][pl], *reinterpret_cast<const bf16x8 *>(&w.b[j][u]), acc[u], 0, 0, 0);
+                    acc[u][pl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        x[j & 1][pl], *reinterpret_cast<const bf16x8 *>(&w.b[j][u]), acc[u][pl], 0, 0, 0);
             // keep that order in the schedule: the next step's three LDS reads, then this step's products
             if (j + 1 < WKS) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 3 * WTW, 0);
@@ -557,9 +569,10 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
             for (int u = 0; u < WTW; ++u) {
                 const int tl = (wave + ct_ * kWaves) * WTW + u;
                 const int col = tl < n_ct ? (tile0 + tl) * CT + (lane & 15) : O;   // O: no column
+                const f32x4 sum = acc[u][0] + (acc[u][1] + acc[u][2]);   // smallest terms first
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float v = acc[u][e] + w.bias[u];
+                    const float v = sum[e] + w.bias[u];
                     if (col <= V) {
                         if (v > rm[e]) {
                             rs[e] = (rs[e] > 0.0f ? rs[e] * __expf(rm[e] - v) : 0.0f) + 1.0f;
@@ -573,7 +586,8 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
                         rda[e] = col - (V + 1);
                     }
                 }
-                acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl) acc[u][pl] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
             }
             cci = 0;
             ++ct_;
@@ -581,14 +595,19 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
             ++cci;
         }
     };
-    for (int c = 0; c < total; c += 2) {
-        if (c + 1 < total) fetch_next(wB);
+    // Pairs of chunks in a loop without branches: the compiler then knows how many loads are in
+    // flight where the products wait for their fragments, and leaves the chunk just requested in
+    // flight.  (A request beyond the wavefront's last chunk re-reads a valid fragment.)
+    int c = 0;
+    for (; c + 2 <= total; c += 2) {
+        fetch_next(wB);
         chunk(wA);
         TR(72);
-        if (c + 2 < total) fetch_next(wA);
-        if (c + 1 < total) chunk(wB);
+        fetch_next(wA);
+        chunk(wB);
         TR(72);
     }
+    if (c < total) chunk(wA);
     TR(73);
 
     // ---- one reduction per work item: across the 16 lanes of a row, then across the wavefronts
