@@ -35,6 +35,7 @@ class _Model(C.Structure):
         ("w_enc", _f32p), ("b_enc", _f32p), ("emb", _f32p),
         ("w_ih", _f32p * MAX_LAYERS), ("w_hh", _f32p * MAX_LAYERS), ("b_lstm", _f32p * MAX_LAYERS),
         ("w_pred", _f32p), ("b_pred", _f32p), ("w_out", _f32p), ("b_out", _f32p),
+        ("multi_blank", C.c_int32),
     ]
 
 
@@ -96,6 +97,7 @@ class OracleModel:
                 m.b_lstm[l] = _fp(w[f"b_lstm{l}"])
         m.w_pred, m.b_pred = _fp(w["w_pred"]), _fp(w["b_pred"])
         m.w_out, m.b_out = _fp(w["w_out"]), _fp(w["b_out"])
+        m.multi_blank = 1 if getattr(cfg, "multi_blank", False) else 0
         self.c = m
         self.durations = (np.asarray(cfg.durations, np.int32) if len(cfg.durations)
                           else None)

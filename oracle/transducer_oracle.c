@@ -18,6 +18,15 @@
  *   logits[0..V]       label scores, index V = <blank>
  *   logits[V+1..V+D]   TDT duration scores (D = 0 for a plain Transducer)
  *
+ * Multi-blank Transducer (related work the paper builds on, Sec. 1; multi_blank
+ * != 0): the D extra outputs are "big blank" symbols of the LABEL head, each
+ * with a fixed frame increment durations[i] >= 1.  One argmax and one softmax
+ * over all V+1+D outputs; a label is emitted as in a plain Transducer (the
+ * frame index stays), the standard blank moves on by one frame, big blank i by
+ * durations[i] frames; the predictor is stepped on labels only.  Reading: the
+ * paper only names the model; the advance rule is the one of Sec. 3.3 with the
+ * increment read off the chosen blank symbol instead of a duration head.
+ *
  * Readings of points the paper leaves open (each is a stated choice):
  *   - BOS is the blank index V; its embedding row is whatever the caller
  *     supplies (the generators zero it); the initial LSTM state is zero and the
@@ -68,6 +77,7 @@ typedef struct {
     const float *b_lstm[ORC_MAX_LAYERS]; /* [4*Hp] */
     const float *w_pred, *b_pred;        /* [H][Hp], [H] */
     const float *w_out, *b_out;          /* [V+1+D][H], [V+1+D] */
+    int32_t multi_blank;                 /* the D extra outputs are big blanks of the label head */
 } orc_model_t;
 
 /* predictor state: LSTM h and c per layer, or the last ctx labels */
@@ -296,6 +306,8 @@ static int decode_frames(const orc_model_t *m, const float *enc, int len, const 
                          int64_t *counts, orc_stream_t *stream)
 {
     const int H = m->h_joint, V = m->vocab, D = m->n_dur, O = V + 1 + D;
+    const int MB = m->multi_blank != 0;
+    const int NL = MB ? O : V + 1; /* outputs of the label head */
     float *enc_proj = (float *)malloc(sizeof(float) * (size_t)H);
     float *pred_proj = (float *)malloc(sizeof(float) * (size_t)H);
     float *hid = (float *)malloc(sizeof(float) * (size_t)H);
@@ -337,9 +349,12 @@ static int decode_frames(const orc_model_t *m, const float *enc, int len, const 
         joint_logits(m, enc_proj, pred_proj, hid, logits);
         ++n_joint;
         float mk = INFINITY, mj = INFINITY;
-        const int k = argmax_margin(logits, V + 1, &mk);
+        const int k = argmax_margin(logits, NL, &mk);
         int j = -1, d;
-        if (D > 0) {
+        if (MB) { /* the chosen symbol says how far to move */
+            d = (k < V) ? 0 : (k == V ? 1 : durations[k - V - 1]);
+            if (k > V && d < 1) d = 1;
+        } else if (D > 0) {
             j = argmax_margin(logits + V + 1, D, &mj);
             d = durations[j];
         } else {
@@ -355,14 +370,14 @@ static int decode_frames(const orc_model_t *m, const float *enc, int len, const 
             trace->margin_dur[i] = mj;
         }
         if (trace) ++trace->n;
-        if (k == V) {
+        if (k >= V) { /* the blank, or a big blank */
             if (d == 0) d = 1;
             t += d;
             sym = 0;
         } else {
             out_labels[n_hyp] = k;
             out_frames[n_hyp] = t;
-            score += logits[k] - logsumexp(logits, V + 1);
+            score += logits[k] - logsumexp(logits, NL);
             ++sym;
             if (d == 0 && sym >= max_symbols) d = 1;
             if (out_durs) out_durs[n_hyp] = d;
@@ -523,6 +538,8 @@ static int replay_rec(replay_t *r, int t, int sym, int u, float score, int n_tie
 {
     const orc_model_t *m = r->m;
     const int H = m->h_joint, V = m->vocab, D = m->n_dur;
+    const int MB = m->multi_blank != 0;
+    const int NL = MB ? V + 1 + D : V + 1;
     if (t >= r->len || u >= r->u_cap) {
         if (u == r->cand_len) {
             r->score = score;
@@ -542,16 +559,16 @@ static int replay_rec(replay_t *r, int t, int sym, int u, float score, int n_tie
     /* admissible label choices, exact argmax first */
     int ks[ORC_MAX_ALT], nk = 0, js[ORC_MAX_ALT], nj = 0;
     float lk[ORC_MAX_ALT];
-    const int k0 = argmax_margin(r->logits, V + 1, NULL);
-    const float lse = logsumexp(r->logits, V + 1);
+    const int k0 = argmax_margin(r->logits, NL, NULL);
+    const float lse = logsumexp(r->logits, NL);
     ks[nk] = k0;
     lk[nk++] = r->logits[k0];
-    for (int i = 0; i <= V && nk < ORC_MAX_ALT; ++i)
+    for (int i = 0; i < NL && nk < ORC_MAX_ALT; ++i)
         if (i != k0 && r->logits[i] >= r->logits[k0] - r->tol) {
             ks[nk] = i;
             lk[nk++] = r->logits[i];
         }
-    if (D > 0) {
+    if (D > 0 && !MB) {
         const float *dl = r->logits + V + 1;
         const int j0 = argmax_margin(dl, D, NULL);
         js[nj++] = j0;
@@ -563,9 +580,15 @@ static int replay_rec(replay_t *r, int t, int sym, int u, float score, int n_tie
     for (int a = 0; a < nk; ++a) {
         for (int b = 0; b < nj; ++b) {
             const int k = ks[a];
-            int d = (D > 0) ? r->durations[js[b]] : (k == V ? 1 : 0);
+            int d;
+            if (MB) {
+                d = (k < V) ? 0 : (k == V ? 1 : r->durations[k - V - 1]);
+                if (k > V && d < 1) d = 1;
+            } else {
+                d = (D > 0) ? r->durations[js[b]] : (k == V ? 1 : 0);
+            }
             const int tie = n_tie + (a != 0) + (b != 0);
-            if (k == V) {
+            if (k >= V) {
                 if (d == 0) d = 1;
                 if (replay_rec(r, t + d, 0, u, score, tie)) return 1;
             } else {

@@ -17,7 +17,8 @@ Gaussian draws:
                     zeroed; LSTM, encoder- and predictor-projection biases 0;
 * output bias       0 except the blank entry (a constant per configuration,
                     read from ``workload_bias.json``) and the TDT duration
-                    entries (+1.5 on durations 1 and 2);
+                    entries (+1.5 on durations 1 and 2); the big blanks of a
+                    multi-blank model get the blank's bias minus 0.1 per position;
 * bf16 configs      ``enc`` and every weight matrix are rounded once, here, to
                     bfloat16-representable values (round to nearest even).
 
@@ -55,6 +56,9 @@ class WorkloadConfig:
     seed: int
     blank_target: float        # blank fraction the blank bias was tuned for
     default_blank_bias: float  # used until workload_bias.json has an entry
+    # Multi-blank Transducer: the entries of `durations` are the frame increments of big-blank
+    # symbols that sit in the label head behind the blank (outputs V+1 ...), not a duration head
+    multi_blank: bool = False
 
     @property
     def n_dur(self) -> int:
@@ -187,7 +191,9 @@ def generate_model(cfg: WorkloadConfig, blank_bias_override: Optional[float] = N
     b_out = np.zeros(cfg.n_out, np.float32)
     b_out[V] = blank_bias(cfg) if blank_bias_override is None else blank_bias_override
     for j, d in enumerate(cfg.durations):
-        b_out[V + 1 + j] = TDT_DURATION_BIAS.get(d, 0.0)
+        # (big blanks compete with the blank: its bias, the longer ones a little lower, which makes
+        # every symbol of the head appear in the benchmark-sized and in the small test models)
+        b_out[V + 1 + j] = b_out[V] - 0.1 * j if cfg.multi_blank else TDT_DURATION_BIAS.get(d, 0.0)
     m["b_out"] = b_out
     return m
 

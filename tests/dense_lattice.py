@@ -59,18 +59,21 @@ def greedy_walk(cfg, logits, length, u_cap):
     path's own labels; returns the emissions it reads off, so a caller can check
     self-consistency.  Also returns the smallest top-2 margin met on the way."""
     V, D, S = cfg.vocab, len(cfg.durations), cfg.max_symbols
+    MB = bool(getattr(cfg, "multi_blank", False))
     t = u = sym = 0
     labels, frames, score = [], [], 0.0
     min_margin = np.inf
     n_dec = 0
     while t < length and u < u_cap and u < logits.shape[1]:
         row = logits[t, u]
-        lab = row[: V + 1]
+        lab = row if MB else row[: V + 1]      # multi-blank: one head over all outputs
         k = int(np.argmax(lab))
         srt = np.sort(lab)
         min_margin = min(min_margin, srt[-1] - srt[-2])
         n_dec += 1
-        if D:
+        if MB:
+            d = 0 if k < V else 1 if k == V else max(int(cfg.durations[k - V - 1]), 1)
+        elif D:
             dl = row[V + 1:]
             d = int(cfg.durations[int(np.argmax(dl))])
             if D > 1:
@@ -78,7 +81,7 @@ def greedy_walk(cfg, logits, length, u_cap):
                 min_margin = min(min_margin, ds[-1] - ds[-2])
         else:
             d = 1 if k == V else 0
-        if k == V:
+        if k >= V:                              # the blank, or a big blank
             t += max(d, 1)
             sym = 0
         else:

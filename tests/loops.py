@@ -54,13 +54,16 @@ class ModelFns:
     joiner: Callable[[int, int, object], np.ndarray]
     vocab: int
     durations: Sequence[int] = ()
+    multi_blank: bool = False                    # the D extra outputs are big blanks of the label head
 
 
 def _decide(fns: ModelFns, logits: np.ndarray):
     V, D = fns.vocab, len(fns.durations)
-    lab = logits[: V + 1]
+    lab = logits[: V + 1 + D] if fns.multi_blank else logits[: V + 1]
     k = int(np.argmax(lab))                      # first maximum
-    if D:
+    if fns.multi_blank:                          # the chosen symbol says how far to move
+        d = 0 if k < V else 1 if k == V else max(int(fns.durations[k - V - 1]), 1)
+    elif D:
         d = int(fns.durations[int(np.argmax(logits[V + 1: V + 1 + D]))])
     else:
         d = 1 if k == V else 0
@@ -98,7 +101,7 @@ def label_looping(fns: ModelFns, lens: Sequence[int], max_symbols: int, u_cap: i
             for b in np.nonzero(need)[0]:
                 k[b], d[b], inc[b] = _decide(fns, fns.joiner(b, int(b2time[b]), decs[b]))
                 found[b] = b2time[b]
-                blank_mask[b] = (k[b] == V)
+                blank_mask[b] = (k[b] >= V)      # the blank, or a big blank
                 if blank_mask[b]:
                     b2time[b] += max(int(d[b]), 1)
                     sym[b] = 0
@@ -180,4 +183,5 @@ def oracle_fns(model, enc: np.ndarray) -> ModelFns:
         return model.pred_proj(dec), new_state
 
     return ModelFns(init_state=model.init_state, predictor=predictor, joiner=joiner,
-                    vocab=model.cfg.vocab, durations=tuple(model.cfg.durations))
+                    vocab=model.cfg.vocab, durations=tuple(model.cfg.durations),
+                    multi_blank=bool(getattr(model.cfg, "multi_blank", False)))

@@ -50,6 +50,12 @@ SMALL = [
                        h_pred=16, emb_dim=8, default_blank_bias=0.3),
     synth.small_config("s_bf16_lstm", dtype="bf16", pred_kind="lstm", seed=18, d_enc=16,
                        h_pred=16, emb_dim=16, h_joint=24, vocab=11, default_blank_bias=0.6),
+    # multi-blank Transducers: the durations are big blanks of the label head
+    synth.small_config("s_mb_lstm", pred_kind="lstm", durations=(2, 4), multi_blank=True, seed=31,
+                       T=24, len_lo=10, len_hi=24, B=4, default_blank_bias=0.6),
+    synth.small_config("s_mb_stateless2", pred_layers=2, emb_dim=4, h_pred=8, durations=(2, 3, 5),
+                       multi_blank=True, seed=32, T=24, len_lo=0, len_hi=24, B=5,
+                       default_blank_bias=0.4),
 ]
 IDS = [c.name for c in SMALL]
 
@@ -117,7 +123,8 @@ def test_dense_lattice_brute_force(oracle_lib, cfg):
         # the trace's nodes are the walk's nodes and the recorded margins are the lattice's
         for i in range(len(r["trace"]["t"])):
             t, u = r["trace"]["t"][i], r["trace"]["u"][i]
-            lab = np.sort(lat[t, u, : cfg.vocab + 1])
+            head = cfg.n_out if cfg.multi_blank else cfg.vocab + 1
+            lab = np.sort(lat[t, u, :head])
             assert abs((lab[-1] - lab[-2]) - r["trace"]["margin_lab"][i]) < 1e-4
         # the exported single-node routine agrees with the lattice
         for (t, u) in [(0, 0), (int(ln[b]) - 1, r["len"])] if ln[b] > 0 else []:
@@ -482,3 +489,134 @@ def test_chunk_stopped_at_capacity_loses_its_rest(oracle_lib):
             _, st = m.predictor_step(st, lab)
         n = cfg.pred_layers * cfg.h_pred
         assert (state["h"][b] == st[0][:n]).all()
+
+
+# --------------------------------------------------------------------------- multi-blank
+# Multi-blank Transducer (Sec. 1, related work): big-blank symbols in the label head, each with a
+# fixed frame increment.  Besides the dense lattice and the label-looping re-ordering above (both
+# run on the two multi-blank models of SMALL), the reductions and closed forms below.
+def _mb_pair(seed, durs, extra_bias):
+    """A plain Transducer and the multi-blank model that has its outputs plus big blanks whose
+    rows are given by `extra_bias` (weights zero, so their logits are exactly that bias)."""
+    cfg_r = synth.small_config("mb_r", pred_kind="lstm", T=25, len_lo=10, len_hi=25, seed=seed,
+                               default_blank_bias=0.6)
+    cfg_m = synth.small_config("mb_m", pred_kind="lstm", T=25, len_lo=10, len_hi=25, seed=seed,
+                               default_blank_bias=0.6, durations=durs, multi_blank=True)
+    w_r = synth.generate_model(cfg_r)
+    V, K = cfg_r.vocab, len(durs)
+    w_out = np.concatenate([w_r["w_out"], np.zeros((K, cfg_r.h_joint), np.float32)])
+    b_out = np.concatenate([w_r["b_out"], np.asarray(extra_bias, np.float32)])
+    w_m = dict(w_r, w_out=w_out, b_out=b_out)
+    enc, ln = synth.generate_inputs(cfg_r)
+    return cfg_r, w_r, cfg_m, w_m, enc, ln
+
+
+def test_multi_blank_that_never_wins_is_rnnt(oracle_lib):
+    # big blanks whose logits are -1e30: never the argmax, exp() of them is exactly 0, so labels,
+    # frames, scores and call counts are those of the plain Transducer bit for bit
+    cfg_r, w_r, cfg_m, w_m, enc, ln = _mb_pair(41, (2, 7), (-1e30, -1e30))
+    u_cap = cfg_r.T * cfg_r.max_symbols
+    rr = oracle_lib.decode_batch(oracle_lib.OracleModel(cfg_r, w_r), enc, ln, cfg_r.max_symbols, u_cap)
+    rm = oracle_lib.decode_batch(oracle_lib.OracleModel(cfg_m, w_m), enc, ln, cfg_m.max_symbols, u_cap)
+    assert rr["len"].sum() > 0
+    for key in ("labels", "frames", "len", "score", "n_joint", "n_pred"):
+        assert (rm[key] == rr[key]).all(), key
+
+
+def test_big_blank_of_one_frame_is_the_blank(oracle_lib):
+    # one big blank of duration 1 whose row is a copy of the blank's: wherever the blank would win
+    # the two tie and the first maximum (the blank) is taken; had the big blank won it would move
+    # by one frame all the same.  Labels, frames and call counts equal the plain Transducer's; the
+    # score differs by the one more term in every softmax: log(sum exp) grows by
+    # log(1 + p_blank), so each emitted label's log-probability drops by exactly that.
+    cfg_r, w_r, cfg_m, w_m, enc, ln = _mb_pair(42, (1,), (0.0,))
+    V = cfg_r.vocab
+    w_m["w_out"][V + 1] = w_m["w_out"][V]
+    w_m["b_out"][V + 1] = w_m["b_out"][V]
+    u_cap = cfg_r.T * cfg_r.max_symbols
+    m_r, m_m = oracle_lib.OracleModel(cfg_r, w_r), oracle_lib.OracleModel(cfg_m, w_m)
+    rr = oracle_lib.decode_batch(m_r, enc, ln, cfg_r.max_symbols, u_cap)
+    rm = oracle_lib.decode_batch(m_m, enc, ln, cfg_m.max_symbols, u_cap)
+    for key in ("labels", "frames", "len", "n_joint", "n_pred"):
+        assert (rm[key] == rr[key]).all(), key
+    for b in range(cfg_r.B):
+        n = rr["len"][b]
+        lat = dense_lattice.lattice(cfg_r, w_r, enc[b], rr["labels"][b, :n])
+        drop = 0.0
+        for u in range(n):
+            row = lat[rr["frames"][b, u], u, : V + 1]
+            p_blank = np.exp(row[V] - np.logaddexp.reduce(row))
+            drop += np.log1p(p_blank)
+        assert abs((rr["score"][b] - rm["score"][b]) - drop) < 2e-4 * max(1, n)
+
+
+def test_multi_blank_predictor_off_closed_form(oracle_lib):
+    # with the predictor's projection switched off the logits depend on the frame only, and the
+    # hypothesis can be read off a per-frame table: a label frame emits S copies and moves on by
+    # one, a blank frame moves by one, big blank i by durations[i]
+    durs = (2, 3, 6)
+    cfg = synth.small_config("mb_p4", pred_kind="lstm", durations=durs, multi_blank=True, T=40,
+                             len_lo=25, len_hi=40, seed=43, default_blank_bias=0.5, max_symbols=3, B=4)
+    w = synth.generate_model(cfg)
+    w["w_pred"][:] = 0.0
+    w["b_pred"][:] = 0.0
+    enc, ln = synth.generate_inputs(cfg)
+    m = oracle_lib.OracleModel(cfg, w)
+    r = oracle_lib.decode_batch(m, enc, ln, cfg.max_symbols, cfg.T * cfg.max_symbols)
+    V, S = cfg.vocab, cfg.max_symbols
+    seen = set()
+    for b in range(cfg.B):
+        hid = np.maximum(enc[b].astype(np.float64) @ w["w_enc"].T.astype(np.float64), 0.0)
+        k = (hid @ w["w_out"].T.astype(np.float64) + w["b_out"]).argmax(1)
+        exp_l, exp_f, t, n_joint = [], [], 0, 0
+        while t < ln[b]:
+            seen.add(min(int(k[t]), V) if k[t] <= V else int(k[t]))
+            if k[t] < V:
+                exp_l += [k[t]] * S
+                exp_f += [t] * S
+                n_joint += S
+                t += 1
+            else:
+                n_joint += 1
+                t += 1 if k[t] == V else durs[k[t] - V - 1]
+        n = r["len"][b]
+        assert r["labels"][b, :n].tolist() == exp_l
+        assert r["frames"][b, :n].tolist() == exp_f
+        assert r["n_joint"][b] == n_joint
+    # the example exercises labels, the blank and at least two of the big blanks
+    assert len([x for x in seen if x > V]) >= 2 and V in seen and any(x < V for x in seen)
+
+
+def test_multi_blank_longest_big_blank_skips_the_utterance(oracle_lib):
+    # a big blank that always wins and is as long as the longest utterance: one joint call per
+    # utterance, nothing emitted; with increment 3: ceil(len / 3) calls
+    for inc in (50, 3):
+        cfg = synth.small_config("mb_skip", pred_kind="lstm", durations=(2, inc), multi_blank=True,
+                                 T=30, len_lo=0, len_hi=30, seed=44, B=6)
+        w = synth.generate_model(cfg)
+        w["b_out"][cfg.vocab + 2] = 1e4
+        enc, ln = synth.generate_inputs(cfg)
+        r = oracle_lib.decode_batch(oracle_lib.OracleModel(cfg, w), enc, ln, cfg.max_symbols, 90)
+        assert (r["len"] == 0).all() and (r["score"] == 0).all()
+        assert (r["n_joint"] == -(-ln // inc)).all()
+        assert (r["n_pred"] == 1).all()
+
+
+def test_multi_blank_replay(oracle_lib):
+    # the tolerant replay accepts the oracle's own multi-blank hypotheses with no tie taken and
+    # rejects an edited one
+    cfg = SMALL[IDS.index("s_mb_lstm")]
+    w, enc, ln, m = _setup(oracle_lib, cfg)
+    u_cap = cfg.T * cfg.max_symbols
+    r = oracle_lib.decode_batch(m, enc, ln, cfg.max_symbols, u_cap)
+    assert r["len"].sum() > 0
+    for b in range(cfg.B):
+        n = int(r["len"][b])
+        got = oracle_lib.replay_utt(m, enc[b], int(ln[b]), cfg.max_symbols, u_cap,
+                                    r["labels"][b, :n], r["frames"][b, :n], tol=1e-6)
+        assert got["ok"] and got["n_tie"] == 0 and abs(got["score"] - r["score"][b]) < 1e-5
+        if n:
+            bad = r["frames"][b, :n].copy()
+            bad[n - 1] += 1
+            assert not oracle_lib.replay_utt(m, enc[b], int(ln[b]), cfg.max_symbols, u_cap,
+                                             r["labels"][b, :n], bad)["ok"]
