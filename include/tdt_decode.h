@@ -72,6 +72,12 @@ enum tdt_pred_kind {
  *   logits        = w_out * relu(enc_proj + pred_proj) + b_out
  *   logits[0..V]      label scores (index V = blank)
  *   logits[V+1..V+D]  TDT duration-class scores (n_dur = D; 0 for a Transducer)
+ * Multi-blank Transducer (Sec. 1 of the paper, related work; `multi_blank` != 0): the D
+ * extra outputs are big-blank symbols of the label head instead.  One argmax and one
+ * softmax run over all V+1+D outputs; a label is emitted as in a Transducer (the frame
+ * index stays), the blank moves on by one frame, big blank i (output V+1+i) by
+ * durations[i] frames -- the advance rule of Sec. 3.3 with the increment read off the
+ * chosen symbol.  The predictor sees labels only.
  *
  * LSTM gate order in w_ih / w_hh / b_lstm rows is i, f, g, o (four blocks of
  * h_pred rows); one bias vector per layer.  Layer 0 reads the embedding
@@ -100,6 +106,8 @@ typedef struct {
     const float *b_pred; /* [h_joint] */
     const void *w_out;   /* [V+1+D][h_joint] */
     const float *b_out;  /* [V+1+D] */
+    int32_t multi_blank; /* non-zero: the D extra outputs are big blanks of the label head
+                            (needs n_dur >= 1 and every increment >= 1) */
 } tdt_weights_t;
 
 /*
@@ -222,6 +230,7 @@ int tdt_workspace_bytes(const tdt_weights_t *weights, int B, int T, int u_cap, s
  *   durations   HOST [n_dur] frame increments of the duration classes
  *               (e.g. {0,1,2,3,4}), each in [0, 2^20], at least one positive; NULL
  *               iff n_dur == 0.  A blank with increment 0 advances one frame.
+ *               Multi-blank models: the increments of the big blanks, each in [1, 2^20].
  *   max_symbols most labels a hypothesis may emit without its frame index moving;
  *               on the max_symbols-th the frame index is advanced by one.
  *   u_cap       label capacity per hypothesis; a hypothesis that reaches it stops

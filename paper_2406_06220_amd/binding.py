@@ -51,6 +51,7 @@ class tdt_weights_t(C.Structure):
         ("w_ih", C.c_void_p * TDT_MAX_LSTM_LAYERS), ("w_hh", C.c_void_p * TDT_MAX_LSTM_LAYERS),
         ("b_lstm", C.c_void_p * TDT_MAX_LSTM_LAYERS),
         ("w_pred", C.c_void_p), ("b_pred", C.c_void_p), ("w_out", C.c_void_p), ("b_out", C.c_void_p),
+        ("multi_blank", C.c_int32),
     ]
 
 
@@ -214,6 +215,7 @@ class DeviceModel:
         w = tdt_weights_t()
         w.dtype = 1 if cfg.dtype == "bf16" else 0
         w.d_enc, w.h_joint, w.vocab, w.n_dur = cfg.d_enc, cfg.h_joint, cfg.vocab, cfg.n_dur
+        w.multi_blank = 1 if getattr(cfg, "multi_blank", False) else 0
         w.pred_kind = 1 if cfg.pred_kind == "lstm" else 0
         w.pred_layers, w.h_pred, w.emb_dim = cfg.pred_layers, cfg.h_pred, cfg.emb_dim
         w.w_enc, w.b_enc, w.emb = t["w_enc"].data_ptr(), t["b_enc"].data_ptr(), t["emb"].data_ptr()

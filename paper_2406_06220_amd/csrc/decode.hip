@@ -118,6 +118,9 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         rank = blockIdx.x / ncl;
     }
     const int B = p.B, T = p.T, H = p.H, V = p.V, D = p.D, O = p.O;
+    // the label head: outputs 0 .. VL (a multi-blank model's big blanks follow the blank V)
+    const int VL = p.VL;
+    const bool big_blanks = p.multi_blank != 0;
     // Which hypotheses this cluster decodes.  A cluster runs as long as its longest utterance
     // and costs more per step the more of its hypotheses are still active, so the clusters are
     // made alike: the batch is ranked by length (longest first, ties by index) and dealt in
@@ -887,7 +890,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     const int ti = idx / wide_ntd, c0 = idx - ti * wide_ntd;
                     const int n_ct = min(wide_ntd - c0, jp.w_hi - idx);
                     WideRowStats ws;
-                    wide_item(S, A, sg, wide_t0 + c0, n_ct, V, O, p.b_out, [&]() { stage_joint(sg, ti); }, wait_hook, ws);
+                    wide_item(S, A, sg, wide_t0 + c0, n_ct, VL, O, p.b_out, [&]() { stage_joint(sg, ti); }, wait_hook, ws);
                     if (tid < RT && ti * RT + tid < M) {   // thread i holds row i of the tile
                         const int r = ti * RT + tid;
                         if (ws.s > 0.0f)
@@ -935,12 +938,12 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                 const int t = c >> 4, j = c & 15;
                                 const int col = (tile0 + base + t) * CT + j;
                                 const float logit = cpart_sum(S, t, ksplit, i, j) + S.bias[c];
-                                if (col <= V) {
+                                if (col <= VL) {
                                     lg[e] = logit;
                                     if (logit > m) { m = logit; a = col; }
                                 } else if (col < O && logit > dm) {
                                     dm = logit;
-                                    da = col - (V + 1);
+                                    da = col - (VL + 1);
                                 }
                             }
                         }
@@ -1028,9 +1031,16 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 for (int e = 0; e < kMaxRowsPerPass / kThreads; ++e) {
                     const int r = tid + e * kThreads;
                     if (r < M) {
-                        S.row_a[r] = best[e] ? unpack_index(best[e]) : V;
+                        const int a = best[e] ? unpack_index(best[e]) : V;
+                        S.row_a[r] = a;
                         S.row_m[r] = unpack_value(best[e]);
-                        S.row_d[r] = D > 0 ? S.durations[unpack_index(bd[e]) & (TDT_MAX_DURATIONS - 1)] : 0;
+                        // the frame step that goes with the row's decision: from the duration head
+                        // (Sec. 3.3), or -- multi-blank -- from the chosen symbol itself: the blank
+                        // one frame, big blank i its increment, a label none
+                        int step = 0;
+                        if (D > 0) step = S.durations[unpack_index(bd[e]) & (TDT_MAX_DURATIONS - 1)];
+                        else if (big_blanks) step = a < V ? 0 : a == V ? 1 : S.durations[(a - V - 1) & (TDT_MAX_DURATIONS - 1)];
+                        S.row_d[r] = step;
                     }
                 }
             }
@@ -1047,12 +1057,12 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                 }
                 w = 0;
                 bool found = false;
-                if (D == 0) {   // Alg. 3 lines 10 / 18: a blank moves one frame on
+                if (D == 0 && !big_blanks) {   // Alg. 3 lines 10 / 18: a blank moves one frame on
                     const unsigned long long nb = __ballot(lane < nv && a != V);
                     if (nb) { found = true; w = __ffsll((long long)nb) - 1; } else { w = nv; }
-                } else {        // Sec. 3.3: the step comes from the duration head
+                } else {        // Sec. 3.3: the step comes from the duration head (or the big blank)
                     while (w < nv) {
-                        if (__shfl(a, w, 64) != V) { found = true; break; }
+                        if (__shfl(a, w, 64) < V) { found = true; break; }
                         const int dd = __shfl(dstep, w, 64);
                         w += dd > 0 ? dd : 1;
                     }

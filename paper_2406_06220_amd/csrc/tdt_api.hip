@@ -211,8 +211,10 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     // durations (Sec. 3.3): one non-negative frame increment per class, at least one positive
     if ((weights->n_dur == 0) != (durations == nullptr)) return TDT_ERR_DURATIONS;
     bool any_pos = weights->n_dur == 0;
+    const bool multi_blank = weights->multi_blank != 0;
+    if (multi_blank && weights->n_dur < 1) return TDT_ERR_DURATIONS;
     for (int j = 0; j < weights->n_dur; ++j) {
-        if (durations[j] < 0 || durations[j] > kMaxDuration) return TDT_ERR_DURATIONS;
+        if (durations[j] < (multi_blank ? 1 : 0) || durations[j] > kMaxDuration) return TDT_ERR_DURATIONS;
         any_pos |= durations[j] > 0;
     }
     if (!any_pos) return TDT_ERR_DURATIONS;
@@ -349,7 +351,9 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     p.d_enc = weights->d_enc;
     p.H = weights->h_joint;
     p.V = weights->vocab;
-    p.D = weights->n_dur;
+    p.D = multi_blank ? 0 : weights->n_dur;
+    p.VL = multi_blank ? weights->vocab + weights->n_dur : weights->vocab;
+    p.multi_blank = multi_blank;
     p.O = weights->vocab + 1 + weights->n_dur;
     p.pred_kind = weights->pred_kind;
     p.pred_layers = weights->pred_layers;

@@ -31,7 +31,9 @@ static_assert(sizeof(LsePartial) == 8, "LsePartial must be 8 bytes");
 
 struct DecodeParams {
     // sizes
-    int B, T, d_enc, H, V, D, O;
+    int B, T, d_enc, H, V, D, O;   // D: outputs of the duration head (0 for a multi-blank model)
+    int VL;                // last output of the label head: V, or V + number of big blanks
+    int multi_blank;       // the outputs V+1 .. VL are big blanks with the increments in durations[]
     int pred_kind, pred_layers, h_pred, emb_dim;
     int max_symbols, u_cap;
     int window;            // 0 = automatic

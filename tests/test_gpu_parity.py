@@ -195,6 +195,14 @@ SMALL = [
     synth.small_config("g_tdt_lstm2_bf16_narrow", dtype="bf16", pred_kind="lstm", pred_layers=2,
                        durations=(0, 1, 3, 5), d_enc=400, h_pred=360, emb_dim=312, h_joint=16, vocab=449,
                        B=114, T=29, len_lo=28, len_hi=29, seed=1023, default_blank_bias=0.87, max_symbols=3),
+    # multi-blank Transducers (big blanks in the label head): float32 stateless with two labels of
+    # context, and an LSTM model on the matrix cores whose label head ends inside a column tile
+    synth.small_config("g_mb_stateless2", d_enc=16, h_pred=16, emb_dim=8, pred_layers=2, h_joint=24,
+                       vocab=13, durations=(2, 3, 5), multi_blank=True, B=12, T=50, len_lo=0, len_hi=50,
+                       seed=65, default_blank_bias=0.6),
+    synth.small_config("g_mb_lstm_bf16", dtype="bf16", pred_kind="lstm", durations=(2, 4, 8),
+                       multi_blank=True, d_enc=40, h_pred=72, emb_dim=24, h_joint=104, vocab=45, B=20,
+                       T=70, len_lo=0, len_hi=70, seed=66, default_blank_bias=0.8, max_symbols=4),
 ]
 
 
@@ -657,3 +665,55 @@ def test_config5_large_tdt_sampled_rows(oracle_lib, gpu):
         assert n > 0 and ((lab >= 0) & (lab < cfg.vocab)).all()
         assert (np.diff(fr) >= 0).all() and (fr >= 0).all() and (fr < ln[b]).all()
         assert out["score"][b] < 0 and out["status"][b] == 0
+
+
+# ------------------------------------------------------------------ multi-blank Transducers
+def test_multi_blank_models(oracle_lib, gpu):
+    """Big blanks in the label head (Sec. 1): beside the two models of SMALL in every variant above,
+    a model of the benchmark's size, the chunked form, the edges, and the reductions the oracle is
+    pinned with -- big blanks that never win give the plain Transducer's result bit for bit."""
+    import dataclasses
+    from test_gpu_chunks import check_chunks
+    cfg = dataclasses.replace(synth.CFG2, name="cfg2_multi_blank", durations=(2, 3, 4), multi_blank=True, B=24)
+    w = synth.generate_model(cfg)
+    enc, ln = synth.generate_inputs(cfg)
+    out, res = check(oracle_lib, gpu, cfg, w, enc, ln, rows=range(0, 24, 3))
+    check(oracle_lib, gpu, cfg, w, enc, ln, rows=range(0, 24, 6), projections=1)
+    small = [c for c in SMALL if c.multi_blank]
+    for c in small:
+        ws = synth.generate_model(c)
+        e, l = synth.generate_inputs(c)
+        check(oracle_lib, gpu, c, ws, e, l, u_cap=3)                 # capacity reached
+        check(oracle_lib, gpu, c, ws, e, l, max_symbols=1)           # one label a frame
+        check(oracle_lib, gpu, c, ws, e[:1], l[:1] * 0 + c.T)        # B = 1
+        check_chunks(oracle_lib, gpu, c, "random", 3)
+        check_chunks(oracle_lib, gpu, c, "single", 0)
+    # a big blank that always wins: nothing is emitted, ceil(len / increment) rows are scored
+    c = small[1]
+    ws = synth.generate_model(c)
+    ws["b_out"][c.vocab + 2] = 1e4
+    e, l = synth.generate_inputs(c)
+    out = run_gpu(gpu, c, ws, e, l, 10, window=1)
+    assert (out["len"] == 0).all() and (out["score"] == 0).all()
+    assert out["stats"]["joint_rows"] == int((-(-l // c.durations[1])).sum())
+    # big blanks that never win: the plain Transducer's labels, frames and scores, bit for bit
+    c_r = synth.small_config("g_mb_reduction", dtype="bf16", pred_kind="lstm", d_enc=40, h_pred=72,
+                             emb_dim=24, h_joint=104, vocab=45, B=20, T=70, len_lo=0, len_hi=70,
+                             seed=67, default_blank_bias=0.8, max_symbols=4)
+    c_m = dataclasses.replace(c_r, durations=(2, 7), multi_blank=True)
+    w_r = synth.generate_model(c_r)
+    w_m = dict(w_r, w_out=np.concatenate([w_r["w_out"], np.zeros((2, c_r.h_joint), np.float32)]),
+               b_out=np.concatenate([w_r["b_out"], np.full(2, -1e30, np.float32)]))
+    e, l = synth.generate_inputs(c_r)
+    o_r = run_gpu(gpu, c_r, w_r, e, l, c_r.T * c_r.max_symbols)
+    o_m = run_gpu(gpu, c_m, w_m, e, l, c_r.T * c_r.max_symbols)
+    for key in ("labels", "frames", "len", "score"):
+        assert (o_r[key] == o_m[key]).all(), key
+
+
+def test_multi_blank_arguments(gpu):
+    """An increment below one frame is refused for a multi-blank model."""
+    c = synth.small_config("g_mb_bad", durations=(0, 2), multi_blank=True, B=2, T=5, len_lo=5, len_hi=5)
+    with pytest.raises(gpu.TdtError) as e:
+        run_gpu(gpu, c, synth.generate_model(c), *synth.generate_inputs(c), 10)
+    assert e.value.code == -4
