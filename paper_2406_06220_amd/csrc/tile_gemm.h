@@ -5,6 +5,8 @@
 #ifndef TDT_TILE_GEMM_H
 #define TDT_TILE_GEMM_H
 
+#include <type_traits>
+
 #include "tdt_internal.h"
 #include "decode_state.h"
 #include "exchange.h"
@@ -496,9 +498,6 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
     WideChunk wA, wB;
     int ft = 0, fci = 0;   // the next chunk to request
     auto fetch_next = [&](WideChunk &w) {
-#ifdef TDT_PROBE_NOLOAD
-        if (ft == 0 && fci < 2)
-#endif
         fetch(ft, fci, w);
         if (++fci == nch) { fci = 0; ++ft; }
     };
@@ -528,30 +527,28 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
         ra[e] = rda[e] = 0x7fffffff;
     }
     int ct_ = 0, cci = 0;   // the chunk being multiplied
-    // the products of one chunk; at the end of a group the logits of this lane update the statistics
-    auto chunk = [&](const WideChunk &w) {
+    // The activation fragments of step j of the chunk.  A chunk that lies inside the reduction
+    // (every chunk when the joint width is a multiple of 32 * WKS) reads them at constant offsets
+    // from three per-lane addresses computed once per chunk; otherwise every step is checked
+    // against the end of the reduction (a step beyond it reads the zero padding).
+    auto products = [&](const WideChunk &w, auto whole_tag) {
+        constexpr bool kWhole = decltype(whole_tag)::value;
         const int s0 = cci * WKS;
-        auto aoff = [&](int s) { return s < nsteps ? s * 32 + kq : zoff; };
+        const uint16_t *a0 = arow + (size_t)s0 * 32 + kq;
+        auto frag = [&](int j, int pl) -> const uint16_t * {
+            if constexpr (kWhole) return a0 + pl * plane + j * 32;
+            else return arow + (s0 + j < nsteps ? (s0 + j) * 32 + kq : zoff) + pl * plane;
+        };
         bf16x8 x[2][3];
-        {
-            const uint16_t *a = arow + aoff(s0);
-            x[0][0] = *reinterpret_cast<const bf16x8 *>(a);
-            x[0][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
-            x[0][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
-        }
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) x[0][pl] = *reinterpret_cast<const bf16x8 *>(frag(0, pl));
         __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // (the schedule: these three reads first)
 #pragma unroll
         for (int j = 0; j < WKS; ++j) {
-#ifdef TDT_PROBE_NOLDS
-            if (j + 1 < WKS) { x[(j + 1) & 1][0] = x[j & 1][0]; x[(j + 1) & 1][1] = x[j & 1][1]; x[(j + 1) & 1][2] = x[j & 1][2]; }
-            if (false) {
-#else
             if (j + 1 < WKS) {
-#endif
-                const uint16_t *a = arow + aoff(s0 + j + 1);
-                x[(j + 1) & 1][0] = *reinterpret_cast<const bf16x8 *>(a);
-                x[(j + 1) & 1][1] = *reinterpret_cast<const bf16x8 *>(a + plane);
-                x[(j + 1) & 1][2] = *reinterpret_cast<const bf16x8 *>(a + 2 * plane);
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl)
+                    x[(j + 1) & 1][pl] = *reinterpret_cast<const bf16x8 *>(frag(j + 1, pl));
             }
             // consecutive products go to different accumulators
 #pragma unroll
@@ -564,6 +561,11 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
             if (j + 1 < WKS) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 3 * WTW, 0);
         }
+    };
+    // the products of one chunk; at the end of a group the logits of this lane update the statistics
+    auto chunk = [&](const WideChunk &w) {
+        if ((cci + 1) * WKS <= nsteps) products(w, std::true_type{});   // uniform over the wavefront
+        else products(w, std::false_type{});
         if (cci == nch - 1) {   // uniform over the wavefront: the group is complete
 #pragma unroll
             for (int u = 0; u < WTW; ++u) {
