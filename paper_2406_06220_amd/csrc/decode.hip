@@ -265,7 +265,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
 #pragma unroll
     for (int j = 0; j < kDeferPerWave; ++j) pend_u[j] = 0ull;
     auto finish_scores = [&]() {   // all threads; the loads were issued a phase ago
-        const int n = S.pend_n, ncg = S.pend_ncg;
+        const int n = uni(S.pend_n), ncg = uni(S.pend_ncg);
 #pragma unroll
         for (int j = 0; j < kDeferPerWave; ++j) {
             const int q = wave + j * kWaves;
@@ -379,7 +379,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     int q_for_tiles = -1, q_tpg = 1, q_ga = 0, q_gb = 0;
     while (ok) {   // ---- Alg. 3 line 5: while any hypothesis is active
         if (!(kPlain && have_act)) build_list(S, S.active, G, S.act_list, &S.n_act);
-        const int n_act = S.n_act;
+        // (what every lane reads from the same LDS word is uniform, but the compiler cannot know:
+        // counts and plans go through readfirstlane, so that the loops and branches they steer
+        // are scalar and the waits for loads in flight behind them stay exact)
+        const int n_act = uni(S.n_act);
         if (n_act == 0) break;
         st_pred_passes += 1;
         const int n_tiles_a = (n_act + RT - 1) / RT;
@@ -391,7 +394,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         if (chunked && first) {
             build_list(S, S.need, G, S.need_list, &S.n_need);
             plist = S.need_list;
-            n_p = S.n_need;
+            n_p = uni(S.n_need);
             if (lstm) {
                 // the state brought along goes where this iteration's step would have put it
                 const int per = L * Hp;
@@ -662,13 +665,22 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             __syncthreads();
             build_list(S, S.need, G, S.need_list, &S.n_need);
             jl = S.need_list;
-            n_need = S.n_need;
+            n_need = uni(S.n_need);
         }
 
         // ---- inner loop (Alg. 3 line 12): joint passes until nobody searches any more
         while (n_need > 0) {
             const int NT = (O + CT - 1) / CT;
-            const JointPlan jp = S.jplan[n_need];
+            JointPlan jp = S.jplan[n_need];
+            jp.Kw = (short)uni(jp.Kw);
+            jp.n_tiles = (short)uni(jp.n_tiles);
+            jp.n_cg = (short)uni(jp.n_cg);
+            jp.ti0 = (short)uni(jp.ti0);
+            jp.tpg = uni(jp.tpg);
+            jp.cg0 = uni(jp.cg0);
+            jp.rcp_kw = uni(jp.rcp_kw);
+            jp.w_lo = uni(jp.w_lo);
+            jp.w_hi = uni(jp.w_hi);
             const int Kw = jp.Kw, n_tiles = jp.n_tiles, n_cg = jp.n_cg, tpg = jp.tpg;
             const int M = n_need * Kw;
             LsePartial *pbuf = pbase + (size_t)(jpass & 1u) * kPartialEntries;
@@ -1168,7 +1180,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             build_two_lists(S, G, S.need, S.need_list, &S.n_need, S.active, S.act_list, &S.n_act);
             have_act = true;
             jl = S.need_list;
-            n_need = S.n_need;
+            n_need = uni(S.n_need);
             TR(5);
             lap(kTkD);
             if (FRAMELOOP) break;   // Alg. 2: the next step starts with the predictor again

@@ -482,7 +482,7 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
     const uint4 *wbase = static_cast<const uint4 *>(sg.w) + (size_t)(sg.k0 >> 5) * 64 + lane;
     // chunk (t, ci) of this wavefront: tiles tile0 + (wave + t * 8) * WTW + u, k-steps ci * WKS ...
     // (a tile beyond the item, a column beyond the matrix: a valid row, results never looked at)
-    auto fetch = [&](int t, int ci, WideChunk &w) {
+    auto fetch = [&](int t, int ci, WideChunk &w) __attribute__((always_inline)) {
         const int s0 = ci * WKS;
 #pragma unroll
         for (int u = 0; u < WTW; ++u) {
@@ -497,9 +497,13 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
     };
     WideChunk wA, wB;
     int ft = 0, fci = 0;   // the next chunk to request
-    auto fetch_next = [&](WideChunk &w) {
+    auto fetch_next = [&](WideChunk &w) __attribute__((always_inline)) {
         fetch(ft, fci, w);
-        if (++fci == nch) { fci = 0; ++ft; }
+        {   // (selections, not branches with stores: those would put the counters into memory)
+            const bool wrap = fci + 1 == nch;
+            ft += wrap ? 1 : 0;
+            fci = wrap ? 0 : fci + 1;
+        }
     };
     if (total > 0) fetch_next(wA);   // before the rows this item depends on have arrived
     TR(70);
@@ -531,9 +535,28 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
     // (every chunk when the joint width is a multiple of 32 * WKS) reads them at constant offsets
     // from three per-lane addresses computed once per chunk; otherwise every step is checked
     // against the end of the reduction (a step beyond it reads the zero padding).
-    auto products = [&](const WideChunk &w, auto whole_tag) {
+    // The fragments of the chunk after this one are requested one k-step at a time, between the
+    // products: a wavefront that asks for a whole chunk at once sits in the compute unit's queue
+    // for the address path (64 bytes a clock for all eight wavefronts: 0.36 us per chunk measured)
+    // while its matrix core idles.
+    auto products = [&](const WideChunk &w, WideChunk &wn, auto whole_tag) __attribute__((always_inline)) {
         constexpr bool kWhole = decltype(whole_tag)::value;
         const int s0 = cci * WKS;
+        // the chunk to request (uniform)
+        const int ns0 = fci * WKS;
+        const uint4 *nfr[WTW];
+#pragma unroll
+        for (int u = 0; u < WTW; ++u) {
+            const int tl = (wave + ft * kWaves) * WTW + u;
+            const int col = (tile0 + tl) * CT + (lane & 15);
+            nfr[u] = wbase + (size_t)(tl < n_ct ? tile0 + tl : tile0) * sg.nst * 64;
+            wn.bias[u] = ldg_f(bias + (tl < n_ct && col < O ? col : 0));
+        }
+        {   // (selections, not branches with stores: those would put the counters into memory)
+            const bool wrap = fci + 1 == nch;
+            ft += wrap ? 1 : 0;
+            fci = wrap ? 0 : fci + 1;
+        }
         const uint16_t *a0 = arow + (size_t)s0 * 32 + kq;
         auto frag = [&](int j, int pl) -> const uint16_t * {
             if constexpr (kWhole) return a0 + pl * plane + j * 32;
@@ -557,15 +580,19 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
                 for (int u = 0; u < WTW; ++u)
                     acc[u][pl] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                         x[j & 1][pl], *reinterpret_cast<const bf16x8 *>(&w.b[j][u]), acc[u][pl], 0, 0, 0);
-            // keep that order in the schedule: the next step's three LDS reads, then this step's products
+#pragma unroll
+            for (int u = 0; u < WTW; ++u) wn.b[j][u] = ldg_u4(nfr[u] + (size_t)min(ns0 + j, nsteps - 1) * 64);
+            // keep that order in the schedule: the next step's three LDS reads, this step's
+            // products, the request for the next chunk's fragments of this step
             if (j + 1 < WKS) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 3 * WTW, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, WTW, 0);
         }
     };
     // the products of one chunk; at the end of a group the logits of this lane update the statistics
-    auto chunk = [&](const WideChunk &w) {
-        if ((cci + 1) * WKS <= nsteps) products(w, std::true_type{});   // uniform over the wavefront
-        else products(w, std::false_type{});
+    auto chunk = [&](const WideChunk &w, WideChunk &wn) __attribute__((always_inline)) {
+        if ((cci + 1) * WKS <= nsteps) products(w, wn, std::true_type{});   // uniform over the wavefront
+        else products(w, wn, std::false_type{});
         if (cci == nch - 1) {   // uniform over the wavefront: the group is complete
 #pragma unroll
             for (int u = 0; u < WTW; ++u) {
@@ -591,25 +618,23 @@ __device__ inline void wide_item(HypShared &S, const ActTile<uint16_t> &A, const
 #pragma unroll
                 for (int pl = 0; pl < 3; ++pl) acc[u][pl] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
             }
-            cci = 0;
-            ++ct_;
-        } else {
-            ++cci;
+        }
+        {
+            const bool last = cci == nch - 1;
+            ct_ += last ? 1 : 0;
+            cci = last ? 0 : cci + 1;
         }
     };
-    // Pairs of chunks in a loop without branches: the compiler then knows how many loads are in
-    // flight where the products wait for their fragments, and leaves the chunk just requested in
-    // flight.  (A request beyond the wavefront's last chunk re-reads a valid fragment.)
+    // Every chunk requests the one after it (beyond the wavefront's last chunk: a valid fragment
+    // again), so the number of loads in flight is the same at every wait.
     int c = 0;
     for (; c + 2 <= total; c += 2) {
-        fetch_next(wB);
-        chunk(wA);
+        chunk(wA, wB);
         TR(72);
-        fetch_next(wA);
-        chunk(wB);
+        chunk(wB, wA);
         TR(72);
     }
-    if (c < total) chunk(wA);
+    if (c < total) chunk(wA, wB);
     TR(73);
 
     // ---- one reduction per work item: across the 16 lanes of a row, then across the wavefronts
