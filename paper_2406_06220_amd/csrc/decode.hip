@@ -67,6 +67,10 @@ extern "C" int tdt_debug_trace(long long *out, int n)
 }
 #endif
 
+#ifndef TDT_TIMER_GROUP
+#define TDT_TIMER_GROUP 0   // the hypothesis group whose phase timers a build with TDT_PHASE_TIMERS reports
+#endif
+
 namespace tdt {
 namespace {
 
@@ -1241,7 +1245,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
             atomicMax((unsigned long long *)&p.out_stats[TDT_STAT_JOINT_PASSES_MAX],
                       (unsigned long long)st_joint_passes);
             if (!ok) add(TDT_STAT_ABORT, 1);
-            if (TDT_PHASE_TIMERS && cl == 0) {   // where the first cluster's time went, in wall-clock ticks
+            if (TDT_PHASE_TIMERS && cl == TDT_TIMER_GROUP) {   // where one cluster's time went, in wall-clock ticks
                 add(TDT_STAT_TICKS_PRED, S.tk[kTkP]);
                 add(TDT_STAT_TICKS_PROJ, S.tk[kTkQ]);
                 add(TDT_STAT_TICKS_JOINT, S.tk[kTkJ]);
