@@ -81,6 +81,27 @@ def test_workspace_bytes(lib):
     assert lib.tdt_workspace_bytes(C.byref(w), 1, 1, 1, None) == -1
 
 
+def test_workspace_holds_the_fragment_major_copies(lib):
+    """A bfloat16 model's workspace is the float32 model's plus the fragment-major copies of the
+    matrices the decode kernel streams: per matrix [N][K], ceil(N / 16) column tiles (an LSTM gate
+    matrix: ceil(h_pred / 4) tiles of 4 units x 4 gates) times ceil(K / 32) steps of 1 KiB."""
+    import dataclasses
+
+    def packed(cfg):
+        tiles = lambda n: -(-n // 16)
+        steps = lambda k: -(-k // 32)
+        H, Hp = cfg.h_joint, cfg.h_pred
+        n = tiles(H) * steps(cfg.d_enc) + tiles(H) * steps(Hp) + tiles(cfg.n_out) * steps(H)
+        if cfg.pred_kind == "lstm":
+            n += (2 * cfg.pred_layers - 1) * (-(-Hp // 4)) * steps(Hp)
+        return -(-n * 1024 // 256) * 256
+
+    for cfg in (synth.CFG2, synth.CFG4, synth.CFG5, dataclasses.replace(synth.CFG3, h_pred=648, emb_dim=648, h_joint=1000)):
+        bf = binding.tdt_workspace_bytes(_weights(cfg), cfg.B, cfg.T, 100)
+        f32 = binding.tdt_workspace_bytes(_weights(dataclasses.replace(cfg, dtype="fp32")), cfg.B, cfg.T, 100)
+        assert bf - f32 == packed(cfg), cfg.name
+
+
 def test_rejects_bad_arguments_before_device_work(lib):
     cfg = synth.CFG3
     w = _weights(cfg)
@@ -110,6 +131,10 @@ def test_rejects_bad_arguments_before_device_work(lib):
     assert _decode(lib, w, durations=[0, 0, 0, 0, 0]) == -4      # no positive entry
     assert _decode(lib, w, durations=[0, 1, -1, 3, 4]) == -4     # negative entry
     assert _decode(lib, _weights(synth.CFG2), durations=[1]) == -4   # list given to a Transducer
+    wm = _weights(cfg); wm.multi_blank = 1                           # multi-blank: increments of at least one frame
+    assert _decode(lib, wm, durations=[0, 1, 2, 3, 4]) == -4
+    wm = _weights(synth.CFG2); wm.multi_blank = 1                    # ... and at least one big blank
+    assert _decode(lib, wm) == -4
     # options
     o = binding.tdt_options_t(); o.window = 65
     assert _decode(lib, w, durations=dur, options=o) == -3
