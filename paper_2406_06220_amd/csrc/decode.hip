@@ -827,7 +827,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         if (!p.pred_tab) {
                             // the predictor output was projected by this iteration's phase Q (or, on
                             // the fly, by the phase before this pass): coherent loads
-                            stage_segment<WT>(
+                            // (a coherent load is 8 bytes at most: two of them, next to each other,
+                            // per lane and step -- that pair runs at the rate of a 16-byte load, while
+                            // 8-byte loads of consecutive lanes run at half of it)
+                            stage_segment4<WT>(
                                 A, sg.K, nrows,
                                 [&](int i) {
                                     JointRow c = row_of(i);
@@ -835,19 +838,22 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                     return c;
                                 },
                                 [](const JointRow &c, int k) {
-                                    EncPred v;
-                                    if constexpr (ONTHEFLY) v.e = ld_co2(c.enc + k);   // written a phase ago
-                                    else v.e = *reinterpret_cast<const float2 *>(c.enc + k);
-                                    v.p = ld_co2(c.pred + k);
+                                    EncPred4 v;
+                                    if constexpr (ONTHEFLY) v.e = ld_co4(c.enc + k);   // written a phase ago
+                                    else v.e = *reinterpret_cast<const float4 *>(c.enc + k);
+                                    v.p = ld_co4(c.pred + k);
                                     return v;
                                 },
-                                [](const JointRow &c, int, EncPred v) {
-                                    return make_float2(c.valid ? fmaxf(v.e.x + v.p.x, 0.0f) : 0.0f,
-                                                       c.valid ? fmaxf(v.e.y + v.p.y, 0.0f) : 0.0f);
+                                [](const JointRow &c, int, EncPred4 v) {
+                                    return make_float4(c.valid ? fmaxf(v.e.x + v.p.x, 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.y + v.p.y, 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.z + v.p.z, 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.w + v.p.w, 0.0f) : 0.0f);
                                 });
                         } else if (L == 1) {
                             // stateless predictor, one label of context: a row of its table
-                            stage_segment<WT>(
+                            // (nothing here is written by the kernel: plain 16-byte loads)
+                            stage_segment4<WT>(
                                 A, sg.K, nrows,
                                 [&](int i) {
                                     JointRow c = row_of(i);
@@ -855,20 +861,22 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                     return c;
                                 },
                                 [](const JointRow &c, int k) {
-                                    EncPred v;
-                                    v.e = *reinterpret_cast<const float2 *>(c.enc + k);
-                                    v.p = *reinterpret_cast<const float2 *>(c.pred + k);
+                                    EncPred4 v;
+                                    v.e = *reinterpret_cast<const float4 *>(c.enc + k);
+                                    v.p = *reinterpret_cast<const float4 *>(c.pred + k);
                                     return v;
                                 },
-                                [](const JointRow &c, int, EncPred v) {
-                                    return make_float2(c.valid ? fmaxf(v.e.x + v.p.x, 0.0f) : 0.0f,
-                                                       c.valid ? fmaxf(v.e.y + v.p.y, 0.0f) : 0.0f);
+                                [](const JointRow &c, int, EncPred4 v) {
+                                    return make_float4(c.valid ? fmaxf(v.e.x + v.p.x, 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.y + v.p.y, 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.z + v.p.z, 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.w + v.p.w, 0.0f) : 0.0f);
                                 });
                         } else {
                             // two labels of context: the older label's row of table 0 plus the newest
                             // label's row of table 1 (which carries the bias) is the projected output
                             // (three loads per slot: one row of the wavefront at a time)
-                            stage_segment<WT, 1>(
+                            stage_segment4<WT, 1>(
                                 A, sg.K, nrows,
                                 [&](int i) {
                                     JointRow c = row_of(i);
@@ -877,15 +885,17 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                     return c;
                                 },
                                 [](const JointRow &c, int k) {
-                                    EncPred2 v;
-                                    v.e = *reinterpret_cast<const float2 *>(c.enc + k);
-                                    v.p = *reinterpret_cast<const float2 *>(c.pred + k);
-                                    v.p2 = *reinterpret_cast<const float2 *>(c.pred2 + k);
+                                    EncPred4x2 v;
+                                    v.e = *reinterpret_cast<const float4 *>(c.enc + k);
+                                    v.p = *reinterpret_cast<const float4 *>(c.pred + k);
+                                    v.p2 = *reinterpret_cast<const float4 *>(c.pred2 + k);
                                     return v;
                                 },
-                                [](const JointRow &c, int, EncPred2 v) {
-                                    return make_float2(c.valid ? fmaxf(v.e.x + (v.p.x + v.p2.x), 0.0f) : 0.0f,
-                                                       c.valid ? fmaxf(v.e.y + (v.p.y + v.p2.y), 0.0f) : 0.0f);
+                                [](const JointRow &c, int, EncPred4x2 v) {
+                                    return make_float4(c.valid ? fmaxf(v.e.x + (v.p.x + v.p2.x), 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.y + (v.p.y + v.p2.y), 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.z + (v.p.z + v.p2.z), 0.0f) : 0.0f,
+                                                       c.valid ? fmaxf(v.e.w + (v.p.w + v.p2.w), 0.0f) : 0.0f);
                                 });
                         }
                                 };

@@ -132,6 +132,13 @@ struct EncPred {
 struct EncPred2 {
     float2 e, p, p2;
 };
+// the same for four inputs (plain 16-byte loads from the per-label tables of a stateless predictor)
+struct EncPred4 {
+    float4 e, p;
+};
+struct EncPred4x2 {
+    float4 e, p, p2;
+};
 // where one row of a joint pass reads them (valid false: past the end of the utterance)
 struct JointRow {
     const float *enc, *pred, *pred2;

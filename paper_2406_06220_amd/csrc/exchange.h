@@ -95,6 +95,11 @@ __device__ inline float2 ld_co2(const float *p)   // p 8-byte aligned
         __hip_atomic_load((const TDT_GLOBAL unsigned long long *)p, __ATOMIC_RELAXED, TDT_AGENT);
     return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
 }
+__device__ inline float4 ld_co4(const float *p)   // p 16-byte aligned: two coherent 8-byte loads
+{
+    const float2 lo = ld_co2(p), hi = ld_co2(p + 2);
+    return make_float4(lo.x, lo.y, hi.x, hi.y);
+}
 __device__ inline unsigned long long ld_co64(const unsigned long long *p)
 {
     return __hip_atomic_load((const TDT_GLOBAL unsigned long long *)p, __ATOMIC_RELAXED, TDT_AGENT);

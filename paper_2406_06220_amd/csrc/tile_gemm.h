@@ -47,6 +47,19 @@ template <> struct ActTile<uint16_t> {
             *reinterpret_cast<unsigned *>(planes + ((size_t)pl * RT + i) * ldb + k) =
                 (a[pl] >> 16) | (b[pl] & 0xffff0000u);
     }
+    // four consecutive inputs k .. k+3 (k a multiple of 4): one 8-byte store per plane
+    __device__ void store4(int i, int k, float4 v) const
+    {
+        unsigned a[3], b[3], c[3], d[3];
+        split3(v.x, a[0], a[1], a[2]);
+        split3(v.y, b[0], b[1], b[2]);
+        split3(v.z, c[0], c[1], c[2]);
+        split3(v.w, d[0], d[1], d[2]);
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)
+            *reinterpret_cast<uint2 *>(planes + ((size_t)pl * RT + i) * ldb + k) =
+                make_uint2((a[pl] >> 16) | (b[pl] & 0xffff0000u), (c[pl] >> 16) | (d[pl] & 0xffff0000u));
+    }
 };
 
 template <> struct ActTile<float> {
@@ -56,6 +69,10 @@ template <> struct ActTile<float> {
     __device__ void store2(int i, int k, float2 v) const
     {
         *reinterpret_cast<float2 *>(planes + (size_t)i * ldb + k) = v;
+    }
+    __device__ void store4(int i, int k, float4 v) const
+    {
+        *reinterpret_cast<float4 *>(planes + (size_t)i * ldb + k) = v;
     }
 };
 
@@ -121,6 +138,64 @@ __device__ inline void stage_segment(const ActTile<WT> &A, int K, int nrows, Ctx
     // 64 lanes x 2 inputs per step: pick the unrolling that covers K without spare loads
     if (K <= 640) stage_segment_impl<WT, 5, RB>(A, K, nrows, ctx, load, mix);
     else stage_segment_impl<WT, KSEG / 128, RB>(A, K, nrows, ctx, load, mix);
+}
+
+// The same with four inputs (16 bytes) per lane and step: mix(c, k, load(c, k)) gives inputs
+// k .. k+3 of row i.  For sources that plain loads may read (what the kernel itself does not
+// write): a compute unit takes in 16-byte-per-lane loads at nearly twice the rate of
+// 8-byte-per-lane ones (measured: 53 against 30 bytes a clock).
+template <typename WT, int KIT, int RB, typename CtxF, typename LoadF, typename MixF>
+__device__ inline void stage_segment4_impl(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
+{
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int Kpad = ((K + 31) / 32) * 32;
+    constexpr int RPW = RT / kWaves;
+    static_assert(RPW % RB == 0, "rows per round must divide the rows of a wavefront");
+#pragma unroll
+    for (int i0 = 0; i0 < RPW; i0 += RB) {
+        decltype(ctx(0)) c[RB];
+#pragma unroll
+        for (int ii = 0; ii < RB; ++ii) {
+            const int i = wave + (i0 + ii) * kWaves;
+            c[ii] = ctx(i < nrows ? i : 0);
+        }
+        decltype(load(c[0], 0)) v[RB][KIT];
+#pragma unroll
+        for (int ii = 0; ii < RB; ++ii)
+            if (wave + (i0 + ii) * kWaves < nrows) {
+#pragma unroll
+                for (int kk = 0; kk < KIT; ++kk) {
+                    const int k = lane * 4 + kk * 256;
+                    v[ii][kk] = load(c[ii], k < K ? k : K - 4);
+                }
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        TR(60);
+#if TDT_TRACE
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        TR(61);
+#endif
+#pragma unroll
+        for (int ii = 0; ii < RB; ++ii)
+            if (wave + (i0 + ii) * kWaves < nrows) {
+#pragma unroll
+                for (int kk = 0; kk < KIT; ++kk) {
+                    const int i = wave + (i0 + ii) * kWaves, k = lane * 4 + kk * 256;
+                    const float4 x = mix(c[ii], k < K ? k : K - 4, v[ii][kk]);
+                    // (K is a multiple of 8: the four inputs lie on one side of it)
+                    if (k < Kpad) A.store4(i, k, k < K ? x : make_float4(0.0f, 0.0f, 0.0f, 0.0f));
+                }
+            }
+    }
+}
+
+template <typename WT, int RB = RT / kWaves, typename CtxF, typename LoadF, typename MixF>
+__device__ inline void stage_segment4(const ActTile<WT> &A, int K, int nrows, CtxF ctx, LoadF load, MixF mix)
+{
+    // 64 lanes x 4 inputs per step: pick the unrolling that covers K without spare loads
+    if (K <= 512) stage_segment4_impl<WT, 2, RB>(A, K, nrows, ctx, load, mix);
+    else if (K <= 768) stage_segment4_impl<WT, 3, RB>(A, K, nrows, ctx, load, mix);
+    else stage_segment4_impl<WT, KSEG / 256, RB>(A, K, nrows, ctx, load, mix);
 }
 
 // accumulators of one wavefront for one 16x16 tile
