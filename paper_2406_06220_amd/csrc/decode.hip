@@ -492,11 +492,12 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         [&](const Seg &sg) {
                             const int k0 = sg.k0;
                             const float *src = sg.part == 1 ? h_cur : x_prev;
-                            stage_segment<WT>(
-                                A, sg.K, nrows,
+                            const int K = sg.K;
+                            stage_segment4<WT>(
+                                A, K, nrows,
                                 [&](int i) { return src + (size_t)(b0 + uni(plist[ti * RT + i])) * Hp + k0; },
-                                [](const float *row, int k) { return ld_co2(row + k); },
-                                [](const float *, int, float2 v) { return v; });
+                                [K](const float *row, int k) { return ld_co4(row, K, k); },
+                                [](const float *, int, float4 v) { return v; });
                         },
                         [&](int ct, int j) -> long long {
                             const int unit = (tile0 + ct) * 4 + (j >> 2);
@@ -597,11 +598,12 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                     S, A, in, tile0, n_ct, sec_b ? nullptr : p.b_pred, sec_b ? p.b_lstm[0] : p.b_pred,
                     [&](const Seg &sg) {
                         const int k0 = sg.k0;
-                        stage_segment<WT>(
-                            A, sg.K, nrows,
+                        const int K = sg.K;
+                        stage_segment4<WT>(
+                            A, K, nrows,
                             [&](int i) { return src + (size_t)(b0 + uni(S.act_list[ti * RT + i])) * Hp + k0; },
-                            [](const float *row, int k) { return ld_co2(row + k); },
-                            [](const float *, int, float2 v) { return v; });
+                            [K](const float *row, int k) { return ld_co4(row, K, k); },
+                            [](const float *, int, float4 v) { return v; });
                     },
                     [&](int ct, int j) -> long long {
                         if (sec_b) {   // a column tile = 4 hidden units x 4 gates
@@ -748,11 +750,12 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                         return make_float2(c.valid ? x.x : 0.0f, c.valid ? x.y : 0.0f);
                                     });
                             } else if (lstm) {
-                                stage_segment<WT>(
-                                    A, sg.K, nrows,
+                                const int K = sg.K;
+                                stage_segment4<WT>(
+                                    A, K, nrows,
                                     [&](int i) { return src_h + (size_t)(b0 + uni(jl[ti * RT + i])) * Hp + k0; },
-                                    [](const float *row, int k) { return ld_co2(row + k); },
-                                    [](const float *, int, float2 v) { return v; });
+                                    [K](const float *row, int k) { return ld_co4(row, K, k); },
+                                    [](const float *, int, float4 v) { return v; });
                             } else {
                                 stage_segment<WT>(
                                     A, sg.K, nrows,
@@ -827,9 +830,6 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                         if (!p.pred_tab) {
                             // the predictor output was projected by this iteration's phase Q (or, on
                             // the fly, by the phase before this pass): coherent loads
-                            // (a coherent load is 8 bytes at most: two of them, next to each other,
-                            // per lane and step -- that pair runs at the rate of a 16-byte load, while
-                            // 8-byte loads of consecutive lanes run at half of it)
                             stage_segment4<WT>(
                                 A, sg.K, nrows,
                                 [&](int i) {
@@ -837,11 +837,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
                                     c.pred = p.pred_proj + (size_t)(b0 + c.g) * H + k0;
                                     return c;
                                 },
-                                [](const JointRow &c, int k) {
+                                [K = sg.K](const JointRow &c, int k) {
                                     EncPred4 v;
-                                    if constexpr (ONTHEFLY) v.e = ld_co4(c.enc + k);   // written a phase ago
+                                    if constexpr (ONTHEFLY) v.e = ld_co4(c.enc, K, k);   // written a phase ago
                                     else v.e = *reinterpret_cast<const float4 *>(c.enc + k);
-                                    v.p = ld_co4(c.pred + k);
+                                    v.p = ld_co4(c.pred, K, k);
                                     return v;
                                 },
                                 [](const JointRow &c, int, EncPred4 v) {

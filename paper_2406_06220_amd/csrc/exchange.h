@@ -95,10 +95,20 @@ __device__ inline float2 ld_co2(const float *p)   // p 8-byte aligned
         __hip_atomic_load((const TDT_GLOBAL unsigned long long *)p, __ATOMIC_RELAXED, TDT_AGENT);
     return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
 }
-__device__ inline float4 ld_co4(const float *p)   // p 16-byte aligned: two coherent 8-byte loads
+// Four floats of a row that other workgroups wrote in an earlier phase, with one 16-byte load
+// of agent scope.  An atomic load is 8 bytes at most, and the compute unit takes in agent-scope
+// 8-byte loads at half the rate of 16-byte ones (27 against 55 bytes a clock, measured); a raw
+// buffer load carries the same scope bit (sc1: what an agent-scope relaxed atomic load compiles
+// to) on a 16-byte access.  The four floats need not arrive as one unit: a row is only read
+// after the group barrier that follows its last store.  `row` must be the same in every lane
+// (the buffer descriptor lives in scalar registers); offsets at or beyond `n` floats read zeros.
+__device__ inline float4 ld_co4(const float *row, int n, int k)
 {
-    const float2 lo = ld_co2(p), hi = ld_co2(p + 2);
-    return make_float4(lo.x, lo.y, hi.x, hi.y);
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(row), 0, n * (int)sizeof(float), 0x00020000);
+    const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rs, k * (int)sizeof(float), 0, 16 /* sc1 */);
+    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
 }
 __device__ inline unsigned long long ld_co64(const unsigned long long *p)
 {
