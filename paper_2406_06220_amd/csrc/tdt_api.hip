@@ -273,22 +273,26 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         // each at most four column tiles of the predictor-side products (two weight batches per
         // wavefront); `fit` is the cluster count at which that holds.  Small batches: two
         // clusters.  An LSTM predictor: `fit`; from about 14 hypotheses per cluster of eight on,
-        // where the row tiles are full either way, eight.  A stateless predictor streams no
-        // matrices per step and likes about ten hypotheses per cluster.
+        // where the row tiles are full either way, eight.  A stateless predictor: see below.
         const bool lstm = weights->pred_kind == TDT_PRED_LSTM;
         const int nt_a = (weights->h_joint + 15) / 16, nt_b = lstm ? (weights->h_pred + 3) / 4 : 0;
         const int q4 = (nt_a + 3) / 4 + (nt_b + 3) / 4;
         int fit = (2 * max_grid + q4) / (2 * q4);   // max_grid / q4, rounded
         if (fit < 1) fit = 1;
-        if (B < 16) {
+        if (B < 16 && lstm) {
             n_clusters = 2;   // also for a single hypothesis: half the workgroups synchronise faster
         } else if (lstm) {
             n_clusters = fit;
             if (fit < 8 && B >= 14 * 8) n_clusters = 8;
         } else {
-            n_clusters = B / 10;
+            // no predictor-side phase, no matrix but the output layer's: small groups.  Two
+            // hypotheses a group up to 28 groups (nine workgroups a group: still one work item of
+            // a joint pass each), from about 140 hypotheses on five a group, at most 64 groups
+            // (measured on the stateless benchmark model, B = 16 ... 512)
+            n_clusters = B / 2;
+            if (n_clusters > 28) n_clusters = B / 5 > 28 ? B / 5 : 28;
+            if (n_clusters > 64) n_clusters = 64;
             if (n_clusters < 2) n_clusters = 2;
-            if (n_clusters > fit) n_clusters = fit;
         }
         if (n_clusters > B && B > 1) n_clusters = B;
         if (n_clusters < min_clusters) n_clusters = min_clusters;
