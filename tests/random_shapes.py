@@ -2,7 +2,8 @@
 
 Every width is a multiple of 8 (the library's requirement); the draws cover both dtypes and
 predictors, one to four LSTM layers, with and without durations, lengths from 0, and the option
-space (window, groups, loop order, projections ahead of the loops or on the fly)."""
+space (window, groups, loop order, projections ahead of the loops or on the fly, the streaming
+joint pass, big blanks)."""
 from __future__ import annotations
 
 import numpy as np
@@ -38,4 +39,13 @@ def draw(seed: int, hi: int = 320, v_hi: int = 400, b_hi: int = 70, t_hi: int = 
     n_chunks = int(rng.integers(2, 6))
     # (drawn last, so that the draws above are what they were before this option existed)
     opts["projections"] = int(opts["algorithm"] == 0 and rng.random() < 0.35)
+    # later options, drawn after everything above for the same reason: the streaming joint pass
+    # where it can run, and the extra outputs read as big blanks of the label head
+    if (rng.random() < 0.7 and cfg.dtype == "bf16" and opts["algorithm"] == 0 and not opts["projections"]
+            and opts["n_clusters"] in (0,) + tuple(range(4, 9))):
+        opts["joint_kernel"] = 2
+    if rng.random() < 0.5 and cfg.durations:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, multi_blank=True,
+                                  durations=tuple(sorted(set(max(1, d) + 1 for d in cfg.durations))))
     return cfg, opts, n_chunks

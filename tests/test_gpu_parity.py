@@ -381,7 +381,7 @@ def test_projections_on_the_fly_edges_and_paper_sizes(oracle_lib, gpu):
         check(oracle_lib, gpu, synth.CONFIGS[name], projections=1)
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(28))
 def test_random_shapes(oracle_lib, gpu, seed):
     """Seeded random widths, depths, batch sizes, lengths and options: whole utterances, and the
     same utterances in chunks where the draw is label-looping."""
@@ -391,7 +391,8 @@ def test_random_shapes(oracle_lib, gpu, seed):
     check(oracle_lib, gpu, cfg, max_replayed_frac=0.2, **opts)
     if opts["algorithm"] == 0 and cfg.T >= 2:
         check_chunks(oracle_lib, gpu, cfg, "random", n_chunks, max_replayed_frac=0.2,
-                     window=opts["window"], n_clusters=opts["n_clusters"])
+                     window=opts["window"], n_clusters=opts["n_clusters"],
+                     **({"joint_kernel": opts["joint_kernel"]} if "joint_kernel" in opts else {}))
 
 
 def test_config1_tiny_rnnt(oracle_lib, gpu):
