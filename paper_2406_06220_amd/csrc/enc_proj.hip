@@ -282,12 +282,91 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void enc_proj_bf16_kernel(LinearPr
     gemm_tile_bf16(q, blockIdx.x);
 }
 
+// ---------------------------------------------------------------------------
+// fragment-major copies of the streamed matrices
+// ---------------------------------------------------------------------------
+struct PackJob {
+    const uint16_t *src;
+    uint4 *dst;
+    int N, K, gate_h;   // gate_h > 0: LSTM gate matrix of gate_h hidden units
+    int steps;
+    long long first, pieces;   // 16-byte pieces: its first in the batch, how many
+};
+constexpr int kMaxPackJobs = 3 + 2 * TDT_MAX_LSTM_LAYERS;
+struct PackBatch {
+    PackJob j[kMaxPackJobs];
+    int n;
+    long long pieces;
+};
+
+// block `blk` of `nblk` blocks of 256 threads copies its share of the pieces
+__device__ inline void pack_pieces(const PackBatch &b, unsigned blk, unsigned nblk)
+{
+    for (long long piece = (long long)blk * 256 + threadIdx.x; piece < b.pieces; piece += (long long)nblk * 256) {
+        int ji = 0;
+        while (ji + 1 < b.n && piece >= b.j[ji + 1].first) ++ji;
+        const PackJob &q = b.j[ji];
+        const long long local = piece - q.first;
+        const int lane = (int)(local & 63);
+        const long long frag = local >> 6;
+        const int step = (int)(frag % q.steps), tile = (int)(frag / q.steps);
+        const int j = lane & 15, k = step * 32 + (lane >> 4) * 8;
+        long long row;
+        if (q.gate_h > 0) {
+            const int unit = tile * 4 + (j >> 2);
+            row = unit < q.gate_h ? (long long)(j & 3) * q.gate_h + unit : -1;
+        } else {
+            row = tile * 16 + j < q.N ? tile * 16 + j : -1;
+        }
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row >= 0 && k < q.K) v = *reinterpret_cast<const uint4 *>(q.src + row * q.K + k);   // K % 8 == 0
+        q.dst[local] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void pack_weights_kernel(PackBatch b) { pack_pieces(b, blockIdx.x, gridDim.x); }
+
+PackBatch pack_batch(const tdt_weights_t *w, const PackedLayout &pl, bool on_the_fly, void *packed)
+{
+    PackBatch b{};
+    if (w->dtype != 1 || pl.total == 0) return b;
+    const bool lstm = w->pred_kind == TDT_PRED_LSTM;
+    auto add = [&](const void *src, const PackedMatrix &m, int N, int K, int gate_h) {
+        PackJob &q = b.j[b.n++];
+        q.src = static_cast<const uint16_t *>(src);
+        q.dst = reinterpret_cast<uint4 *>(static_cast<char *>(packed) + m.offset);
+        q.N = N;
+        q.K = K;
+        q.gate_h = gate_h;
+        q.steps = m.steps;
+        q.first = b.pieces;
+        q.pieces = (long long)m.tiles * m.steps * 64;
+        b.pieces += q.pieces;
+    };
+    // what a call does not multiply by stays unpacked: the encoder projection and, with a
+    // stateless predictor, its projection are products of the kernel only when it projects on the fly
+    if (on_the_fly) add(w->w_enc, pl.w_enc, w->h_joint, w->d_enc, 0);
+    if (on_the_fly || lstm) add(w->w_pred, pl.w_pred, w->h_joint, w->h_pred, 0);
+    add(w->w_out, pl.w_out, w->vocab + 1 + w->n_dur, w->h_joint, 0);
+    for (int l = 0; lstm && l < w->pred_layers; ++l) {
+        if (l > 0) add(w->w_ih[l], pl.w_ih[l], 4 * w->h_pred, w->h_pred, w->h_pred);
+        add(w->w_hh[l], pl.w_hh[l], 4 * w->h_pred, w->h_pred, w->h_pred);
+    }
+    return b;
+}
+unsigned pack_blocks_for(const PackBatch &b)
+{
+    const long long blocks = (b.pieces + 255) / 256;
+    return (unsigned)(blocks < 1024 ? blocks : 1024);
+}
+
 // Everything a decode call needs before its decode kernel, in one launch: the encoder
 // projection, the per-label tables of the predictor side (a product with blocks == 0 is
 // absent), and the clearing of the workspace's zero region and of the statistics.  The tasks
 // are independent; a workgroup takes its task from its index.  Every product's workgroup count
 // is a multiple of the number of dies, so each keeps its die-aware order of tiles.
-__global__ __launch_bounds__(GEMM_THREADS, 2) void prepare_bf16_kernel(LinearBatch batch, uint4 *zero, size_t n16,
+__global__ __launch_bounds__(GEMM_THREADS, 2) void prepare_bf16_kernel(LinearBatch batch, PackBatch pack,
+                                                                   unsigned pack_blocks, uint4 *zero, size_t n16,
                                                                    long long *out_stats)
 {
     unsigned b = blockIdx.x, used = 0;
@@ -300,6 +379,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void prepare_bf16_kernel(LinearBat
         b -= batch.q[i].blocks;
         used += batch.q[i].blocks;
     }
+    if (b < pack_blocks) {   // the fragment-major copies of the matrices the decode kernel streams
+        pack_pieces(pack, b, pack_blocks);
+        return;
+    }
+    b -= pack_blocks;
+    used += pack_blocks;
     const unsigned zb = b, nzb = gridDim.x - used;
     for (size_t i = (size_t)zb * GEMM_THREADS + threadIdx.x; i < n16; i += (size_t)nzb * GEMM_THREADS)
         zero[i] = make_uint4(0, 0, 0, 0);
@@ -386,8 +471,9 @@ static LinearProblem linear_problem(const void *a, int64_t rows, int K, const vo
 }
 
 hipError_t launch_prepare_bf16(const void *enc, const int32_t *enc_len, int B, int T, const tdt_weights_t *w,
-                               float *enc_proj, float *emb_gates, float *pred_tab, void *zero_begin,
-                               size_t zero_bytes, long long *out_stats, hipStream_t stream)
+                               float *enc_proj, float *emb_gates, float *pred_tab, const PackedLayout &pl,
+                               bool on_the_fly, void *packed, void *zero_begin, size_t zero_bytes,
+                               long long *out_stats, hipStream_t stream)
 {
     LinearBatch batch{};
     int n = 0;
@@ -414,8 +500,10 @@ hipError_t launch_prepare_bf16(const void *enc, const int32_t *enc_len, int B, i
     size_t zb = (n16 + GEMM_THREADS - 1) / GEMM_THREADS;
     if (zb > 256) zb = 256;
     if (zb < 1) zb = 1;
-    hipLaunchKernelGGL(prepare_bf16_kernel, dim3(blocks + (unsigned)zb), dim3(GEMM_THREADS), 0, stream, batch,
-                       static_cast<uint4 *>(zero_begin), n16, out_stats);
+    const PackBatch pack = pack_batch(w, pl, on_the_fly, packed);
+    const unsigned pb = pack.pieces > 0 ? pack_blocks_for(pack) : 0;
+    hipLaunchKernelGGL(prepare_bf16_kernel, dim3(blocks + pb + (unsigned)zb), dim3(GEMM_THREADS), 0, stream, batch,
+                       pack, pb, static_cast<uint4 *>(zero_begin), n16, out_stats);
     return hipGetLastError();
 }
 
@@ -461,49 +549,7 @@ hipError_t launch_encoder_projection(const void *enc, int64_t rows, const tdt_we
     return launch_linear(enc, rows, w->d_enc, w->w_enc, w->d_enc, w->h_joint, w->b_enc, w->dtype, 0, out, stream);
 }
 
-// ---------------------------------------------------------------------------
-// fragment-major copies of the streamed matrices
-// ---------------------------------------------------------------------------
 namespace {
-struct PackJob {
-    const uint16_t *src;
-    uint4 *dst;
-    int N, K, gate_h;   // gate_h > 0: LSTM gate matrix of gate_h hidden units
-    int steps;
-    long long first, pieces;   // 16-byte pieces: its first in the batch, how many
-};
-constexpr int kMaxPackJobs = 3 + 2 * TDT_MAX_LSTM_LAYERS;
-struct PackBatch {
-    PackJob j[kMaxPackJobs];
-    int n;
-    long long pieces;
-};
-
-__global__ __launch_bounds__(256) void pack_weights_kernel(PackBatch b)
-{
-    for (long long piece = (long long)blockIdx.x * 256 + threadIdx.x; piece < b.pieces;
-         piece += (long long)gridDim.x * 256) {
-        int ji = 0;
-        while (ji + 1 < b.n && piece >= b.j[ji + 1].first) ++ji;
-        const PackJob &q = b.j[ji];
-        const long long local = piece - q.first;
-        const int lane = (int)(local & 63);
-        const long long frag = local >> 6;
-        const int step = (int)(frag % q.steps), tile = (int)(frag / q.steps);
-        const int j = lane & 15, k = step * 32 + (lane >> 4) * 8;
-        long long row;
-        if (q.gate_h > 0) {
-            const int unit = tile * 4 + (j >> 2);
-            row = unit < q.gate_h ? (long long)(j & 3) * q.gate_h + unit : -1;
-        } else {
-            row = tile * 16 + j < q.N ? tile * 16 + j : -1;
-        }
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (row >= 0 && k < q.K) v = *reinterpret_cast<const uint4 *>(q.src + row * q.K + k);   // K % 8 == 0
-        q.dst[local] = v;
-    }
-}
-
 PackedMatrix place(size_t &off, int tiles, int K)
 {
     PackedMatrix m;
@@ -533,35 +579,14 @@ PackedLayout packed_layout(const tdt_weights_t *w)
     return pl;
 }
 
+
+// the copies in a launch of their own (calls that reuse the projections of an earlier call)
 hipError_t launch_pack_weights(const tdt_weights_t *w, const PackedLayout &pl, bool on_the_fly, void *packed,
                                hipStream_t stream)
 {
-    if (w->dtype != 1 || pl.total == 0) return hipSuccess;
-    PackBatch b{};
-    const bool lstm = w->pred_kind == TDT_PRED_LSTM;
-    auto add = [&](const void *src, const PackedMatrix &m, int N, int K, int gate_h) {
-        PackJob &q = b.j[b.n++];
-        q.src = static_cast<const uint16_t *>(src);
-        q.dst = reinterpret_cast<uint4 *>(static_cast<char *>(packed) + m.offset);
-        q.N = N;
-        q.K = K;
-        q.gate_h = gate_h;
-        q.steps = m.steps;
-        q.first = b.pieces;
-        q.pieces = (long long)m.tiles * m.steps * 64;
-        b.pieces += q.pieces;
-    };
-    // what a call does not multiply by stays unpacked: the encoder projection and, with a
-    // stateless predictor, its projection are products of the kernel only when it projects on the fly
-    if (on_the_fly) add(w->w_enc, pl.w_enc, w->h_joint, w->d_enc, 0);
-    if (on_the_fly || lstm) add(w->w_pred, pl.w_pred, w->h_joint, w->h_pred, 0);
-    add(w->w_out, pl.w_out, w->vocab + 1 + w->n_dur, w->h_joint, 0);
-    for (int l = 0; lstm && l < w->pred_layers; ++l) {
-        if (l > 0) add(w->w_ih[l], pl.w_ih[l], 4 * w->h_pred, w->h_pred, w->h_pred);
-        add(w->w_hh[l], pl.w_hh[l], 4 * w->h_pred, w->h_pred, w->h_pred);
-    }
-    const long long blocks = (b.pieces + 255) / 256;
-    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream, b);
+    const PackBatch b = pack_batch(w, pl, on_the_fly, packed);
+    if (b.pieces == 0) return hipSuccess;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3(pack_blocks_for(b)), dim3(256), 0, stream, b);
     return hipGetLastError();
 }
 

@@ -324,17 +324,20 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     float *pred_tab = weights->pred_kind == TDT_PRED_STATELESS && !on_the_fly
                           ? reinterpret_cast<float *>(ws + L.pred_tab) : nullptr;
     const PackedLayout PL = packed_layout(weights);
-    if (launch_pack_weights(weights, PL, on_the_fly, ws + L.packed, s) != hipSuccess) return TDT_ERR_LAUNCH;
     if (!reuse_enc_proj && weights->dtype == 1) {
         // one launch: the projection, the predictor side's per-label tables, the clearing
         // (projections on the fly: no rows for the projection here)
-        if (launch_prepare_bf16(enc, enc_len, on_the_fly ? 0 : B, T, weights, enc_proj, emb_gates, pred_tab,
-                                ws + L.zero_begin, L.zero_end - L.zero_begin,
+        if (launch_prepare_bf16(enc, enc_len, on_the_fly ? 0 : B, T, weights, enc_proj, emb_gates, pred_tab, PL,
+                                on_the_fly, ws + L.packed, ws + L.zero_begin, L.zero_end - L.zero_begin,
                                 reinterpret_cast<long long *>(out_stats), s) != hipSuccess)
             return TDT_ERR_LAUNCH;
-    } else if (launch_init(ws + L.zero_begin, L.zero_end - L.zero_begin,
-                           reinterpret_cast<long long *>(out_stats), s) != hipSuccess) {
-        return TDT_ERR_LAUNCH;
+    } else {
+        // (a call that reuses the projections of an earlier one still gets its own copies of the
+        // matrices: the caller vouches for the projections, not for what else the workspace holds)
+        if (launch_pack_weights(weights, PL, on_the_fly, ws + L.packed, s) != hipSuccess) return TDT_ERR_LAUNCH;
+        if (launch_init(ws + L.zero_begin, L.zero_end - L.zero_begin, reinterpret_cast<long long *>(out_stats),
+                        s) != hipSuccess)
+            return TDT_ERR_LAUNCH;
     }
     if (!reuse_enc_proj && weights->dtype != 1) {
         if (!on_the_fly && launch_encoder_projection_valid(enc, enc_len, B, T, weights, enc_proj, s) != hipSuccess)

@@ -110,9 +110,7 @@ hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int 
 // input product into emb_gates; a stateless predictor's projected output into pred_tab, which may
 // be null: then none) and the clearing of the zero region in one launch
 // (the projection covers frames t < enc_len[b] of each of the B utterances only; B == 0: none)
-hipError_t launch_prepare_bf16(const void *enc, const int32_t *enc_len, int B, int T, const tdt_weights_t *w,
-                               float *enc_proj, float *emb_gates, float *pred_tab, void *zero_begin,
-                               size_t zero_bytes, long long *out_stats, hipStream_t stream);
+
 // the encoder projection of the valid frames of B utterances (any dtype)
 hipError_t launch_encoder_projection_valid(const void *enc, const int32_t *enc_len, int B, int T,
                                            const tdt_weights_t *w, float *out, hipStream_t stream);
@@ -139,6 +137,11 @@ struct PackedLayout {
 PackedLayout packed_layout(const tdt_weights_t *w);
 hipError_t launch_pack_weights(const tdt_weights_t *w, const PackedLayout &pl, bool on_the_fly, void *packed,
                                hipStream_t stream);
+// (the same copies as part of the one launch that prepares a call)
+hipError_t launch_prepare_bf16(const void *enc, const int32_t *enc_len, int B, int T, const tdt_weights_t *w,
+                               float *enc_proj, float *emb_gates, float *pred_tab, const PackedLayout &pl,
+                               bool on_the_fly, void *packed, void *zero_begin, size_t zero_bytes,
+                               long long *out_stats, hipStream_t stream);
 hipError_t launch_init(void *zero_begin, size_t zero_bytes, long long *out_stats,
                        hipStream_t stream);
 // which compiled form of the decode kernel a call runs
