@@ -272,7 +272,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         // joint passes, so more clusters pay -- until a cluster has too few workgroups to give
         // each at most four column tiles of the predictor-side products (two weight batches per
         // wavefront); `fit` is the cluster count at which that holds.  Small batches: two
-        // clusters.  An LSTM predictor: `fit`; from about 14 hypotheses per cluster of eight on,
+        // to four clusters.  An LSTM predictor: `fit`; from about 14 hypotheses per cluster of eight on,
         // where the row tiles are full either way, eight.  A stateless predictor: see below.
         const bool lstm = weights->pred_kind == TDT_PRED_LSTM;
         const int nt_a = (weights->h_joint + 15) / 16, nt_b = lstm ? (weights->h_pred + 3) / 4 : 0;
@@ -280,7 +280,10 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
         int fit = (2 * max_grid + q4) / (2 * q4);   // max_grid / q4, rounded
         if (fit < 1) fit = 1;
         if (B < 16 && lstm) {
-            n_clusters = 2;   // also for a single hypothesis: half the workgroups synchronise faster
+            // two groups also for a single hypothesis (half the workgroups synchronise faster),
+            // four from four hypotheses on (3 to 8 % faster than two at B = 4 ... 12)
+            n_clusters = B < 4 ? 2 : (fit < 4 ? fit : 4);
+            if (n_clusters < 2) n_clusters = 2;
         } else if (lstm) {
             n_clusters = fit;
             if (fit < 8 && B >= 14 * 8) n_clusters = 8;
