@@ -213,7 +213,9 @@ enum tdt_stat {
 
 /*
  * Bytes of DEVICE workspace tdt_greedy_decode needs for this model and these
- * sizes (projected encoder frames [B][T][h_joint] in float32 dominate).
+ * sizes (projected encoder frames [B][T][h_joint] in float32 dominate; a bfloat16
+ * model also gets copies of its matrices there, re-ordered for the matrix cores,
+ * which every call writes anew: the caller's weights are only read).
  * Host-only computation.  Returns TDT_OK or TDT_ERR_NULL / _SHAPE / _UNSUPPORTED.
  */
 int tdt_workspace_bytes(const tdt_weights_t *weights, int B, int T, int u_cap, size_t *bytes);
