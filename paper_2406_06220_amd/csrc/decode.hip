@@ -319,7 +319,10 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         int Kw = FRAMELOOP ? 1 : p.window;   // Alg. 2 looks at one frame per step
         if (Kw <= 0) {
             Kw = auto_rows / n;
-            if (Kw < 3) Kw = 3;
+            if (Kw < 3) Kw = 3;   // (2, 4 and 5 measured no better on any benchmark model)
+            // the row tiles this window needs are paid for whole: as many frames as fill them
+            const int fill = (n * Kw + RT - 1) / RT * RT / n;
+            if (fill > Kw) Kw = fill;
         }
         if (Kw > kMaxWindow) Kw = kMaxWindow;
         if (Kw * n > rows_cap) Kw = rows_cap / n;
