@@ -157,29 +157,45 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
     // into the other -- at this kernel's few hundred bytes per flop-microsecond it is the number
     // of bytes in flight per compute unit that decides how much of the HBM rate it gets.
     uint4 ra[2][4], rb[2][4];
-    long long a_row[4];   // source row of the tile rows this thread loads
+    // What this thread loads of every K tile: 16-byte chunk kc of four rows of each operand.
+    // The loads themselves are unconditional -- a row or chunk that does not exist is read from
+    // one that does (row 0, the last chunk) and replaced by zeros on its way into LDS -- because
+    // a load inside a block that depends on the lane makes the compiler wait for every load
+    // still in flight before it issues the next, and the two K tiles in flight become one.
+    const int kc = tid & 7;
+    const uint16_t *a_src[4], *w_src[4];
+    bool a_ok[4], w_ok[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) a_row[j] = row_of[(tid + j * GEMM_THREADS) >> 3];
+    for (int j = 0; j < 4; ++j) {
+        const int row = (tid + j * GEMM_THREADS) >> 3;
+        const long long ar = row_of[row];
+        const int n = n0 + row;
+        a_ok[j] = ar >= 0;
+        w_ok[j] = n < N;
+        a_src[j] = A + (a_ok[j] ? ar : 0) * K;
+        w_src[j] = W + (long long)(w_ok[j] ? n : 0) * ldw;
+    }
     auto load_tiles = [&](int k0, uint4 (&xa)[4], uint4 (&xb)[4]) {
+        const int k = min(k0 + kc * 8, K - 8);   // K is a multiple of 8
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int c = tid + j * GEMM_THREADS;   // 0..1023
-            const int row = c >> 3, kc = c & 7;
-            const int k = k0 + kc * 8;
-            const int n = n0 + row;
-            xa[j] = (a_row[j] >= 0 && k < K) ? *reinterpret_cast<const uint4 *>(A + a_row[j] * K + k)
-                                             : make_uint4(0, 0, 0, 0);
-            xb[j] = (n < N && k < K) ? *reinterpret_cast<const uint4 *>(W + (long long)n * ldw + k)
-                                     : make_uint4(0, 0, 0, 0);
+            xa[j] = *reinterpret_cast<const uint4 *>(a_src[j] + k);
+            xb[j] = *reinterpret_cast<const uint4 *>(w_src[j] + k);
         }
     };
-    auto store_tiles = [&](int buf, const uint4 (&xa)[4], const uint4 (&xb)[4]) {
+    auto store_tiles = [&](int buf, int k0, const uint4 (&xa)[4], const uint4 (&xb)[4]) {
+        const bool k_ok = k0 + kc * 8 < K;
+        // (masks, not a choice between two values: a choice between the register set and a
+        // constant becomes a choice between two addresses, which puts the set into scratch memory)
+        auto keep = [](uint4 v, bool ok) {
+            const unsigned m = ok ? 0xffffffffu : 0u;
+            return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
+        };
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int c = tid + j * GEMM_THREADS;
-            const int row = c >> 3, kc = c & 7;
-            *reinterpret_cast<uint4 *>(As[buf] + lds_off(row, kc)) = xa[j];
-            *reinterpret_cast<uint4 *>(Bs[buf] + lds_off(row, kc)) = xb[j];
+            const int row = (tid + j * GEMM_THREADS) >> 3;
+            *reinterpret_cast<uint4 *>(As[buf] + lds_off(row, kc)) = keep(xa[j], a_ok[j] && k_ok);
+            *reinterpret_cast<uint4 *>(Bs[buf] + lds_off(row, kc)) = keep(xb[j], w_ok[j] && k_ok);
         }
     };
     auto products = [&](int buf) {
@@ -202,23 +218,68 @@ __device__ inline void gemm_tile_bf16(const LinearProblem &q, unsigned block)
         }
     };
 
+    // The same products with the requests for a later K tile dealt out between them, one after
+    // every two products (step s asks for the thread's s-th chunk of both operands), so that
+    // the compute unit's address path takes them one by one instead of eight in a row.
+    auto products_and_loads = [&](int buf, int k0, uint4 (&xa)[4], uint4 (&xb)[4]) __attribute__((always_inline)) {
+        static_assert(BK / 16 == 4, "one chunk of each operand per k step");
+        const int k = min(k0 + kc * 8, K - 8);
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            const int chunk = s * 2 + (lane >> 5);
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int ar = wm * 64 + i * 32 + (lane & 31);
+                const int br = wn * 64 + i * 32 + (lane & 31);
+                a[i] = *reinterpret_cast<const bf16x8 *>(As[buf] + lds_off(ar, chunk));
+                b[i] = *reinterpret_cast<const bf16x8 *>(Bs[buf] + lds_off(br, chunk));
+            }
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[1], acc[0][1], 0, 0, 0);
+            xa[s] = *reinterpret_cast<const uint4 *>(a_src[s] + k);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[0], acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], acc[1][1], 0, 0, 0);
+            xb[s] = *reinterpret_cast<const uint4 *>(w_src[s] + k);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // the step's four fragments from LDS
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // two products
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one request
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+    };
+
     const int nk = (K + BK - 1) / BK;
     load_tiles(0, ra[0], rb[0]);
     if (nk > 1) load_tiles(BK, ra[1], rb[1]);
-    store_tiles(0, ra[0], rb[0]);
+    store_tiles(0, 0, ra[0], rb[0]);
     __syncthreads();
-    // two K tiles per trip, so that the register sets are named at compile time; one workgroup
+    // Two K tiles per trip, so that the register sets are named at compile time; one workgroup
     // barrier per K tile (the buffer written after the products was last read before the
-    // previous barrier)
-    for (int kt = 0; kt < nk; kt += 2) {
+    // previous barrier).  The trips that have all their tiles run without a branch: behind a
+    // branch, even a uniform one, the compiler no longer knows how many loads are in flight and
+    // waits for all of them where the older set would do.  (The fence keeps the older set's way
+    // into LDS behind the products.)
+    int kt = 0;
+    for (; kt + 4 <= nk; kt += 2) {
+        products_and_loads(0, (kt + 2) * BK, ra[0], rb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        store_tiles(1, (kt + 1) * BK, ra[1], rb[1]);
+        __syncthreads();
+        products_and_loads(1, (kt + 3) * BK, ra[1], rb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        store_tiles(0, (kt + 2) * BK, ra[0], rb[0]);
+        __syncthreads();
+    }
+    for (; kt < nk; kt += 2) {   // the last one to three tiles
         if (kt + 2 < nk) load_tiles((kt + 2) * BK, ra[0], rb[0]);
         products(0);
-        if (kt + 1 < nk) store_tiles(1, ra[1], rb[1]);
+        if (kt + 1 < nk) store_tiles(1, (kt + 1) * BK, ra[1], rb[1]);
         __syncthreads();
         if (kt + 1 < nk) {
             if (kt + 3 < nk) load_tiles((kt + 3) * BK, ra[1], rb[1]);
             products(1);
-            if (kt + 2 < nk) store_tiles(0, ra[0], rb[0]);
+            if (kt + 2 < nk) store_tiles(0, (kt + 2) * BK, ra[0], rb[0]);
             __syncthreads();
         }
     }
