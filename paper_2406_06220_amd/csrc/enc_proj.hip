@@ -12,6 +12,9 @@
 // mapping wants: lane l supplies row (l % 32), k-slice (l / 32) * 8 .. + 7.
 #include "tdt_internal.h"
 
+#include <mutex>
+#include <type_traits>
+
 namespace tdt {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -51,16 +54,16 @@ struct LinearBatch {
 };
 
 // Which frames rows m0 .. m0 + ROWS - 1 of the packed sequence of valid frames are: row_of[i] =
-// b * T + t, or -1 beyond the last valid frame.  Called by all GEMM_THREADS threads of a workgroup;
+// b * T + t, or -1 beyond the last valid frame.  Called by all THREADS threads of a workgroup;
 // returns false (for all of them) if the tile holds no valid frame at all.  Every thread sums a
 // stretch of the utterances' lengths, the stretches' sums are scanned across the workgroup, and
 // each row finds its utterance by a search over the stretches and a walk through its stretch.
-template <int ROWS>
+template <int ROWS, int THREADS = GEMM_THREADS>
 __device__ inline bool valid_row_map(const int32_t *lens, int B, int T, long long m0, long long *row_of, int *scan,
                                      int *wsum)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int per = (B + GEMM_THREADS - 1) / GEMM_THREADS;
+    const int per = (B + THREADS - 1) / THREADS;
     const int b_lo = min(tid * per, B), b_hi = min(b_lo + per, B);
     int mine = 0;   // B * T < 2^31, so every sum of lengths fits an int
     for (int b = b_lo; b < b_hi; ++b) mine += min(max(lens[b], 0), T);
@@ -74,7 +77,7 @@ __device__ inline bool valid_row_map(const int32_t *lens, int B, int T, long lon
     __syncthreads();
     int base = 0, total = 0;
 #pragma unroll
-    for (int w = 0; w < GEMM_THREADS / 64; ++w) {
+    for (int w = 0; w < THREADS / 64; ++w) {
         if (w < wave) base += wsum[w];
         total += wsum[w];
     }
@@ -85,7 +88,7 @@ __device__ inline bool valid_row_map(const int32_t *lens, int B, int T, long lon
         const long long m = m0 + tid;
         long long src = -1;
         if (m < total) {
-            int lo = 0, hi = GEMM_THREADS - 1;   // the last stretch that starts at or before m
+            int lo = 0, hi = THREADS - 1;   // the last stretch that starts at or before m
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
                 if (scan[mid] <= m) lo = mid; else hi = mid - 1;
@@ -344,6 +347,199 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void enc_proj_bf16_kernel(LinearPr
 }
 
 // ---------------------------------------------------------------------------
+// The same product for large problems: 256 x 256 output tile, 8 wavefronts, each 128 x 64
+// ---------------------------------------------------------------------------
+// With 64 x 64 outputs a wavefront every MFMA needs one 16-byte fragment per lane from LDS, and
+// the LDS of a compute unit (128 bytes a clock) is busy four fifths of the K loop while the
+// matrix cores are busy half of it.  At 128 x 64 outputs a wavefront six fragments feed eight
+// MFMAs, and a 256 x 256 tile stores half as many operand bytes per product.  One workgroup of
+// 8 wavefronts per compute unit (two a SIMD), two LDS buffers of 64 KB, one register set that
+// is requested during one K tile and stored to LDS during the next.
+constexpr int GM = 256, GN = 256, BIG_THREADS = 512;
+constexpr int BIG_OUT_ROWS = 64;          // rows of the output tile in LDS at a time
+constexpr int BIG_CLD = GN + 4;           // floats per row of that part
+struct BigShared {
+    long long row_of[GM];
+    int scan[BIG_THREADS], wsum[BIG_THREADS / 64];
+};
+constexpr size_t kBigTileBytes = 2 * (size_t)(GM + GN) * BK * sizeof(uint16_t);
+static_assert((size_t)BIG_OUT_ROWS * BIG_CLD * sizeof(float) <= kBigTileBytes, "the output parts reuse the operand buffers");
+constexpr size_t kBigLdsBytes = kBigTileBytes + sizeof(BigShared);
+
+__global__ __launch_bounds__(BIG_THREADS, 1) void enc_proj_bf16_big_kernel(LinearProblem q)
+{
+    extern __shared__ __align__(16) unsigned char big_lds[];
+    const uint16_t *__restrict__ A = q.A;
+    const uint16_t *__restrict__ W = q.W;
+    const float *__restrict__ bias = q.bias;
+    float *__restrict__ C = q.C;
+    const long long M = q.M;
+    const int N = q.N, K = q.K, ldw = q.ldw;
+    uint16_t *const As = reinterpret_cast<uint16_t *>(big_lds);                     // [2][GM * BK]
+    uint16_t *const Bs = As + 2 * GM * BK;                                          // [2][GN * BK]
+    float *const Cs = reinterpret_cast<float *>(big_lds);
+    BigShared &sh = *reinterpret_cast<BigShared *>(big_lds + kBigTileBytes);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    // the die-aware order of tiles of the 128 x 128 kernel
+    const unsigned block = blockIdx.x;
+    const int nt_n = (N + GN - 1) / GN;
+    const long long jb = block / kXcds;
+    const long long mt = (jb / nt_n) * kXcds + block % kXcds;
+    const long long m0 = mt * GM;
+    const int n0 = (int)(jb % nt_n) * GN;
+    if (m0 >= M) return;   // uniform over the workgroup
+    if (q.lens) {
+        if (!valid_row_map<GM, BIG_THREADS>(q.lens, q.B, q.T, m0, sh.row_of, sh.scan, sh.wsum)) return;   // uniform
+    } else if (tid < GM) {
+        sh.row_of[tid] = m0 + tid < M ? m0 + tid : -1;
+    }
+    __syncthreads();
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    // this thread's part of every K tile: 16-byte chunk kc of four rows of each operand
+    // (unconditional loads, zeros by mask: see the 128 x 128 kernel)
+    const int kc = tid & 7;
+    const uint16_t *a_src[4], *w_src[4];
+    bool a_ok[4], w_ok[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = (tid + j * BIG_THREADS) >> 3;
+        const long long ar = sh.row_of[row];
+        const int n = n0 + row;
+        a_ok[j] = ar >= 0;
+        w_ok[j] = n < N;
+        a_src[j] = A + (a_ok[j] ? ar : 0) * K;
+        w_src[j] = W + (long long)(w_ok[j] ? n : 0) * ldw;
+    }
+    uint4 xa[4], xb[4];
+    auto keep = [](uint4 v, bool ok) {   // (a mask, not a choice: see the 128 x 128 kernel)
+        const unsigned m = ok ? 0xffffffffu : 0u;
+        return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
+    };
+    // chunk idx (0..3 of A, 4..7 of W) of the register set: its request, and its way into LDS
+    auto request = [&](int idx, int k) __attribute__((always_inline)) {
+        if (idx < 4) xa[idx] = *reinterpret_cast<const uint4 *>(a_src[idx] + k);
+        else xb[idx - 4] = *reinterpret_cast<const uint4 *>(w_src[idx - 4] + k);
+    };
+    auto to_lds = [&](int idx, int buf, bool k_ok) __attribute__((always_inline)) {
+        const int row = (tid + (idx & 3) * BIG_THREADS) >> 3;
+        if (idx < 4) *reinterpret_cast<uint4 *>(As + buf * (GM * BK) + lds_off(row, kc)) = keep(xa[idx], a_ok[idx] && k_ok);
+        else *reinterpret_cast<uint4 *>(Bs + buf * (GN * BK) + lds_off(row, kc)) = keep(xb[idx - 4], w_ok[idx - 4] && k_ok);
+    };
+    // The products of the K tile in buffer `buf`.  Between the products of its first two k steps
+    // the register set (K tile kt + 1, requested during the tile before) goes into the other
+    // buffer, between those of its last two the set is requested again for K tile kt + 2: one
+    // LDS store or one request after every two products, so that neither the stores nor the
+    // requests stand between two K tiles, where all wavefronts would do them at the same time
+    // with the matrix cores idle.
+    auto products = [&](int buf, auto stores, auto loads, int k_store, int k_load) __attribute__((always_inline)) {
+        constexpr bool STORES = decltype(stores)::value, LOADS = decltype(loads)::value;
+        const uint16_t *const Ab = As + buf * (GM * BK), *const Bb = Bs + buf * (GN * BK);
+        const bool k_ok = k_store + kc * 8 < K;
+        const int k = min(k_load + kc * 8, K - 8);
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            const int chunk = s * 2 + (lane >> 5);
+            bf16x8 a[4], b[2];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                a[i] = *reinterpret_cast<const bf16x8 *>(Ab + lds_off(wm * 128 + i * 32 + (lane & 31), chunk));
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                b[j] = *reinterpret_cast<const bf16x8 *>(Bb + lds_off(wn * 64 + j * 32 + (lane & 31), chunk));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[0], acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[1], acc[i][1], 0, 0, 0);
+                if (STORES && s < 2) to_lds(s * 4 + i, buf ^ 1, k_ok);
+                if (LOADS && s >= 2) request((s - 2) * 4 + i, k);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);   // the step's six fragments from LDS
+            if ((STORES && s < 2) || (LOADS && s >= 2)) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                  // two products
+                    if (s < 2) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);       // one LDS store
+                    else __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // or one request
+                }
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+            }
+        }
+    };
+
+    const int nk = (K + BK - 1) / BK;
+#pragma unroll
+    for (int idx = 0; idx < 8; ++idx) request(idx, min(kc * 8, K - 8));
+#pragma unroll
+    for (int idx = 0; idx < 8; ++idx) to_lds(idx, 0, kc * 8 < K);
+    if (nk > 1) {
+#pragma unroll
+        for (int idx = 0; idx < 8; ++idx) request(idx, min(BK + kc * 8, K - 8));
+    }
+    __syncthreads();
+    // one workgroup barrier per K tile: the buffer written during the products of tile kt was
+    // last read before the barrier that ended tile kt - 1.  The trips that store and request
+    // run without a branch.
+    const std::true_type yes{};
+    const std::false_type no{};
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) {
+        products(kt & 1, yes, yes, (kt + 1) * BK, (kt + 2) * BK);
+        __syncthreads();
+    }
+    if (kt + 1 < nk) {
+        products(kt & 1, yes, no, (kt + 1) * BK, 0);
+        __syncthreads();
+        ++kt;
+    }
+    products(kt & 1, no, no, 0, 0);
+    __syncthreads();   // the operand buffers are dead: the output tile passes through them
+
+    // accumulator register e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32.  The tile
+    // leaves in four parts of 64 rows, each as whole rows: a wavefront stores one 1024-byte row.
+    const int c4 = lane * 4;
+    const int n = n0 + c4;
+    float4 bn = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (bias && n < N) bn = *reinterpret_cast<const float4 *>(bias + n);   // N is a multiple of 8
+#pragma unroll
+    for (int part = 0; part < GM / BIG_OUT_ROWS; ++part) {
+        if (part > 0) __syncthreads();   // the part before has left LDS
+        if (wm == part / 2) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int r = i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                        Cs[r * BIG_CLD + wn * 64 + j * 32 + (lane & 31)] = acc[(part & 1) * 2 + i][j][e];
+                    }
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int it = 0; it < BIG_OUT_ROWS / (BIG_THREADS / 64); ++it) {
+            const int r = it * (BIG_THREADS / 64) + wave;
+            const long long dst = sh.row_of[part * BIG_OUT_ROWS + r];
+            float4 v = *reinterpret_cast<const float4 *>(Cs + r * BIG_CLD + c4);
+            v.x += bn.x;
+            v.y += bn.y;
+            v.z += bn.z;
+            v.w += bn.w;
+            if (dst >= 0 && n < N) *reinterpret_cast<float4 *>(C + dst * N + n) = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // fragment-major copies of the streamed matrices
 // ---------------------------------------------------------------------------
 struct PackJob {
@@ -531,6 +727,36 @@ static LinearProblem linear_problem(const void *a, int64_t rows, int K, const vo
     return q;
 }
 
+// Large products with a column count that 256-column tiles divide take the 256 x 256 kernel
+// (a launch of its own: it has its own workgroup size and LDS footprint).
+static bool takes_big_tiles(int64_t rows, int N, int group)
+{
+    return group == 0 && N % GN == 0 && rows >= 32768;
+}
+
+static hipError_t launch_big_tiles(LinearProblem q, hipStream_t stream)
+{
+    static std::mutex mu;
+    static bool ready[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!ready[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(enc_proj_bf16_big_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBigLdsBytes);
+            if (e != hipSuccess) return e;
+            ready[dev] = true;
+        }
+    }
+    const long long row_tiles = (q.M + GM - 1) / GM, rounds = (row_tiles + kXcds - 1) / kXcds;
+    q.blocks = (unsigned)(rounds * kXcds * ((q.N + GN - 1) / GN));
+    hipLaunchKernelGGL(enc_proj_bf16_big_kernel, dim3(q.blocks), dim3(BIG_THREADS), kBigLdsBytes, stream, q);
+    return hipGetLastError();
+}
+
 hipError_t launch_prepare_bf16(const void *enc, const int32_t *enc_len, int B, int T, const tdt_weights_t *w,
                                float *enc_proj, float *emb_gates, float *pred_tab, const PackedLayout &pl,
                                bool on_the_fly, void *packed, void *zero_begin, size_t zero_bytes,
@@ -543,6 +769,11 @@ hipError_t launch_prepare_bf16(const void *enc, const int32_t *enc_len, int B, i
     batch.q[n].lens = enc_len;
     batch.q[n].B = B;
     batch.q[n].T = T;
+    if (takes_big_tiles((int64_t)B * T, w->h_joint, 0)) {
+        const hipError_t e = launch_big_tiles(batch.q[n], stream);
+        if (e != hipSuccess) return e;
+        batch.q[n].blocks = 0;   // not part of the launch below
+    }
     ++n;
     if (w->pred_kind == TDT_PRED_LSTM) {   // stored [label][unit][gate]
         batch.q[n++] = linear_problem(w->emb, w->vocab + 1, w->emb_dim, w->w_ih[0], w->emb_dim, 4 * w->h_pred,
@@ -574,6 +805,7 @@ hipError_t launch_linear(const void *a, int64_t rows, int K, const void *w, int 
     if (rows <= 0) return hipSuccess;
     if (dtype == 1) {
         const LinearProblem q = linear_problem(a, rows, K, w, ldw, N, bias, group, out);
+        if (takes_big_tiles(rows, N, group)) return launch_big_tiles(q, stream);
         hipLaunchKernelGGL(enc_proj_bf16_kernel, dim3(q.blocks), dim3(GEMM_THREADS), 0, stream, q);
     } else {
         dim3 grid((unsigned)(((N + 63) / 64) * ((rows + 63) / 64)));
@@ -594,6 +826,7 @@ hipError_t launch_encoder_projection_valid(const void *enc, const int32_t *enc_l
         q.lens = enc_len;
         q.B = B;
         q.T = T;
+        if (takes_big_tiles(rows, w->h_joint, 0)) return launch_big_tiles(q, stream);
         hipLaunchKernelGGL(enc_proj_bf16_kernel, dim3(q.blocks), dim3(GEMM_THREADS), 0, stream, q);
     } else {
         dim3 grid((unsigned)(((w->h_joint + 63) / 64) * ((rows + 63) / 64)));

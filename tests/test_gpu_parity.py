@@ -62,6 +62,9 @@ def check(oracle, binding, cfg, w=None, enc=None, ln=None, u_cap=None, rows=None
 # ------------------------------------------------------------------ encoder projection
 @pytest.mark.parametrize("dtype,rows,d_enc,H", [
     ("bf16", 1000, 512, 640), ("bf16", 37, 64, 72), ("bf16", 257, 1024, 1024), ("bf16", 128, 8, 8),
+    # from 32768 rows on, a column count that 256 divides takes the kernel with 256 x 256 tiles:
+    # a ragged last row tile, a reduction that is no multiple of its K tile, one and two column tiles
+    ("bf16", 33000, 72, 256), ("bf16", 32769, 136, 512),
     ("fp32", 200, 64, 64), ("fp32", 77, 24, 40)])
 def test_encoder_projection(oracle_lib, gpu, dtype, rows, d_enc, H):
     import torch
@@ -86,6 +89,7 @@ def test_encoder_projection(oracle_lib, gpu, dtype, rows, d_enc, H):
 
 
 @pytest.mark.parametrize("dtype,B,T,d_enc,H", [("bf16", 9, 150, 136, 200), ("bf16", 300, 7, 32, 40),
+                                               ("bf16", 70, 600, 40, 256),   # 256 x 256 tiles
                                                ("fp32", 5, 90, 24, 72)])
 def test_encoder_projection_of_valid_frames(oracle_lib, gpu, dtype, B, T, d_enc, H):
     """tdt_encoder_projection_valid: every valid frame's row equals the oracle's, rows of padding
