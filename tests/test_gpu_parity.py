@@ -545,12 +545,19 @@ def test_side_stream_and_back_to_back_calls(oracle_lib, gpu):
         assert res["replayed"] <= 2, res
 
 
-def test_call_replayed_from_a_graph(oracle_lib, gpu):
+@pytest.mark.parametrize("which", ["cfg2", "projection_in_a_launch_of_its_own"])
+def test_call_replayed_from_a_graph(oracle_lib, gpu, which):
     """The whole call (clear, encoder projection, table, cooperative decode kernel) captured into
     a HIP graph: every replay, with eager calls and synchronisations in between, gives the eager
-    result bit for bit."""
+    result bit for bit.  The second model has 32768 frames and 256 joint units, so its encoder
+    projection is the kernel with 256 x 256 tiles, a third launch of the call."""
     import torch
-    cfg = synth.CONFIGS["cfg2_rnnt_lstm"]
+    if which == "cfg2":
+        cfg = synth.CONFIGS["cfg2_rnnt_lstm"]
+    else:
+        cfg = synth.small_config("g_graph_big_proj", dtype="bf16", pred_kind="lstm", d_enc=24, h_pred=32,
+                                 emb_dim=16, h_joint=256, vocab=60, B=64, T=512, len_lo=100, len_hi=512,
+                                 seed=97, default_blank_bias=1.5, max_symbols=4)
     w = synth.generate_model(cfg)
     enc, ln = synth.generate_inputs(cfg)
     u_cap = cfg.T * cfg.max_symbols
