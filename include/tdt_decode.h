@@ -129,7 +129,8 @@ typedef struct {
  *               decode kernel on its own).
  *   joint_tiles the automatic window is sized so that one joint pass gives every
  *               workgroup at most one work item of this many 16-column tiles of the
- *               output layer.  0 = automatic (4, more for many hypotheses per group).
+ *               output layer.  0 = automatic (4 in groups of fewer than five hypotheses,
+ *               else 8).
  *               Ignored when window > 0.
  *   algorithm   TDT_ALG_LABEL_LOOPING (0, default): Algorithm 3.  TDT_ALG_FRAME_LOOPING:
  *               the conventional batched order the paper compares against (Algorithm 2)

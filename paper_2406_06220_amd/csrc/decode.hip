@@ -290,9 +290,11 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
     };
     // Automatic window: as many rows as give every workgroup at most one joint work item of at
     // most `tiles_per_item` column tiles (then one round, all wavefronts busy).  Unless the
-    // caller fixes it, a work item takes 4 column tiles, more (up to 8, one round) where the group's
-    // hypotheses with the smallest window of 4 frames would otherwise make more items than
-    // there are workgroups.
+    // caller fixes it, a work item takes 8 column tiles, one a wavefront, in groups of five
+    // hypotheses or more (the longer windows save more joint passes than the longer items cost:
+    // measured 2 to 5 % at 6 to 13 hypotheses a group) and 4 in smaller groups (1 to 2 % the
+    // other way), more (up to 8) where the group's hypotheses with the smallest window of 4
+    // frames would otherwise make more items than there are workgroups.
     int auto_rows;
     {
         const int NT = (O + CT - 1) / CT;
@@ -300,7 +302,7 @@ __global__ __launch_bounds__(kThreads, 1) void decode_kernel(DecodeParams p)
         if (tiles_per_item <= 0) {
             const int row_tiles_min = (G * 4 + RT - 1) / RT;
             const int groups_fit = max(1, C / row_tiles_min);
-            tiles_per_item = min(8, max(4, (NT + groups_fit - 1) / groups_fit));
+            tiles_per_item = G >= 5 ? 8 : min(8, max(4, (NT + groups_fit - 1) / groups_fit));
         }
         const int groups = (NT + tiles_per_item - 1) / tiles_per_item;
         auto_rows = max(1, C / groups) * RT;

@@ -37,7 +37,7 @@ struct DecodeParams {
     int pred_kind, pred_layers, h_pred, emb_dim;
     int max_symbols, u_cap;
     int window;            // 0 = automatic
-    int joint_tiles;       // column tiles per joint work item the automatic window aims at (0 = 4)
+    int joint_tiles;       // column tiles per joint work item the automatic window aims at (0 = automatic: 4 to 8)
     int kseg_max;          // longest K segment staged at once (set by launch_decode)
     int lds_bytes;         // dynamic LDS of the launch, a multiple of 16 (set by launch_decode)
     int n_clusters, hyps_per_cluster;
