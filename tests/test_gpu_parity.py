@@ -120,6 +120,38 @@ def test_encoder_projection_of_valid_frames(oracle_lib, gpu, dtype, B, T, d_enc,
         assert (got[b, ln[b]:] == 7.0).all(), f"padding rows of utterance {b} were written"
 
 
+@pytest.mark.timeout(600)
+def test_encoder_projection_at_config5_size(oracle_lib, gpu):
+    """The launch the benchmark times for config 5 (282 804 valid frames of 256 x 1500, 1024 -> 1024:
+    the kernel with 256 x 256 tiles): sampled rows against the oracle one by one -- among them the
+    first and the last valid frame of every sampled utterance, where row tiles begin and end --
+    and sampled padding rows, which must be left as they were."""
+    import torch
+    cfg = synth.CFG5
+    w = synth.generate_model(cfg)
+    w["b_enc"] = np.random.default_rng(7).standard_normal(cfg.h_joint).astype(np.float32)
+    enc, ln = synth.generate_inputs(cfg)
+    parity.announce(f"tdt_encoder_projection_valid at config 5's size, {int(ln.sum())} valid frames")
+    model = gpu.DeviceModel(cfg, w)
+    enc_d = model.upload_enc(enc)
+    len_d = torch.from_numpy(ln).to(model.device)
+    out = torch.full((cfg.B, cfg.T, cfg.h_joint), 7.0, dtype=torch.float32, device=model.device)
+    gpu.tdt_encoder_projection_valid(enc_d.data_ptr(), len_d.data_ptr(), cfg.B, cfg.T, model.c, out.data_ptr(),
+                                     torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    om = oracle_lib.OracleModel(cfg, w)
+    rng = np.random.default_rng(8)
+    for b in list(range(0, cfg.B, 37)) + [cfg.B - 1]:
+        frames = {0, int(ln[b]) - 1} | set(int(t) for t in rng.integers(0, ln[b], size=24))
+        for t in sorted(frames):
+            got = out[b, t].cpu().numpy()
+            np.testing.assert_allclose(got, om.enc_proj_frame(enc[b, t]), atol=4e-4, rtol=1e-5,
+                                       err_msg=f"utterance {b} frame {t}")
+        if ln[b] < cfg.T:
+            pad = out[b, int(ln[b]):].cpu().numpy()
+            assert (pad == 7.0).all(), f"padding rows of utterance {b} were written"
+
+
 @pytest.mark.parametrize("name", ["bf16", "fp32"])
 def test_padding_frames_are_neither_read_nor_needed(oracle_lib, gpu, name):
     """Frames at or beyond an utterance's length are never read (Alg. 3 line 2 projects the
