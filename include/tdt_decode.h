@@ -13,7 +13,9 @@
  *     library allocates nothing, keeps no state between calls, reads inputs and
  *     weights, and writes only outputs, the workspace and -- in the chunk-by-chunk
  *     call -- the state buffer the caller passes;
- *   - every matrix is [out_features][in_features], row-major;
+ *   - every matrix is [out_features][in_features], row-major; enc, the matrices, embedding
+ *     tables and biases of the model and the output of the projection calls start at
+ *     16-byte boundaries (rows are read and written 16 bytes at a time);
  *   - dtype 0: enc, embeddings and weight matrices are float32;
  *     dtype 1: they are bfloat16 (raw 16-bit patterns); biases are float32 in
  *     both cases, and every accumulation and intermediate value is float32;
@@ -47,7 +49,8 @@ enum tdt_status {
     TDT_ERR_DURATIONS = -4,   /* n_dur / durations mismatch, entry outside [0, 2^20], or no positive entry */
     TDT_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or smaller than tdt_workspace_bytes */
     TDT_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch or a query */
-    TDT_ERR_TOO_LARGE = -7    /* tdt_greedy_decode_static: the sizes need more than TDT_STATIC_SCRATCH_BYTES */
+    TDT_ERR_TOO_LARGE = -7,   /* tdt_greedy_decode_static: the sizes need more than TDT_STATIC_SCRATCH_BYTES */
+    TDT_ERR_ALIGN = -8        /* enc, a matrix, an embedding table, a bias or a projection output is not 16-byte aligned */
 };
 
 enum tdt_pred_kind {

@@ -35,6 +35,7 @@ TDT_HYP_TRUNCATED = 1
 TDT_HYP_LEN_CLAMPED = 2
 TDT_HYP_ABORTED = 4
 TDT_ERR_TOO_LARGE = -7
+TDT_ERR_ALIGN = -8
 TDT_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ("tdt_workspace_bytes", "tdt_greedy_decode", "tdt_greedy_decode_static", "tdt_state_bytes",

@@ -125,14 +125,23 @@ static int check_model(const tdt_weights_t *w)
     return TDT_OK;
 }
 
+// the kernels read rows of these arrays 16 bytes at a time
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
 static int check_model_pointers(const tdt_weights_t *w, bool need_decoder)
 {
     if (!w->w_enc || !w->b_enc) return TDT_ERR_NULL;
+    if (!aligned16(w->w_enc) || !aligned16(w->b_enc)) return TDT_ERR_ALIGN;
     if (!need_decoder) return TDT_OK;
     if (!w->emb || !w->w_pred || !w->b_pred || !w->w_out || !w->b_out) return TDT_ERR_NULL;
+    if (!aligned16(w->emb) || !aligned16(w->w_pred) || !aligned16(w->b_pred) || !aligned16(w->w_out) ||
+        !aligned16(w->b_out))
+        return TDT_ERR_ALIGN;
     if (w->pred_kind == TDT_PRED_LSTM)
-        for (int l = 0; l < w->pred_layers; ++l)
+        for (int l = 0; l < w->pred_layers; ++l) {
             if (!w->w_ih[l] || !w->w_hh[l] || !w->b_lstm[l]) return TDT_ERR_NULL;
+            if (!aligned16(w->w_ih[l]) || !aligned16(w->w_hh[l]) || !aligned16(w->b_lstm[l])) return TDT_ERR_ALIGN;
+        }
     return TDT_OK;
 }
 
@@ -159,7 +168,8 @@ int tdt_encoder_projection(const void *enc, int64_t rows, const tdt_weights_t *w
     const int st = check_model(weights);
     if (st != TDT_OK) return st;
     if (!enc || !out) return TDT_ERR_NULL;
-    if (check_model_pointers(weights, false) != TDT_OK) return TDT_ERR_NULL;
+    if (!aligned16(enc) || !aligned16(out)) return TDT_ERR_ALIGN;
+    if (const int sp = check_model_pointers(weights, false); sp != TDT_OK) return sp;
     if (rows < 0 || rows > ((int64_t)1 << 31)) return TDT_ERR_SHAPE;
     if (launch_encoder_projection(enc, rows, weights, out, static_cast<hipStream_t>(stream)) != hipSuccess)
         return TDT_ERR_LAUNCH;
@@ -173,7 +183,8 @@ int tdt_encoder_projection_valid(const void *enc, const int32_t *enc_len, int B,
     const int st = check_model(weights);
     if (st != TDT_OK) return st;
     if (!enc || !enc_len || !out) return TDT_ERR_NULL;
-    if (check_model_pointers(weights, false) != TDT_OK) return TDT_ERR_NULL;
+    if (!aligned16(enc) || !aligned16(out)) return TDT_ERR_ALIGN;
+    if (const int sp = check_model_pointers(weights, false); sp != TDT_OK) return sp;
     if (B < 1 || T < 1 || (int64_t)B * T > ((int64_t)1 << 31)) return TDT_ERR_SHAPE;
     if (launch_encoder_projection_valid(enc, enc_len, B, T, weights, out, static_cast<hipStream_t>(stream)) !=
         hipSuccess)
@@ -204,6 +215,7 @@ static int decode_common(const void *enc, const int32_t *enc_len, int B, int T,
     if (st != TDT_OK) return st;
     if (!enc || !enc_len || !out_labels || !out_frames || !out_len || !out_score || !out_status)
         return TDT_ERR_NULL;
+    if (!aligned16(enc)) return TDT_ERR_ALIGN;
     st = check_model_pointers(weights, true);
     if (st != TDT_OK) return st;
     if (B < 1 || T < 1 || u_cap < 1 || max_symbols < 1) return TDT_ERR_SHAPE;
@@ -500,6 +512,7 @@ const char *tdt_status_string(int status)
     case TDT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case TDT_ERR_LAUNCH: return "HIP launch or query failed";
     case TDT_ERR_TOO_LARGE: return "sizes beyond the library's own scratch memory";
+    case TDT_ERR_ALIGN: return "an input array is not 16-byte aligned";
     default: return "unknown status";
     }
 }

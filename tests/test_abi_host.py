@@ -62,7 +62,7 @@ def _decode(lib, w, *, enc=4096, enc_len=4096, B=2, T=10, durations=None, S=3, u
 
 
 def test_status_strings(lib):
-    for code in range(0, -7, -1):
+    for code in range(0, -9, -1):
         s = binding.tdt_status_string(code)
         assert s and s != "unknown status"
     assert binding.tdt_status_string(-99) == "unknown status"
@@ -114,6 +114,15 @@ def test_rejects_bad_arguments_before_device_work(lib):
     assert _decode(lib, w2, durations=dur) == -1
     w2 = _weights(cfg); w2.w_hh[0] = None
     assert _decode(lib, w2, durations=dur) == -1
+    # arrays that do not start at a 16-byte boundary (rows are read 16 bytes at a time)
+    assert _decode(lib, w, enc=4096 + 8, durations=dur) == -8
+    for field in ("w_enc", "b_enc", "emb", "w_pred", "b_pred", "w_out", "b_out"):
+        w2 = _weights(cfg); setattr(w2, field, 4096 + 4)
+        assert _decode(lib, w2, durations=dur) == -8, field
+    w2 = _weights(cfg); w2.b_lstm[0] = 4096 + 2
+    assert _decode(lib, w2, durations=dur) == -8
+    assert lib.tdt_encoder_projection(4096, 10, C.byref(w), 4096 + 4, None) == -8
+    assert lib.tdt_encoder_projection_valid(4096 + 2, 4096, 2, 5, C.byref(w), 4096, None) == -8
     # sizes
     for kw in (dict(B=0), dict(T=0), dict(u_cap=0), dict(S=0)):
         assert _decode(lib, w, durations=dur, **kw) == -2
